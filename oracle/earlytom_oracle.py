@@ -1,0 +1,258 @@
+"""CPU oracle for EarlyTom's in-encoder token compression.  TEST INFRASTRUCTURE ONLY.
+
+A plain, slow, step-by-step numpy implementation of what the HIP library
+computes: a pre-LayerNorm ViT encoder (SigLIP layout) over the frames of a video
+clip, with the paper's early token compression applied once inside the encoder:
+
+  Sec. 3.2  frame similarity s_t = mean over spatial positions of the cosine
+            similarity of co-located tokens of frames t and t-1;
+  Eq. 1     a segment boundary is placed before frame t when the (smoothed)
+            similarity drops below the threshold (alpha = 1 here: no smoothing);
+  Sec. 3.2  frames of a segment are merged (here: the whole segment is averaged
+            per spatial position, the simplified form this build's task names;
+            Eq. 2-3 pairwise weighted merging is not part of this file);
+  Eq. 4     per frame, the top-k tokens by score are kept (score = squared L2
+            norm of the merged token; ties go to the lower position);
+  Eq. 7     kept tokens are gathered in their original order and the remaining
+            encoder blocks run on the shorter sequence.
+
+Everything is float64 unless `dtype` says otherwise; matmul/einsum are the only
+library primitives; nothing is blocked, fused or reordered.  Only tests,
+`__graft_entry__.smoke()` and `bench.py`'s cpu_baseline leg may import this
+file; the product path never does, and this file imports nothing of the product.
+
+Parity pins (tests/test_oracle_*.py): closed forms for the similarity, hand
+cases for the boundary scan, brute-force selection for the top-k, textbook
+special cases for LayerNorm / softmax / GELU, an independent per-token loop
+implementation of one encoder block, and the end-to-end invariants
+(compression disabled == plain encoder; identical frames == single frame).
+"""
+import math
+
+import numpy as np
+
+
+# --------------------------------------------------------------------------
+# Encoder pieces (SigLIP layout; the paper names the model only, Sec. 4.1)
+# --------------------------------------------------------------------------
+
+def patchify(frames, patch):
+    """[T,C,H,W] -> [T, L, C*P*P]; non-overlapping patches, trailing pixels dropped.
+
+    Token l = gy * grid_w + gx; the patch vector is flattened in (c, py, px) order.
+    """
+    T, C, H, W = frames.shape
+    gy, gx = H // patch, W // patch
+    f = frames[:, :, :gy * patch, :gx * patch]
+    f = f.reshape(T, C, gy, patch, gx, patch)
+    f = f.transpose(0, 2, 4, 1, 3, 5)                    # T, gy, gx, C, py, px
+    return f.reshape(T, gy * gx, C * patch * patch)
+
+
+def patch_embed(frames, w, patch, dtype=np.float64):
+    """x[t,l,:] = patch(t,l) @ patch_w.T + patch_b + pos_emb[l]."""
+    p = patchify(np.asarray(frames, dtype=dtype), patch)
+    x = p @ np.asarray(w["patch_w"], dtype=dtype).T
+    x = x + np.asarray(w["patch_b"], dtype=dtype) + np.asarray(w["pos_emb"], dtype=dtype)[None]
+    return x
+
+
+def layer_norm(x, g, b, eps):
+    """(x - mean) / sqrt(biased variance + eps) * g + b over the last axis."""
+    mu = x.mean(axis=-1, keepdims=True)
+    var = ((x - mu) ** 2).mean(axis=-1, keepdims=True)
+    return (x - mu) / np.sqrt(var + eps) * g + b
+
+
+def gelu_tanh(u):
+    """0.5 u (1 + tanh( sqrt(2/pi) (u + 0.044715 u^3) ))."""
+    return 0.5 * u * (1.0 + np.tanh(math.sqrt(2.0 / math.pi) * (u + 0.044715 * u ** 3)))
+
+
+def softmax_rows(s):
+    m = s.max(axis=-1, keepdims=True)
+    e = np.exp(s - m)
+    return e / e.sum(axis=-1, keepdims=True)
+
+
+def attention(xn, lw, n_heads):
+    """Bidirectional multi-head self-attention inside each frame.  xn: [F, n, D]."""
+    F, n, D = xn.shape
+    hd = D // n_heads
+    dt = xn.dtype
+    qkv = xn @ np.asarray(lw["wqkv"], dtype=dt).T + np.asarray(lw["bqkv"], dtype=dt)
+    q, k, v = qkv[..., :D], qkv[..., D:2 * D], qkv[..., 2 * D:]
+    q = q.reshape(F, n, n_heads, hd).transpose(0, 2, 1, 3)      # F, H, n, hd
+    k = k.reshape(F, n, n_heads, hd).transpose(0, 2, 1, 3)
+    v = v.reshape(F, n, n_heads, hd).transpose(0, 2, 1, 3)
+    s = (q @ k.transpose(0, 1, 3, 2)) / math.sqrt(hd)
+    p = softmax_rows(s)
+    o = (p @ v).transpose(0, 2, 1, 3).reshape(F, n, D)
+    return o @ np.asarray(lw["wo"], dtype=dt).T + np.asarray(lw["bo"], dtype=dt)
+
+
+def mlp(xn, lw):
+    dt = xn.dtype
+    h = gelu_tanh(xn @ np.asarray(lw["w1"], dtype=dt).T + np.asarray(lw["b1"], dtype=dt))
+    return h @ np.asarray(lw["w2"], dtype=dt).T + np.asarray(lw["b2"], dtype=dt)
+
+
+def encoder_block(x, lw, n_heads, eps):
+    """Pre-LN block: x += Attn(LN1(x)); x += MLP(LN2(x)).  x: [F, n, D]."""
+    dt = x.dtype
+    x = x + attention(layer_norm(x, np.asarray(lw["ln1_g"], dt), np.asarray(lw["ln1_b"], dt), eps),
+                      lw, n_heads)
+    x = x + mlp(layer_norm(x, np.asarray(lw["ln2_g"], dt), np.asarray(lw["ln2_b"], dt), eps), lw)
+    return x
+
+
+# --------------------------------------------------------------------------
+# Compression pieces
+# --------------------------------------------------------------------------
+
+COS_EPS = 1e-8
+
+
+def frame_similarity(x):
+    """Sec. 3.2.  x: [T, L, D] -> (c [T-1, L], s [T-1]).
+
+    c[t-1, l] = <x[t,l], x[t-1,l]> / max(|x[t,l]| |x[t-1,l]|, 1e-8); s = mean over l.
+    """
+    a, b = x[1:], x[:-1]
+    dot = (a * b).sum(axis=-1)
+    na = np.sqrt((a * a).sum(axis=-1))
+    nb = np.sqrt((b * b).sum(axis=-1))
+    c = dot / np.maximum(na * nb, COS_EPS)
+    return c, c.mean(axis=-1)
+
+
+def segment_starts(s, tau, T):
+    """Eq. 1 with alpha = 1: frame t opens a new segment iff s_t < tau (strict).
+
+    Returns seg_start [N+1] (int32): first input frame of each segment, last entry T.
+    """
+    starts = [0]
+    for t in range(1, T):
+        sim = float(s[t - 1])
+        if sim < tau or math.isnan(sim):
+            starts.append(t)
+    starts.append(T)
+    return np.asarray(starts, dtype=np.int32)
+
+
+def segment_mean(x, seg_start):
+    """x: [T, L, D] -> [N, L, D]: per spatial position, the mean over the segment's frames."""
+    N = len(seg_start) - 1
+    out = np.empty((N,) + x.shape[1:], dtype=x.dtype)
+    for n in range(N):
+        a, b = int(seg_start[n]), int(seg_start[n + 1])
+        acc = np.zeros(x.shape[1:], dtype=x.dtype)
+        for t in range(a, b):
+            acc = acc + x[t]
+        out[n] = acc / (b - a)
+    return out
+
+
+def token_score(xm):
+    """Score of a merged token = its squared L2 norm.  [N, L, D] -> [N, L]."""
+    return (xm * xm).sum(axis=-1)
+
+
+def keep_count(L, keep_ratio):
+    """k = clamp(floor(keep_ratio * L + 1e-4), 1, L)."""
+    k = int(math.floor(float(keep_ratio) * L + 1e-4))
+    return max(1, min(L, k))
+
+
+def topk_positions(z, k):
+    """Eq. 4 with a total order: rank by (score descending, position ascending), keep the
+    first k, return those positions in ascending order (Eq. 7's "initial order").
+
+    The ranking is decided on float32 scores (the precision the kernel ranks in);
+    NaN ranks below everything.
+    """
+    z32 = np.asarray(z, dtype=np.float32)
+    key = np.where(np.isnan(z32), -np.inf, z32.astype(np.float64))
+    pos = np.arange(len(key))
+    order = np.lexsort((pos, -key))          # primary: -key ascending, secondary: pos ascending
+    return np.sort(order[:k]).astype(np.int32)
+
+
+def compact(xm, kept):
+    """Eq. 7.  xm: [N, L, D], kept: [N, k] -> packed [N*k, D], frame-major."""
+    N, k = kept.shape
+    return np.concatenate([xm[n][kept[n]] for n in range(N)], axis=0)
+
+
+def merge_select(x, sim_threshold, keep_ratio, force_seg_start=None, force_kept=None):
+    """The whole compression stage on hidden states x [T, L, D].
+
+    Returns a dict: frame_sim [T-1], cos [T-1, L], seg_start [N+1], merged [N, L, D],
+    score [N, L], k, kept_idx [N, k], cu_tokens [N+1], tokens [N*k, D].
+    `force_*` replace the decisions (used to separate arithmetic error from rank flips).
+    """
+    T, L, D = x.shape
+    if T > 1:
+        c, s = frame_similarity(x)
+    else:
+        c, s = np.zeros((0, L), x.dtype), np.zeros((0,), x.dtype)
+    seg = segment_starts(s, sim_threshold, T) if force_seg_start is None \
+        else np.asarray(force_seg_start, dtype=np.int32)
+    xm = segment_mean(x, seg)
+    z = token_score(xm)
+    k = keep_count(L, keep_ratio)
+    N = xm.shape[0]
+    if force_kept is None:
+        kept = np.stack([topk_positions(z[n], k) for n in range(N)])
+    else:
+        kept = np.asarray(force_kept, dtype=np.int32).reshape(N, k)
+    cu = (np.arange(N + 1) * k).astype(np.int32)
+    return dict(frame_sim=s, cos=c, seg_start=seg, merged=xm, score=z, k=k,
+                kept_idx=kept, cu_tokens=cu, tokens=compact(xm, kept))
+
+
+# --------------------------------------------------------------------------
+# Whole path
+# --------------------------------------------------------------------------
+
+def encode_clip(shape, w, frames, merge_layer, sim_threshold, keep_ratio,
+                dtype=np.float64, force_seg_start=None, force_kept=None, x_at_merge=None):
+    """Encoder forward with the compression applied after `merge_layer` blocks.
+
+    merge_layer < 0 disables compression (plain encoder).  merge_layer == n_layers
+    compresses after the last block, before the final LayerNorm.
+    `x_at_merge` (optional [T, L, D]) replaces the hidden states the compression
+    stage sees and the blocks after it continue from; used for stage-wise parity.
+    Returns a dict with tokens [n_tokens, D], kept_idx [n_tokens], cu_tokens,
+    seg_start, frame_sim, hidden_at_merge, n_frames_out.
+    """
+    n_layers = len(w["layers"])
+    T = frames.shape[0]
+    L = shape.tokens_per_frame
+    x = patch_embed(frames, w, shape.patch, dtype)
+    info = None
+    for i in range(n_layers + 1):
+        if i == merge_layer:
+            if x_at_merge is not None:
+                x = np.asarray(x_at_merge, dtype=dtype)
+            info = merge_select(x, sim_threshold, keep_ratio, force_seg_start, force_kept)
+            info["hidden_at_merge"] = x
+            N, k = info["kept_idx"].shape
+            x = info["tokens"].reshape(N, k, -1)
+        if i < n_layers:
+            x = encoder_block(x, w["layers"][i], shape.n_heads, shape.ln_eps)
+    if shape.has_final_ln:
+        x = layer_norm(x, np.asarray(w["final_ln_g"], dtype), np.asarray(w["final_ln_b"], dtype),
+                       shape.ln_eps)
+    F, n, D = x.shape
+    out = dict(tokens=x.reshape(F * n, D), n_frames_out=F)
+    if info is None:
+        out.update(kept_idx=np.tile(np.arange(L, dtype=np.int32), T),
+                   cu_tokens=(np.arange(T + 1) * L).astype(np.int32),
+                   seg_start=np.arange(T + 1, dtype=np.int32),
+                   frame_sim=np.zeros((max(T - 1, 0),), dtype), hidden_at_merge=None)
+    else:
+        out.update(kept_idx=info["kept_idx"].reshape(-1), cu_tokens=info["cu_tokens"],
+                   seg_start=info["seg_start"], frame_sim=info["frame_sim"],
+                   hidden_at_merge=info["hidden_at_merge"], score=info["score"])
+    return out
