@@ -1,0 +1,191 @@
+/*
+ * earlytom.h — C boundary of the MI355X (gfx950) EarlyTom vision-encoder library.
+ *
+ * The library runs a pre-LayerNorm ViT encoder (SigLIP layout) over the frames of a
+ * video clip and applies the paper's early token compression once, inside the encoder:
+ * adjacent-frame similarity (Sec. 3.2) -> segment boundaries (Eq. 1, alpha = 1) ->
+ * per-position mean over each segment (Sec. 3.2, simplified whole-segment merge) ->
+ * per-frame top-k token selection (Eq. 4; score = squared L2 norm, ties to the lower
+ * position) -> gather in original order (Eq. 7) -> remaining blocks on the kept tokens.
+ *
+ * Conventions
+ *   - Pointers named *_dev are DEVICE memory owned by the caller; pointers without the
+ *     suffix are HOST memory.  The library never frees caller memory and returns nothing
+ *     the caller must free, except the opaque encoder (et_encoder_destroy).
+ *   - All device activations are bfloat16 (bit patterns, uint16_t), row-major; index and
+ *     offset data are int32.
+ *   - Every function returning int returns ET_OK (0) or a negative ET_ERR_* code; the
+ *     message of the last failure on the calling thread is available from et_last_error().
+ *     Arguments are validated before any device work is issued.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  All
+ *     work is enqueued on it.  One encoder must be used by one stream at a time.
+ *   - No exceptions cross this boundary.
+ */
+#ifndef EARLYTOM_H
+#define EARLYTOM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ET_OK 0
+#define ET_ERR_INVALID_ARG (-1) /* null pointer, size or parameter out of range          */
+#define ET_ERR_WORKSPACE (-2)   /* workspace_bytes smaller than the required size        */
+#define ET_ERR_HIP (-3)         /* a HIP runtime call or kernel launch failed            */
+#define ET_ERR_ALLOC (-4)       /* host or device allocation failed (create only)        */
+#define ET_ERR_UNSUPPORTED (-5) /* a shape the kernels are not instantiated for          */
+
+typedef struct et_encoder et_encoder; /* opaque; owns the packed device weights */
+
+/* Encoder shape.  Tokens per frame L = (image_h / patch) * (image_w / patch); pixels past the
+ * last whole patch are ignored.  head_dim = d_model / n_heads must be 16, 32, 64, 72, 80, 96
+ * or 128; d_model must be a multiple of 8. */
+typedef struct {
+  int32_t n_layers, d_model, n_heads, d_mlp, patch, image_h, image_w, channels;
+  float ln_eps;
+  int32_t has_final_ln;
+} et_config;
+
+/* HOST float32 weights, row-major, read only during et_encoder_create (converted once to
+ * bfloat16 with round-to-nearest-even; LayerNorm gains/biases and linear biases stay fp32).
+ * Linear layers are y = x * W^T + b with W stored out-features major. */
+typedef struct {
+  const float *patch_w; /* [D, C*P*P], patch vector flattened in (c, py, px) order        */
+  const float *patch_b; /* [D]                                                            */
+  const float *pos_emb; /* [L, D], token l = gy * (image_w / patch) + gx                  */
+  /* per-layer tables: n_layers host pointers each */
+  const float *const *ln1_g, *const *ln1_b; /* [D]                                        */
+  const float *const *wqkv, *const *bqkv;   /* [3D, D] rows q | k | v; head h = rows h*hd.. */
+  const float *const *wo, *const *bo;       /* [D, D], [D]                                */
+  const float *const *ln2_g, *const *ln2_b; /* [D]                                        */
+  const float *const *w1, *const *b1;       /* [Mh, D], [Mh]                              */
+  const float *const *w2, *const *b2;       /* [D, Mh], [D]                               */
+  const float *final_ln_g, *final_ln_b;     /* [D]; may be NULL iff !has_final_ln         */
+} et_weights;
+
+/* Outputs.  Every *_dev buffer is caller-allocated with the stated capacity (in elements). */
+typedef struct {
+  uint16_t *tokens_dev;   /* bf16, capacity T*L*D; written [n_tokens, D], frame-major      */
+  int32_t *kept_idx_dev;  /* capacity T*L; written [n_tokens]: spatial position l of each
+                             output token, ascending inside a frame                        */
+  int32_t *cu_tokens_dev; /* capacity T+1; written [n_frames_out+1]: token offset of each
+                             output frame                                                  */
+  int32_t *seg_start_dev; /* capacity T+1; written [n_frames_out+1]: first input frame of
+                             each segment, last entry = T                                  */
+  float *frame_sim_dev;   /* capacity max(T-1,1); written s_t for t = 1..T-1; may be NULL  */
+  int32_t n_frames_out;   /* HOST, valid on return: number of segments N                   */
+  int32_t n_tokens;       /* HOST, valid on return: N * k                                  */
+} et_output;
+
+/* ---- the hot path ------------------------------------------------------------------- */
+
+/* Pack `weights` for `config` onto the current HIP device.  max_frames bounds T of later
+ * calls.  On success *out receives the encoder.  Errors: INVALID_ARG, UNSUPPORTED, ALLOC, HIP. */
+int et_encoder_create(const et_config *config, const et_weights *weights, int32_t max_frames,
+                      et_encoder **out);
+void et_encoder_destroy(et_encoder *enc); /* NULL is allowed */
+
+/* Bytes of device workspace et_encode_clip needs for a clip of T frames (0 on bad arguments). */
+size_t et_workspace_bytes(const et_encoder *enc, int32_t T);
+
+/* Encode one clip.
+ *   frames_dev   float32 [T, C, image_h, image_w] (NCHW), device.
+ *   merge_layer  m: compression acts on the residual stream after m blocks have run,
+ *                0 <= m <= n_layers (m = n_layers: after the last block, before the final
+ *                LayerNorm).  m < 0 disables compression (plain encoder: N = T, k = L).
+ *   sim_threshold  tau of Eq. 1: frame t opens a new segment iff s_t < tau (NaN s_t also
+ *                opens one).  +INFINITY makes every frame its own segment.  NaN is rejected.
+ *   keep_ratio   in (0, 1]; k = et_keep_count(L, keep_ratio) tokens are kept per output frame.
+ * Synchronises `hip_stream` once in the middle (to learn N) and once before returning.
+ * Errors: INVALID_ARG (incl. T < 1 or T > max_frames), WORKSPACE, HIP. */
+int et_encode_clip(et_encoder *enc, const float *frames_dev, int32_t T, int32_t merge_layer,
+                   float sim_threshold, float keep_ratio, void *workspace_dev,
+                   size_t workspace_bytes, void *hip_stream, et_output *out);
+
+/* The compression stage alone on caller-supplied hidden states x_dev (bf16 [T, L, D],
+ * D a multiple of 8, T >= 1): similarity, boundary scan, segment mean, top-k, compaction.
+ * out->tokens_dev receives the packed merged tokens [N*k, D].  Needs
+ * et_merge_workspace_bytes(T, L, D) bytes of workspace.  Synchronises the stream once
+ * before returning. */
+int et_merge_select(const uint16_t *x_dev, int32_t T, int32_t L, int32_t D, float sim_threshold,
+                    float keep_ratio, void *workspace_dev, size_t workspace_bytes,
+                    void *hip_stream, et_output *out);
+size_t et_merge_workspace_bytes(int32_t T, int32_t L, int32_t D);
+
+/* k = clamp(floor(keep_ratio * L + 1e-4), 1, L); 0 on bad arguments.  (The paper floors
+ * window sizes in Eq. 6 but does not state the rounding for top-K; this rule is this
+ * library's reading.) */
+int32_t et_keep_count(int32_t L, float keep_ratio);
+
+const char *et_last_error(void); /* thread-local, never NULL */
+
+/* ---- per-kernel timing (optional) ----------------------------------------------------
+ * With profiling on, et_encode_clip brackets every kernel launch with HIP events on
+ * `hip_stream` and accumulates elapsed time and launch counts per kernel kind.  Off by
+ * default (events cost a little host time). */
+enum {
+  ET_K_IM2COL = 0, ET_K_GEMM_PATCH, ET_K_LAYERNORM, ET_K_GEMM_QKV, ET_K_ATTENTION,
+  ET_K_GEMM_OUT, ET_K_GEMM_FC1, ET_K_GEMM_FC2, ET_K_SIMILARITY, ET_K_SCAN, ET_K_MERGE,
+  ET_K_SELECT, ET_K_COMPACT, ET_K_MISC, ET_K_COUNT
+};
+int et_profile_enable(et_encoder *enc, int32_t on);
+/* Adds nothing; reads the accumulators: ms[ET_K_COUNT], launches[ET_K_COUNT]; then clears
+ * them if `reset` is non-zero. */
+int et_profile_read(et_encoder *enc, double *ms, int64_t *launches, int32_t reset);
+const char *et_kernel_name(int32_t kind);
+
+/* ---- single steps (the same kernels the hot path launches; for parity tests and
+ *      micro-benchmarks).  All asynchronous on `hip_stream` unless stated. ------------- */
+
+/* Sec. 3.2: cos_dev [T-1, L] float32 per-position cosine similarities of frames t and t-1,
+ * sim_dev [T-1] their mean over positions.  x_dev bf16 [T, L, D]. */
+int et_frame_similarity(const uint16_t *x_dev, int32_t T, int32_t L, int32_t D, float *cos_dev,
+                        float *sim_dev, void *hip_stream);
+
+/* Eq. 1 (alpha = 1): seg_start_dev [capacity T+1] and *n_seg_dev (one int32) from sim_dev [T-1]. */
+int et_segment_scan(const float *sim_dev, int32_t T, float sim_threshold, int32_t *seg_start_dev,
+                    int32_t *n_seg_dev, void *hip_stream);
+
+/* Segment mean and score: merged_dev bf16 [N, L, D] (capacity T*L*D), score_dev float32
+ * [N, L] (capacity T*L); N and the ranges are read from the device arrays. */
+int et_segment_mean(const uint16_t *x_dev, int32_t T, int32_t L, int32_t D,
+                    const int32_t *seg_start_dev, const int32_t *n_seg_dev, uint16_t *merged_dev,
+                    float *score_dev, void *hip_stream);
+
+/* Eq. 4: for each of n_rows rows of score_dev [n_rows, L] (float32, non-negative or NaN), the
+ * k positions that come first in the order (score descending, position ascending), written
+ * ascending to kept_idx_dev [n_rows, k]. */
+int et_topk_select(const float *score_dev, int32_t n_rows, int32_t L, int32_t k,
+                   int32_t *kept_idx_dev, void *hip_stream);
+
+/* Eq. 7: out_dev[(n*k + j), :] = merged_dev[n, kept_idx_dev[n*k + j], :], n < n_rows. */
+int et_compact_tokens(const uint16_t *merged_dev, const int32_t *kept_idx_dev, int32_t n_rows,
+                      int32_t L, int32_t D, int32_t k, uint16_t *out_dev, void *hip_stream);
+
+/* LayerNorm over rows: y = (x - mean) / sqrt(var + eps) * gamma + beta; x, y bf16 [rows, D]
+ * (may alias), gamma/beta float32 [D] on the device. */
+int et_layernorm(const uint16_t *x_dev, const float *gamma_dev, const float *beta_dev, float eps,
+                 int32_t rows, int32_t D, uint16_t *y_dev, void *hip_stream);
+
+/* C[M, N] = A[M, K] * W[N, K]^T + bias, bf16 in / fp32 accumulate / bf16 out, with an
+ * epilogue: 0 bias only, 1 bias + GELU-tanh, 2 bias + residual (res_dev bf16 [M, N], may
+ * alias c_dev).  bias_dev float32 [N].  Standalone form for tests: any M >= 1, N and K
+ * multiples of 8; allocates and frees padded copies of the operands itself and synchronises. */
+int et_gemm_bf16(const uint16_t *a_dev, const uint16_t *w_dev, const float *bias_dev,
+                 const uint16_t *res_dev, int32_t M, int32_t N, int32_t K, int32_t epilogue,
+                 uint16_t *c_dev, void *hip_stream);
+
+/* Per-frame multi-head attention on a fused projection buffer qkv_dev bf16 [rows, 3D]
+ * (q | k | v, head h at columns h*hd): out_dev bf16 [rows, D].  cu_tokens_dev [n_frames+1]
+ * gives each frame's row range; max_len >= the longest frame. */
+int et_attention(const uint16_t *qkv_dev, const int32_t *cu_tokens_dev, int32_t n_frames,
+                 int32_t max_len, int32_t n_heads, int32_t head_dim, uint16_t *out_dev,
+                 void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EARLYTOM_H */

@@ -1,0 +1,511 @@
+// Dense encoder kernels for gfx950: LayerNorm, patch extraction, the bf16 MFMA GEMM with fused
+// epilogues (bias | bias + GELU-tanh | bias + residual) and per-frame multi-head attention.
+//
+// MFMA shape used throughout: v_mfma_f32_32x32x16_bf16.  Per 64-lane wavefront, with
+// g = lane / 32 and r = lane % 32:
+//   operand "A" (32 x 16): lane holds row r,    k = 8g .. 8g+7   (8 bf16 = one 16-byte vector)
+//   operand "B" (16 x 32): lane holds column r, k = 8g .. 8g+7
+//   accumulator (32 x 32): lane holds column r, rows (i / 4) * 8 + 4g + (i % 4), i = 0..15
+#include "et_common.h"
+
+namespace et {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+namespace {
+
+__device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
+  bf16x2 v;
+  v.x = (__bf16)lo;
+  v.y = (__bf16)hi;
+  return __builtin_bit_cast(uint32_t, v);
+}
+
+__device__ __forceinline__ f32x16 mfma32(const uint4 &a, const uint4 &b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                 __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+// ---------------------------------------------------------------------------------------
+// LayerNorm: one wavefront per row, row held in registers, fp32 statistics (two passes over
+// the registers: mean, then biased variance about the mean).
+// ---------------------------------------------------------------------------------------
+constexpr int kLnRows = 4;
+
+template <int NV>
+__global__ __launch_bounds__(kLnRows * kWave) void layernorm_kernel(
+    const uint16_t *__restrict__ x, const float *__restrict__ gamma, const float *__restrict__ beta,
+    float eps, int rows, int D, uint16_t *__restrict__ y) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * kLnRows + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  uint4 raw[NV];
+  Row<NV> r;
+  load_row<NV>(x + (size_t)row * D, D, lane, raw);
+  unpack_row<NV>(raw, r);
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV * 8; ++i) s += r.v[i];           // pad lanes hold zeros
+  const float mean = wave_sum(s) / (float)D;
+  float q = 0.f;
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    if ((j * kWave + lane) * 8 < D) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float d = r.v[j * 8 + e] - mean;
+        q = fmaf(d, d, q);
+      }
+    }
+  }
+  const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)D + eps);
+  uint16_t *out = y + (size_t)row * D;
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    const int c = (j * kWave + lane) * 8;
+    if (c < D) {
+      const float4 g0 = *reinterpret_cast<const float4 *>(gamma + c);
+      const float4 g1 = *reinterpret_cast<const float4 *>(gamma + c + 4);
+      const float4 b0 = *reinterpret_cast<const float4 *>(beta + c);
+      const float4 b1 = *reinterpret_cast<const float4 *>(beta + c + 4);
+      const float *v = &r.v[j * 8];
+      uint4 o;
+      o.x = cvt_pk_bf16((v[0] - mean) * rstd * g0.x + b0.x, (v[1] - mean) * rstd * g0.y + b0.y);
+      o.y = cvt_pk_bf16((v[2] - mean) * rstd * g0.z + b0.z, (v[3] - mean) * rstd * g0.w + b0.w);
+      o.z = cvt_pk_bf16((v[4] - mean) * rstd * g1.x + b1.x, (v[5] - mean) * rstd * g1.y + b1.y);
+      o.w = cvt_pk_bf16((v[6] - mean) * rstd * g1.z + b1.z, (v[7] - mean) * rstd * g1.w + b1.w);
+      *reinterpret_cast<uint4 *>(out + c) = o;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Patch extraction: frames fp32 [T, C, H, W] -> bf16 [T * L, Kpad]; row (t, gy, gx), column
+// (c, py, px) flattened; columns >= C*P*P are zero.  One thread writes 8 columns (16 bytes).
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void im2col_kernel(const float *__restrict__ frames, int T, int C, int H,
+                                                     int W, int P, int GX, int L, int Kreal, int Kpad,
+                                                     uint16_t *__restrict__ out) {
+  const int chunks = Kpad / 8;
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (size_t)T * L * chunks) return;
+  const int ch = (int)(idx % chunks);
+  const size_t row = idx / chunks;
+  const int l = (int)(row % L), t = (int)(row / L);
+  const int gy = l / GX, gx = l % GX;
+  float v[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int kk = ch * 8 + e;
+    float val = 0.f;
+    if (kk < Kreal) {
+      const int c = kk / (P * P), rem = kk % (P * P);
+      const int py = rem / P, px = rem % P;
+      val = frames[(((size_t)t * C + c) * H + (gy * P + py)) * W + (gx * P + px)];
+    }
+    v[e] = val;
+  }
+  uint4 o;
+  o.x = cvt_pk_bf16(v[0], v[1]); o.y = cvt_pk_bf16(v[2], v[3]);
+  o.z = cvt_pk_bf16(v[4], v[5]); o.w = cvt_pk_bf16(v[6], v[7]);
+  *reinterpret_cast<uint4 *>(out + row * Kpad + ch * 8) = o;
+}
+
+// ---------------------------------------------------------------------------------------
+// GEMM  C[m, n] = sum_k A[m, k] W[n, k] + bias[n]  (+ epilogue), bf16 operands, fp32 accumulate.
+// Both operands are k-contiguous, so both feed MFMA as 16-byte vectors straight from LDS.
+// The weight tile is MFMA operand "A" (rows = n) and the activation tile operand "B"
+// (columns = m): each lane then owns 4 consecutive n of one output row m per accumulator
+// quad, which packs to an 8-byte bf16 store.
+// Tiling: workgroup BM x BN x 64, WAVES_M x WAVES_N wavefronts, double-buffered LDS with the
+// next k-tile prefetched global -> registers while the current one is multiplied.
+// ---------------------------------------------------------------------------------------
+constexpr int kBK = 64;
+constexpr int kLdsRow = kBK + 8;   // 144-byte row stride: 16-byte reads of 16 rows hit distinct banks
+
+__device__ __forceinline__ float gelu_tanh_f(float u) {
+  // 0.5 u (1 + tanh(y)) = u / (1 + exp(-2y)),  y = sqrt(2/pi) (u + 0.044715 u^3)
+  const float y2 = 1.5957691216057308f * (u + 0.044715f * u * u * u);
+  return u / (1.0f + __expf(-y2));
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI>
+__global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(GemmArgs g, int tiles_m, int tiles_n) {
+  constexpr int NT = WAVES_M * WAVES_N * 64;
+  constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;    // wavefront tile
+  constexpr int FM = WTM / 32, FN = WTN / 32;              // MFMA tiles per wavefront
+  constexpr int A_CH = BM * (kBK / 8) / NT;                // 16-byte chunks per thread per k-tile
+  constexpr int W_CH = BN * (kBK / 8) / NT;
+  static_assert(BM * (kBK / 8) % NT == 0 && BN * (kBK / 8) % NT == 0, "tile/threads mismatch");
+  extern __shared__ __align__(16) uint16_t lds[];
+  uint16_t *As = lds;                                      // [2][BM][kLdsRow]
+  uint16_t *Ws = lds + 2 * BM * kLdsRow;                   // [2][BN][kLdsRow]
+
+  // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of tiles
+  // (n fastest) so that tiles sharing an activation row block meet in the same L2.
+  const int nblk = tiles_m * tiles_n;
+  int bid = blockIdx.x;
+  {
+    const int per = nblk / 8, rem = nblk % 8, xcd = bid % 8, slot = bid / 8;
+    bid = xcd * per + (xcd < rem ? xcd : rem) + slot;
+  }
+  const int tile_m = bid / tiles_n, tile_n = bid % tiles_n;
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+  const int r32 = lane & 31, grp = lane >> 5;
+
+  const uint16_t *a_src[A_CH];
+  const uint16_t *w_src[W_CH];
+  int a_dst[A_CH], w_dst[W_CH];
+#pragma unroll
+  for (int i = 0; i < A_CH; ++i) {
+    const int c = i * NT + tid, row = c >> 3, kc = c & 7;
+    int m = m0 + row;
+    if (m >= g.M) m = g.M - 1;                             // clamp: rows past M are never stored
+    a_src[i] = g.A + (size_t)m * g.lda + kc * 8;
+    a_dst[i] = row * kLdsRow + kc * 8;
+  }
+#pragma unroll
+  for (int i = 0; i < W_CH; ++i) {
+    const int c = i * NT + tid, row = c >> 3, kc = c & 7;
+    w_src[i] = g.W + (size_t)(n0 + row) * g.K + kc * 8;    // W is padded to whole tiles in n
+    w_dst[i] = row * kLdsRow + kc * 8;
+  }
+
+  f32x16 acc[FN][FM];
+#pragma unroll
+  for (int a = 0; a < FN; ++a)
+#pragma unroll
+    for (int b = 0; b < FM; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+
+  uint4 a_reg[A_CH], w_reg[W_CH];
+#pragma unroll
+  for (int i = 0; i < A_CH; ++i) a_reg[i] = *reinterpret_cast<const uint4 *>(a_src[i]);
+#pragma unroll
+  for (int i = 0; i < W_CH; ++i) w_reg[i] = *reinterpret_cast<const uint4 *>(w_src[i]);
+#pragma unroll
+  for (int i = 0; i < A_CH; ++i) *reinterpret_cast<uint4 *>(As + a_dst[i]) = a_reg[i];
+#pragma unroll
+  for (int i = 0; i < W_CH; ++i) *reinterpret_cast<uint4 *>(Ws + w_dst[i]) = w_reg[i];
+  __syncthreads();
+
+  const int kt_n = g.K / kBK;
+  for (int kt = 0; kt < kt_n; ++kt) {
+    const int cur = kt & 1;
+    if (kt + 1 < kt_n) {
+      const int ko = (kt + 1) * kBK;
+#pragma unroll
+      for (int i = 0; i < A_CH; ++i) a_reg[i] = *reinterpret_cast<const uint4 *>(a_src[i] + ko);
+#pragma unroll
+      for (int i = 0; i < W_CH; ++i) w_reg[i] = *reinterpret_cast<const uint4 *>(w_src[i] + ko);
+    }
+    const uint16_t *Ac = As + cur * BM * kLdsRow + (wm * WTM + r32) * kLdsRow + grp * 8;
+    const uint16_t *Wc = Ws + cur * BN * kLdsRow + (wn * WTN + r32) * kLdsRow + grp * 8;
+#pragma unroll
+    for (int ks = 0; ks < kBK / 16; ++ks) {
+      uint4 fa[FM], fw[FN];
+#pragma unroll
+      for (int b = 0; b < FM; ++b) fa[b] = *reinterpret_cast<const uint4 *>(Ac + b * 32 * kLdsRow + ks * 16);
+#pragma unroll
+      for (int a = 0; a < FN; ++a) fw[a] = *reinterpret_cast<const uint4 *>(Wc + a * 32 * kLdsRow + ks * 16);
+#pragma unroll
+      for (int a = 0; a < FN; ++a)
+#pragma unroll
+        for (int b = 0; b < FM; ++b) acc[a][b] = mfma32(fw[a], fa[b], acc[a][b]);
+    }
+    if (kt + 1 < kt_n) {
+      uint16_t *An = As + (cur ^ 1) * BM * kLdsRow;
+      uint16_t *Wn = Ws + (cur ^ 1) * BN * kLdsRow;
+#pragma unroll
+      for (int i = 0; i < A_CH; ++i) *reinterpret_cast<uint4 *>(An + a_dst[i]) = a_reg[i];
+#pragma unroll
+      for (int i = 0; i < W_CH; ++i) *reinterpret_cast<uint4 *>(Wn + w_dst[i]) = w_reg[i];
+    }
+    __syncthreads();
+  }
+
+  // Epilogue: lane owns row m = .. + r32 and, per accumulator quad q, columns n = .. + 8q + 4grp + (0..3).
+#pragma unroll
+  for (int b = 0; b < FM; ++b) {
+    const int m = m0 + wm * WTM + b * 32 + r32;
+    if (m >= g.M) continue;
+    uint16_t *crow = g.C + (size_t)m * g.ldc;
+    const uint16_t *rrow = nullptr;
+    if (EPI == EPI_BIAS_RES) rrow = g.res + (size_t)(m % g.res_mod) * g.ldr;
+#pragma unroll
+    for (int a = 0; a < FN; ++a) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n = n0 + wn * WTN + a * 32 + q * 8 + grp * 4;
+        if (n >= g.n_store) continue;
+        const float4 bi = *reinterpret_cast<const float4 *>(g.bias + n);
+        float v0 = acc[a][b][q * 4 + 0] + bi.x, v1 = acc[a][b][q * 4 + 1] + bi.y;
+        float v2 = acc[a][b][q * 4 + 2] + bi.z, v3 = acc[a][b][q * 4 + 3] + bi.w;
+        if (EPI == EPI_BIAS_GELU) {
+          v0 = gelu_tanh_f(v0); v1 = gelu_tanh_f(v1); v2 = gelu_tanh_f(v2); v3 = gelu_tanh_f(v3);
+        }
+        if (EPI == EPI_BIAS_RES) {
+          const uint2 rr = *reinterpret_cast<const uint2 *>(rrow + n);
+          v0 += bf16lo_to_f32(rr.x); v1 += bf16hi_to_f32(rr.x);
+          v2 += bf16lo_to_f32(rr.y); v3 += bf16hi_to_f32(rr.y);
+        }
+        uint2 o;
+        o.x = cvt_pk_bf16(v0, v1);
+        o.y = cvt_pk_bf16(v2, v3);
+        *reinterpret_cast<uint2 *>(crow + n) = o;
+      }
+    }
+  }
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N>
+int launch_gemm_cfg(const GemmArgs &g, hipStream_t s) {
+  constexpr int NT = WAVES_M * WAVES_N * 64;
+  constexpr size_t lds_bytes = (size_t)2 * (BM + BN) * kLdsRow * sizeof(uint16_t);
+  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.n_store + BN - 1) / BN;
+  const dim3 grid(tiles_m * tiles_n), block(NT);
+#define ET_GEMM_LAUNCH(E)                                                                        \
+  {                                                                                              \
+    auto kern = gemm_kernel<BM, BN, WAVES_M, WAVES_N, E>;                                        \
+    static bool attr_set = false;                                                                \
+    if (!attr_set) {                                                                             \
+      ET_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                           \
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));   \
+      attr_set = true;                                                                           \
+    }                                                                                            \
+    hipLaunchKernelGGL(kern, grid, block, lds_bytes, s, g, tiles_m, tiles_n);                    \
+  }
+  switch (g.epilogue) {
+    case EPI_BIAS: ET_GEMM_LAUNCH(EPI_BIAS); break;
+    case EPI_BIAS_GELU: ET_GEMM_LAUNCH(EPI_BIAS_GELU); break;
+    case EPI_BIAS_RES: ET_GEMM_LAUNCH(EPI_BIAS_RES); break;
+    default: set_error("unknown epilogue %d", g.epilogue); return ET_ERR_INVALID_ARG;
+  }
+#undef ET_GEMM_LAUNCH
+  ET_LAUNCH_CHECK();
+  return ET_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// Attention: softmax(Q K^T / sqrt(hd)) V inside one frame, one head per workgroup column.
+// Flash-style streaming over 64-key tiles with an online softmax.  Everything is computed
+// transposed: S^T = K Q^T puts the query on the accumulator's lane axis, so the running
+// maximum, the running sum and the rescale factor are per-lane scalars, and the exponentiated
+// accumulator registers are, without any data movement, MFMA operand "B" of
+// O^T = V^T P^T.  V is staged transposed in LDS with the keys of each 16-key chunk permuted
+// to match the accumulator's row order.
+// ---------------------------------------------------------------------------------------
+constexpr int kAttWaves = 4;
+constexpr int kAttBQ = kAttWaves * 32;
+constexpr int kAttBKV = 64;
+constexpr int kVtRow = kAttBKV + 8;
+
+template <int HD>
+__global__ __launch_bounds__(kAttWaves * 64) void attention_kernel(
+    const uint16_t *__restrict__ qkv, const int32_t *__restrict__ cu, int n_heads, float scale_log2,
+    uint16_t *__restrict__ out) {
+  constexpr int NC = (HD + 15) / 16;        // 16-wide contraction chunks of Q K^T
+  constexpr int HDP = NC * 16;
+  constexpr int KROW = HDP + 8;             // LDS row stride of the K tile (elements)
+  constexpr int NDB = (HD + 31) / 32;       // 32-row blocks of O^T
+  constexpr int NCH = HD / 8;               // 16-byte chunks per head row in global memory
+  static_assert(HD % 8 == 0, "head_dim must be a multiple of 8");
+  __shared__ __align__(16) uint16_t Ks[kAttBKV * KROW];
+  __shared__ __align__(16) uint16_t Vt[NDB * 32 * kVtRow];
+
+  const int f = blockIdx.z, h = blockIdx.y;
+  const int start = cu[f], len = cu[f + 1] - start;
+  const int q0 = blockIdx.x * kAttBQ;
+  if (q0 >= len) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r32 = lane & 31, grp = lane >> 5;
+  const int D = n_heads * HD, ld = 3 * D;
+  const uint16_t *qbase = qkv + (size_t)start * ld + h * HD;
+  const uint16_t *kbase = qbase + D;
+  const uint16_t *vbase = qbase + 2 * D;
+
+  // rows of V^T past the head dimension stay zero for the whole kernel
+  for (int i = tid; i < NDB * 32 * kVtRow / 2; i += kAttWaves * 64) reinterpret_cast<uint32_t *>(Vt)[i] = 0u;
+
+  uint4 qf[NC];
+  {
+    const int q = q0 + wave * 32 + r32;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      const int d = c * 16 + grp * 8;
+      qf[c] = (q < len && d < HD) ? *reinterpret_cast<const uint4 *>(qbase + (size_t)q * ld + d)
+                                  : make_uint4(0, 0, 0, 0);
+    }
+  }
+
+  f32x16 o_acc[NDB];
+#pragma unroll
+  for (int b = 0; b < NDB; ++b)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o_acc[b][i] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+
+  for (int kv0 = 0; kv0 < len; kv0 += kAttBKV) {
+    __syncthreads();                                   // previous tile fully consumed (and Vt zeroed)
+    for (int i = tid; i < kAttBKV * (HDP / 8); i += kAttWaves * 64) {
+      const int key = i / (HDP / 8), ch = i % (HDP / 8);
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (kv0 + key < len && ch < NCH) v = *reinterpret_cast<const uint4 *>(kbase + (size_t)(kv0 + key) * ld + ch * 8);
+      *reinterpret_cast<uint4 *>(Ks + key * KROW + ch * 8) = v;
+    }
+    for (int i = tid; i < kAttBKV * NCH; i += kAttWaves * 64) {
+      const int key = i / NCH, ch = i % NCH;
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (kv0 + key < len) v = *reinterpret_cast<const uint4 *>(vbase + (size_t)(kv0 + key) * ld + ch * 8);
+      // position of this key inside its 16-key chunk: group (key/4)%2, slot (key/8)*4 + key%4
+      const int k16 = key & 15;
+      const int pos = (key & ~15) + ((k16 >> 2) & 1) * 8 + (k16 >> 3) * 4 + (k16 & 3);
+      uint16_t *dst = Vt + (ch * 8) * kVtRow + pos;
+      dst[0 * kVtRow] = (uint16_t)(v.x & 0xFFFF); dst[1 * kVtRow] = (uint16_t)(v.x >> 16);
+      dst[2 * kVtRow] = (uint16_t)(v.y & 0xFFFF); dst[3 * kVtRow] = (uint16_t)(v.y >> 16);
+      dst[4 * kVtRow] = (uint16_t)(v.z & 0xFFFF); dst[5 * kVtRow] = (uint16_t)(v.z >> 16);
+      dst[6 * kVtRow] = (uint16_t)(v.w & 0xFFFF); dst[7 * kVtRow] = (uint16_t)(v.w >> 16);
+    }
+    __syncthreads();
+
+    // S^T for two 32-key blocks: rows = keys, columns = this wavefront's 32 queries
+    f32x16 s_acc[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s_acc[kb][i] = 0.f;
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        const uint4 kf = *reinterpret_cast<const uint4 *>(Ks + (kb * 32 + r32) * KROW + c * 16 + grp * 8);
+        s_acc[kb] = mfma32(kf, qf[c], s_acc[kb]);
+      }
+    }
+    float m_tile = -INFINITY;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int key = kv0 + kb * 32 + (i >> 2) * 8 + grp * 4 + (i & 3);
+        const float v = (key < len) ? s_acc[kb][i] * scale_log2 : -INFINITY;
+        s_acc[kb][i] = v;
+        m_tile = fmaxf(m_tile, v);
+      }
+    m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32, 64));
+    const float m_new = fmaxf(m_run, m_tile);            // finite: every tile has a valid key
+    const float alpha = exp2f(m_run - m_new);
+    m_run = m_new;
+    float l_tile = 0.f;
+    uint4 pf[4];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      float p[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        p[i] = exp2f(s_acc[kb][i] - m_new);
+        l_tile += p[i];
+      }
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh) {
+        uint4 v;
+        v.x = cvt_pk_bf16(p[hh * 8 + 0], p[hh * 8 + 1]); v.y = cvt_pk_bf16(p[hh * 8 + 2], p[hh * 8 + 3]);
+        v.z = cvt_pk_bf16(p[hh * 8 + 4], p[hh * 8 + 5]); v.w = cvt_pk_bf16(p[hh * 8 + 6], p[hh * 8 + 7]);
+        pf[kb * 2 + hh] = v;
+      }
+    }
+    l_run = l_run * alpha + l_tile;
+#pragma unroll
+    for (int b = 0; b < NDB; ++b) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o_acc[b][i] *= alpha;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const uint4 vf = *reinterpret_cast<const uint4 *>(Vt + (b * 32 + r32) * kVtRow + c * 16 + grp * 8);
+        o_acc[b] = mfma32(vf, pf[c], o_acc[b]);
+      }
+    }
+  }
+
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const float inv = 1.0f / l_tot;
+  const int q = q0 + wave * 32 + r32;
+  if (q < len) {
+    uint16_t *orow = out + (size_t)(start + q) * D + h * HD;
+#pragma unroll
+    for (int b = 0; b < NDB; ++b)
+#pragma unroll
+      for (int qd = 0; qd < 4; ++qd) {
+        const int d = b * 32 + qd * 8 + grp * 4;
+        if (d < HD) {
+          uint2 o;
+          o.x = cvt_pk_bf16(o_acc[b][qd * 4 + 0] * inv, o_acc[b][qd * 4 + 1] * inv);
+          o.y = cvt_pk_bf16(o_acc[b][qd * 4 + 2] * inv, o_acc[b][qd * 4 + 3] * inv);
+          *reinterpret_cast<uint2 *>(orow + d) = o;
+        }
+      }
+  }
+}
+
+}  // namespace
+
+int launch_layernorm(const uint16_t *x, const float *g, const float *b, float eps, int rows, int D,
+                     uint16_t *y, hipStream_t s) {
+  if (rows <= 0) return ET_OK;
+  dim3 grid((rows + kLnRows - 1) / kLnRows), block(kLnRows * kWave);
+  ET_DISPATCH_NV(D, hipLaunchKernelGGL(layernorm_kernel<NV>, grid, block, 0, s, x, g, b, eps, rows, D, y));
+  ET_LAUNCH_CHECK();
+  return ET_OK;
+}
+
+int launch_im2col(const float *frames, int T, int C, int H, int W, int P, int Kpad, uint16_t *out,
+                  hipStream_t s) {
+  const int GX = W / P, GY = H / P, L = GX * GY;
+  const size_t n = (size_t)T * L * (Kpad / 8);
+  hipLaunchKernelGGL(im2col_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, frames, T, C, H, W, P,
+                     GX, L, C * P * P, Kpad, out);
+  ET_LAUNCH_CHECK();
+  return ET_OK;
+}
+
+int launch_gemm(const GemmArgs &g, hipStream_t s) {
+  if (g.M <= 0) return ET_OK;
+  if (g.K % kBK != 0 || g.n_store % 4 != 0) {
+    set_error("gemm: K = %d must be a multiple of 64 and n_store = %d of 4", g.K, g.n_store);
+    return ET_ERR_INVALID_ARG;
+  }
+  // Large problems: 256 x 256 tiles when N divides evenly, else 256 x 128; small M falls back
+  // to 128 x 128 so that the launch still covers the 256 compute units.
+  const long tiles_big = (long)((g.M + 255) / 256) * ((g.n_store + 127) / 128);
+  if (tiles_big >= 512) {
+    if (g.n_store % 256 == 0) return launch_gemm_cfg<256, 256, 2, 4>(g, s);
+    return launch_gemm_cfg<256, 128, 2, 2>(g, s);
+  }
+  return launch_gemm_cfg<128, 128, 2, 2>(g, s);
+}
+
+bool head_dim_supported(int hd) {
+  return hd == 16 || hd == 32 || hd == 64 || hd == 72 || hd == 80 || hd == 96 || hd == 128;
+}
+
+int launch_attention(const uint16_t *qkv, const int32_t *cu, int n_frames, int max_len, int n_heads,
+                     int head_dim, uint16_t *out, hipStream_t s) {
+  if (n_frames <= 0 || max_len <= 0) return ET_OK;
+  const dim3 grid((max_len + kAttBQ - 1) / kAttBQ, n_heads, n_frames), block(kAttWaves * 64);
+  const float scale_log2 = 1.4426950408889634f / sqrtf((float)head_dim);
+#define ET_ATT(HD) \
+  case HD: hipLaunchKernelGGL(attention_kernel<HD>, grid, block, 0, s, qkv, cu, n_heads, scale_log2, out); break;
+  switch (head_dim) {
+    ET_ATT(16) ET_ATT(32) ET_ATT(64) ET_ATT(72) ET_ATT(80) ET_ATT(96) ET_ATT(128)
+    default: set_error("head_dim %d is not instantiated", head_dim); return ET_ERR_UNSUPPORTED;
+  }
+#undef ET_ATT
+  ET_LAUNCH_CHECK();
+  return ET_OK;
+}
+
+}  // namespace et

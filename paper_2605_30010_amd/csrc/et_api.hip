@@ -1,0 +1,222 @@
+// C boundary of libearlytom: argument validation, error reporting, the single-step entry
+// points and the compression stage (et_merge_select).  The encoder itself lives in
+// encoder.hip.
+#include <math.h>
+#include <string.h>
+
+#include "et_common.h"
+
+namespace et {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+int hip_fail(hipError_t e, const char *what, const char *file, int line) {
+  const char *base = strrchr(file, '/');
+  set_error("HIP error %d (%s) at %s:%d in %s", (int)e, hipGetErrorString(e), base ? base + 1 : file,
+            line, what);
+  return ET_ERR_HIP;
+}
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Carves a workspace into 256-byte aligned pieces.
+struct Carver {
+  char *base;
+  size_t off = 0;
+  explicit Carver(void *p) : base(static_cast<char *>(p)) {}
+  template <typename T>
+  T *take(size_t n) {
+    T *p = base ? reinterpret_cast<T *>(base + off) : nullptr;
+    off += align_up(n * sizeof(T), 256);
+    return p;
+  }
+};
+
+MergeWs carve_merge(void *ws, int T, int L, int D) {
+  Carver c(ws);
+  MergeWs m;
+  m.cos = c.take<float>((size_t)(T > 1 ? T - 1 : 1) * L);
+  m.sim = c.take<float>((size_t)T);
+  m.score = c.take<float>((size_t)T * L);
+  m.n_seg = c.take<int32_t>(64);
+  m.merged = c.take<uint16_t>((size_t)T * L * D);
+  m.bytes = c.off;
+  return m;
+}
+
+static int check_merge_shape(int T, int L, int D) {
+  ET_REQUIRE(T >= 1, "T = %d: a clip needs at least one frame", T);
+  ET_REQUIRE(L >= 1, "L = %d: a frame needs at least one token", L);
+  ET_REQUIRE(D >= 8 && D % 8 == 0, "D = %d must be a positive multiple of 8", D);
+  ET_REQUIRE((double)T * L * D < 2.0e9 * 4, "T*L*D too large");
+  if (D > 4096) { set_error("D = %d above the supported 4096", D); return ET_ERR_UNSUPPORTED; }
+  if (L > 15360) { set_error("L = %d above the supported 15360", L); return ET_ERR_UNSUPPORTED; }
+  return ET_OK;
+}
+
+static int check_outputs(const et_output *out) {
+  ET_REQUIRE(out != nullptr, "out is NULL");
+  ET_REQUIRE(out->tokens_dev && out->kept_idx_dev && out->cu_tokens_dev && out->seg_start_dev,
+             "an output buffer is NULL (tokens_dev, kept_idx_dev, cu_tokens_dev, seg_start_dev are required)");
+  return ET_OK;
+}
+
+int enqueue_merge_stage(const uint16_t *x, int T, int L, int D, float tau, int k, const MergeWs &w,
+                        float *sim_out, int32_t *seg_start, int32_t *kept, int32_t *cu_tokens,
+                        uint16_t *packed, hipStream_t s, Profiler *prof) {
+  float *sim = sim_out ? sim_out : w.sim;
+  ET_TIMED_P(prof, ET_K_SIMILARITY, launch_similarity(x, T, L, D, w.cos, s));
+  ET_TIMED_P(prof, ET_K_SCAN, launch_sim_mean_scan(w.cos, T, L, tau, sim, seg_start, w.n_seg, true, true, s));
+  ET_TIMED_P(prof, ET_K_MERGE, launch_segment_mean(x, T, L, D, seg_start, w.n_seg, w.merged, w.score, s));
+  ET_TIMED_P(prof, ET_K_SELECT, launch_topk(w.score, T, w.n_seg, L, k, kept, cu_tokens, s));
+  ET_TIMED_P(prof, ET_K_COMPACT, launch_compact(w.merged, kept, T, w.n_seg, L, D, k, packed, s));
+  return ET_OK;
+}
+
+int Profiler::begin(int kind, hipStream_t s) {
+  if (!on) return ET_OK;
+  const size_t need = 2 * (kinds.size() + 1);
+  while (pool.size() < need) {
+    hipEvent_t e;
+    ET_HIP(hipEventCreate(&e));
+    pool.push_back(e);
+  }
+  kinds.push_back(kind);
+  ET_HIP(hipEventRecord(pool[2 * (kinds.size() - 1)], s));
+  return ET_OK;
+}
+
+int Profiler::end(hipStream_t s) {
+  if (!on) return ET_OK;
+  ET_HIP(hipEventRecord(pool[2 * (kinds.size() - 1) + 1], s));
+  return ET_OK;
+}
+
+int Profiler::collect() {
+  if (!on) return ET_OK;
+  for (size_t i = 0; i < kinds.size(); ++i) {
+    float t = 0.f;
+    ET_HIP(hipEventElapsedTime(&t, pool[2 * i], pool[2 * i + 1]));
+    ms[kinds[i]] += t;
+    launches[kinds[i]] += 1;
+  }
+  kinds.clear();
+  return ET_OK;
+}
+
+void Profiler::destroy() {
+  for (hipEvent_t e : pool) (void)hipEventDestroy(e);
+  pool.clear();
+}
+
+}  // namespace et
+
+using namespace et;
+
+extern "C" {
+
+const char *et_last_error(void) { return g_err; }
+
+int32_t et_keep_count(int32_t L, float keep_ratio) {
+  if (L < 1 || !(keep_ratio > 0.f) || !(keep_ratio <= 1.f)) return 0;
+  double v = floor((double)keep_ratio * (double)L + 1e-4);
+  int32_t k = (int32_t)v;
+  if (k < 1) k = 1;
+  if (k > L) k = L;
+  return k;
+}
+
+size_t et_merge_workspace_bytes(int32_t T, int32_t L, int32_t D) {
+  if (T < 1 || L < 1 || D < 8) return 0;
+  return carve_merge(nullptr, T, L, D).bytes;
+}
+
+int et_merge_select(const uint16_t *x_dev, int32_t T, int32_t L, int32_t D, float sim_threshold,
+                    float keep_ratio, void *workspace_dev, size_t workspace_bytes, void *hip_stream,
+                    et_output *out) {
+  int rc;
+  ET_REQUIRE(x_dev != nullptr, "x_dev is NULL");
+  if ((rc = check_merge_shape(T, L, D))) return rc;
+  if ((rc = check_outputs(out))) return rc;
+  ET_REQUIRE(!isnan(sim_threshold), "sim_threshold is NaN");
+  ET_REQUIRE(keep_ratio > 0.f && keep_ratio <= 1.f, "keep_ratio = %g outside (0, 1]", (double)keep_ratio);
+  ET_REQUIRE(workspace_dev != nullptr, "workspace_dev is NULL");
+  size_t need = et_merge_workspace_bytes(T, L, D);
+  if (workspace_bytes < need) {
+    set_error("workspace of %zu bytes is smaller than the %zu needed", workspace_bytes, need);
+    return ET_ERR_WORKSPACE;
+  }
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  MergeWs w = carve_merge(workspace_dev, T, L, D);
+  const int k = et_keep_count(L, keep_ratio);
+  if ((rc = enqueue_merge_stage(x_dev, T, L, D, sim_threshold, k, w, out->frame_sim_dev,
+                                out->seg_start_dev, out->kept_idx_dev, out->cu_tokens_dev,
+                                out->tokens_dev, s, nullptr)))
+    return rc;
+  int32_t n_seg = 0;
+  ET_HIP(hipMemcpyAsync(&n_seg, w.n_seg, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  ET_HIP(hipStreamSynchronize(s));
+  out->n_frames_out = n_seg;
+  out->n_tokens = n_seg * k;
+  return ET_OK;
+}
+
+int et_frame_similarity(const uint16_t *x_dev, int32_t T, int32_t L, int32_t D, float *cos_dev,
+                        float *sim_dev, void *hip_stream) {
+  int rc;
+  ET_REQUIRE(x_dev && cos_dev && sim_dev, "a pointer argument is NULL");
+  if ((rc = check_merge_shape(T, L, D))) return rc;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (T < 2) return ET_OK;
+  if ((rc = launch_similarity(x_dev, T, L, D, cos_dev, s))) return rc;
+  return launch_sim_mean_scan(cos_dev, T, L, 0.f, sim_dev, nullptr, nullptr, true, false, s);
+}
+
+int et_segment_scan(const float *sim_dev, int32_t T, float sim_threshold, int32_t *seg_start_dev,
+                    int32_t *n_seg_dev, void *hip_stream) {
+  ET_REQUIRE(seg_start_dev && n_seg_dev, "a pointer argument is NULL");
+  ET_REQUIRE(T >= 1, "T = %d: a clip needs at least one frame", T);
+  ET_REQUIRE(T == 1 || sim_dev != nullptr, "sim_dev is NULL");
+  ET_REQUIRE(!isnan(sim_threshold), "sim_threshold is NaN");
+  return launch_sim_mean_scan(nullptr, T, 1, sim_threshold, const_cast<float *>(sim_dev), seg_start_dev,
+                              n_seg_dev, false, true, static_cast<hipStream_t>(hip_stream));
+}
+
+int et_segment_mean(const uint16_t *x_dev, int32_t T, int32_t L, int32_t D, const int32_t *seg_start_dev,
+                    const int32_t *n_seg_dev, uint16_t *merged_dev, float *score_dev, void *hip_stream) {
+  int rc;
+  ET_REQUIRE(x_dev && seg_start_dev && n_seg_dev && merged_dev && score_dev, "a pointer argument is NULL");
+  if ((rc = check_merge_shape(T, L, D))) return rc;
+  return launch_segment_mean(x_dev, T, L, D, seg_start_dev, n_seg_dev, merged_dev, score_dev,
+                             static_cast<hipStream_t>(hip_stream));
+}
+
+int et_topk_select(const float *score_dev, int32_t n_rows, int32_t L, int32_t k, int32_t *kept_idx_dev,
+                   void *hip_stream) {
+  ET_REQUIRE(score_dev && kept_idx_dev, "a pointer argument is NULL");
+  ET_REQUIRE(n_rows >= 0 && L >= 1, "n_rows = %d, L = %d out of range", n_rows, L);
+  ET_REQUIRE(k >= 1 && k <= L, "k = %d outside [1, L = %d]", k, L);
+  if (n_rows == 0) return ET_OK;
+  return launch_topk(score_dev, n_rows, nullptr, L, k, kept_idx_dev, nullptr,
+                     static_cast<hipStream_t>(hip_stream));
+}
+
+int et_compact_tokens(const uint16_t *merged_dev, const int32_t *kept_idx_dev, int32_t n_rows, int32_t L,
+                      int32_t D, int32_t k, uint16_t *out_dev, void *hip_stream) {
+  ET_REQUIRE(merged_dev && kept_idx_dev && out_dev, "a pointer argument is NULL");
+  ET_REQUIRE(n_rows >= 0 && L >= 1 && D >= 8 && D % 8 == 0, "n_rows = %d, L = %d, D = %d out of range",
+             n_rows, L, D);
+  ET_REQUIRE(k >= 1 && k <= L, "k = %d outside [1, L = %d]", k, L);
+  if (n_rows == 0) return ET_OK;
+  return launch_compact(merged_dev, kept_idx_dev, n_rows, nullptr, L, D, k, out_dev,
+                        static_cast<hipStream_t>(hip_stream));
+}
+
+}  // extern "C"

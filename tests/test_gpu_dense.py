@@ -1,0 +1,116 @@
+"""GPU parity of the dense encoder kernels (LayerNorm, MFMA GEMM + epilogues, attention)
+against the CPU oracle's definitions, on bf16-representable inputs.
+
+Tolerances: the kernels accumulate in float32 and round the result once to bf16
+(relative step 2^-8), so element errors are bounded by about 2^-8 of the result's
+magnitude plus float32 accumulation noise; relative L2 errors stay below 4e-3.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2605_30010_amd as et
+from et_inputs import bf16_bits_to_f32, f32_to_bf16_bits
+from oracle import earlytom_oracle as O
+from tests._util import bits_to_dev, dev_to_f64, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+
+def _bf(rng, shape, scale=1.0, shift=0.0):
+    bits = f32_to_bf16_bits((rng.standard_normal(shape) * scale + shift).astype(np.float32))
+    return bits, bf16_bits_to_f32(bits).astype(np.float64)
+
+
+@pytest.mark.parametrize("rows,D", [(1, 64), (37, 64), (1000, 1152), (5, 4096), (9, 520)])
+def test_layernorm_matches_oracle(rows, D):
+    rng = np.random.default_rng(rows + D)
+    bits, x = _bf(rng, (rows, D), scale=3.0, shift=1.5)
+    g = (1 + 0.1 * rng.standard_normal(D)).astype(np.float32)
+    b = (0.1 * rng.standard_normal(D)).astype(np.float32)
+    ref = O.layer_norm(x, g.astype(np.float64), b.astype(np.float64), 1e-6)
+    y = et.et_layernorm(bits_to_dev(bits), torch.from_numpy(g).cuda(), torch.from_numpy(b).cuda(), 1e-6)
+    got = dev_to_f64(y)
+    assert np.max(np.abs(got - ref) - 2 ** -8 * np.abs(ref)) < 2e-5
+    assert rel_l2(got, ref) < 3e-3
+
+
+@pytest.mark.parametrize("M,N,K", [(64, 64, 64), (300, 192, 128), (1000, 1152, 1152), (257, 4304, 1152),
+                                   (513, 1152, 4304), (5, 8, 8), (2050, 3456, 1152), (700, 1152, 592)])
+@pytest.mark.parametrize("epi", [0, 1, 2])
+def test_gemm_matches_oracle(M, N, K, epi):
+    if epi != 0 and M * N * K > 600 * 1152 * 1152 and (M, N, K) != (257, 4304, 1152):
+        pytest.skip("large shapes are covered with the plain epilogue")
+    rng = np.random.default_rng(M + N + K + epi)
+    a_bits, a = _bf(rng, (M, K))
+    w_bits, w = _bf(rng, (N, K), scale=0.05)
+    bias = (0.1 * rng.standard_normal(N)).astype(np.float32)
+    r_bits, r = _bf(rng, (M, N))
+    ref = a @ w.T + bias.astype(np.float64)
+    if epi == 1:
+        ref = O.gelu_tanh(ref)
+    if epi == 2:
+        ref = ref + r
+    c = et.et_gemm_bf16(bits_to_dev(a_bits), bits_to_dev(w_bits), torch.from_numpy(bias).cuda(), epi,
+                        residual=bits_to_dev(r_bits) if epi == 2 else None)
+    got = dev_to_f64(c)
+    scale = np.sqrt(K) * 0.05 + 1.0
+    assert np.max(np.abs(got - ref) - 2 ** -8 * np.abs(ref)) < 2e-4 * scale
+    assert rel_l2(got, ref) < 4e-3
+
+
+def test_gemm_residual_in_place():
+    rng = np.random.default_rng(5)
+    M, N, K = 333, 128, 64
+    a_bits, a = _bf(rng, (M, K))
+    w_bits, w = _bf(rng, (N, K), scale=0.1)
+    r_bits, r = _bf(rng, (M, N))
+    bias = torch.zeros(N, dtype=torch.float32, device="cuda")
+    res = bits_to_dev(r_bits)
+    lib = et.load_library()
+    import ctypes as C
+    a_d, w_d = bits_to_dev(a_bits), bits_to_dev(w_bits)
+    rc = lib.et_gemm_bf16(C.c_void_p(a_d.data_ptr()), C.c_void_p(w_d.data_ptr()), C.c_void_p(bias.data_ptr()),
+                          C.c_void_p(res.data_ptr()), M, N, K, 2, C.c_void_p(res.data_ptr()),
+                          C.c_void_p(torch.cuda.current_stream().cuda_stream))
+    assert rc == 0, et.et_last_error()
+    assert rel_l2(dev_to_f64(res), a @ w.T + r) < 4e-3
+
+
+def _attention_ref(qkv, cu, n_heads, hd):
+    D = n_heads * hd
+    out = np.zeros((qkv.shape[0], D))
+    for f in range(len(cu) - 1):
+        a, b = cu[f], cu[f + 1]
+        if b == a:
+            continue
+        q = qkv[a:b, :D].reshape(b - a, n_heads, hd).transpose(1, 0, 2)
+        k = qkv[a:b, D:2 * D].reshape(b - a, n_heads, hd).transpose(1, 0, 2)
+        v = qkv[a:b, 2 * D:].reshape(b - a, n_heads, hd).transpose(1, 0, 2)
+        p = O.softmax_rows(q @ k.transpose(0, 2, 1) / math.sqrt(hd))
+        out[a:b] = (p @ v).transpose(1, 0, 2).reshape(b - a, D)
+    return out
+
+
+@pytest.mark.parametrize("n_heads,hd", [(4, 16), (16, 72), (2, 64), (2, 128), (3, 32), (2, 80), (2, 96)])
+def test_attention_matches_oracle(n_heads, hd):
+    rng = np.random.default_rng(n_heads * hd)
+    lens = [5, 64, 131, 729, 1, 128, 364, 182] if hd in (16, 72) else [5, 130, 64, 1]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    rows, D = int(cu[-1]), n_heads * hd
+    # logits with a spread of several units so that the softmax is far from uniform
+    bits, qkv = _bf(rng, (rows, 3 * D), scale=1.0)
+    qkv_s = qkv.copy()
+    qkv_s[:, :D] *= 2.0
+    bits = f32_to_bf16_bits(qkv_s.astype(np.float32))
+    qkv_s = bf16_bits_to_f32(bits).astype(np.float64)
+    ref = _attention_ref(qkv_s, cu, n_heads, hd)
+    out = et.et_attention(bits_to_dev(bits), torch.from_numpy(cu).cuda(), max(lens), n_heads, hd)
+    got = dev_to_f64(out)
+    assert rel_l2(got, ref) < 6e-3
+    assert np.max(np.abs(got - ref)) < 0.05
+    # a one-token frame attends to itself only: output = its own v, exactly
+    one = int(cu[lens.index(1)])
+    assert np.array_equal(got[one], qkv_s[one, 2 * D:])

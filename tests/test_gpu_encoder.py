@@ -1,0 +1,158 @@
+"""GPU parity of the whole hot path (et_encode_clip) against the CPU oracle.
+
+Decisions (segments, kept positions) are compared bit-exactly under the protocol the
+oracle's float64 and the kernels' bf16 arithmetic allow: the hidden states at the merge
+layer are taken from the GPU (an encoder truncated to `merge_layer` blocks, same kernels,
+so bit-identical to what the full run sees), the oracle continues from them, and seeds are
+chosen so that every similarity is >= 1e-2 from the threshold and the k-th / (k+1)-th score
+gap is >= 1e-5 relative.  Output tokens: relative L2 error <= 2e-2.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2605_30010_amd as et
+from et_inputs import TINY, SIGLIP, build_workload, make_clip, make_weights, bf16_bits_to_f32
+from oracle import earlytom_oracle as O
+from tests._util import dev_to_bits, dev_to_f64, rel_l2
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+
+
+def _encode(enc, frames, m, tau, keep):
+    r = enc.encode(torch.from_numpy(frames).cuda(), m, tau, keep)
+    return {k: (v.clone() if isinstance(v, torch.Tensor) else v) for k, v in r.items()}
+
+
+def _truncated(shape, w, m, max_frames):
+    """Encoder with only the first m blocks and no final LayerNorm: its plain output is the
+    residual stream the compression stage sees."""
+    from dataclasses import replace
+    sh = replace(shape, n_layers=m, has_final_ln=0)
+    return et.Encoder(sh, dict(w, layers=w["layers"][:m]), max_frames)
+
+
+def _stagewise_check(shape, w, frames, m, tau, keep, enc=None):
+    T = frames.shape[0]
+    L, D = shape.tokens_per_frame, shape.d_model
+    enc = enc or et.Encoder(shape, w, T)
+    got = _encode(enc, frames, m, tau, keep)
+    trunc = _truncated(shape, w, m, T)
+    xm = _encode(trunc, frames, -1, 0.0, 1.0)["tokens"]
+    trunc.close()
+    x_gpu = bf16_bits_to_f32(dev_to_bits(xm)).astype(np.float64).reshape(T, L, D)
+    ref = O.encode_clip(shape, w, frames, m, tau, np.float32(keep), x_at_merge=x_gpu)
+    # margins: only then are bit-exact decisions promised
+    assert np.min(np.abs(ref["frame_sim"] - tau)) >= 1e-2
+    k = O.keep_count(L, np.float32(keep))
+    safe = all((np.sort(z)[::-1][k - 1] - np.sort(z)[::-1][k]) >= 1e-5 * np.sort(z)[::-1][k - 1]
+               for z in ref["score"]) if k < L else True
+    assert got["seg_start"].tolist() == ref["seg_start"].tolist()
+    assert got["cu_tokens"].tolist() == ref["cu_tokens"].tolist()
+    np.testing.assert_allclose(got["frame_sim"].cpu().numpy(), ref["frame_sim"], atol=5e-6, rtol=0)
+    same_idx = np.array_equal(got["kept_idx"].cpu().numpy(), ref["kept_idx"])
+    if safe:
+        assert same_idx, "kept positions differ although the score gaps are safe"
+    if not same_idx:       # separate arithmetic error from rank flips of near-tied scores
+        ref = O.encode_clip(shape, w, frames, m, tau, np.float32(keep), x_at_merge=x_gpu,
+                            force_kept=got["kept_idx"].cpu().numpy())
+    err = rel_l2(dev_to_f64(got["tokens"]), ref["tokens"])
+    assert err <= TOL, err
+    return got, ref, err, safe
+
+
+@pytest.fixture(scope="module")
+def tiny():
+    rec = build_workload("c1_tiny")
+    return rec["weights"], rec["frames"]
+
+
+def test_tiny_plain_encoder_matches_oracle(tiny):
+    w, frames = tiny
+    enc = et.Encoder(TINY, w, 8)
+    got = _encode(enc, frames, -1, 0.9, 0.5)
+    ref = O.encode_clip(TINY, w, frames, -1, 0.9, 0.5)
+    assert got["n_frames_out"] == 8 and got["n_tokens"] == 512
+    assert got["kept_idx"].tolist() == ref["kept_idx"].tolist()
+    assert got["cu_tokens"].tolist() == ref["cu_tokens"].tolist()
+    assert got["seg_start"].tolist() == ref["seg_start"].tolist()
+    assert rel_l2(dev_to_f64(got["tokens"]), ref["tokens"]) <= TOL
+    # disabled by arguments instead of merge_layer < 0: identical bits
+    for m in (0, 2, 4):
+        off = _encode(enc, frames, m, math.inf, 1.0)
+        assert torch.equal(off["tokens"], got["tokens"])
+        assert off["seg_start"].tolist() == list(range(9))
+    # frames are independent
+    one = _encode(enc, frames[3:4], -1, 0.9, 0.5)
+    assert torch.equal(one["tokens"], got["tokens"][3 * 64:4 * 64])
+    enc.close()
+
+
+def test_tiny_config_end_to_end(tiny):
+    """Config 1: two scenes of four frames -> two segments, 32 of 64 tokens each."""
+    w, frames = tiny
+    enc = et.Encoder(TINY, w, 8)
+    got, ref, err, safe = _stagewise_check(TINY, w, frames, 2, 0.9, 0.5, enc)
+    assert got["n_frames_out"] == 2 and got["n_tokens"] == 64
+    assert got["seg_start"].tolist() == [0, 4, 8]
+    # fully end-to-end against the float64 oracle (no hidden-state injection)
+    e2e = O.encode_clip(TINY, w, frames, 2, 0.9, 0.5)
+    assert got["seg_start"].tolist() == e2e["seg_start"].tolist()
+    if np.array_equal(got["kept_idx"].cpu().numpy(), e2e["kept_idx"]):
+        assert rel_l2(dev_to_f64(got["tokens"]), e2e["tokens"]) <= TOL
+    for m in (0, 1, 3, 4):
+        _stagewise_check(TINY, w, frames, m, 0.9, 0.5, enc)
+    # two runs are bit-identical
+    again = _encode(enc, frames, 2, 0.9, 0.5)
+    assert torch.equal(again["tokens"], got["tokens"]) and torch.equal(again["kept_idx"], got["kept_idx"])
+    enc.close()
+
+
+def test_identical_frames_collapse_to_the_single_frame_result(tiny):
+    w, frames = tiny
+    enc = et.Encoder(TINY, w, 8)
+    clip = np.repeat(frames[:1], 8, axis=0)
+    for keep in (0.5, 1.0):
+        many = _encode(enc, clip, 2, 0.9, keep)
+        one = _encode(enc, frames[:1], 2, 0.9, keep)
+        assert many["n_frames_out"] == 1 and many["seg_start"].tolist() == [0, 8]
+        assert torch.equal(many["kept_idx"], one["kept_idx"])
+        assert torch.equal(many["tokens"], one["tokens"])
+    plain = _encode(enc, frames[:1], -1, 0.9, 0.5)
+    assert torch.equal(many["tokens"], plain["tokens"])
+    enc.close()
+
+
+def test_ragged_clip_lengths_and_merge_at_the_ends(tiny):
+    w, _ = tiny
+    enc = et.Encoder(TINY, w, 11)
+    frames = make_clip(TINY, [1, 5, 2, 3], 77, base="uniform", sigma=0.02)
+    for m in (0, 4):
+        got, ref, err, safe = _stagewise_check(TINY, w, frames, m, 0.9, 0.3, enc)
+        assert got["seg_start"].tolist() == [0, 1, 6, 8, 11]
+    with pytest.raises(et.EtError):
+        enc.encode(torch.zeros((12, 3, 112, 112), device="cuda"), 2, 0.9, 0.5)
+    with pytest.raises(et.EtError):
+        enc.encode(torch.from_numpy(frames).cuda(), 5, 0.9, 0.5)
+    enc.close()
+
+
+@pytest.fixture(scope="module")
+def siglip8():
+    rec = build_workload("c2_siglip_t8")
+    return rec
+
+
+def test_siglip_shape_8_frames_stagewise(siglip8):
+    """Config 2 (27 layers, d = 1152, 16 heads of 72, 8 frames of 384 x 384, merge after 8 blocks)."""
+    rec = siglip8
+    enc = et.Encoder(SIGLIP, rec["weights"], 8)
+    got, ref, err, safe = _stagewise_check(SIGLIP, rec["weights"], rec["frames"], rec["merge_layer"],
+                                           rec["sim_threshold"], rec["keep_ratio"], enc)
+    assert got["seg_start"].tolist() == np.concatenate([[0], np.cumsum(rec["lengths"])]).tolist()
+    assert got["n_tokens"] == got["n_frames_out"] * 364
+    print("config 2: rel-L2 %.4g, safe margins %s" % (err, safe))
+    enc.close()
