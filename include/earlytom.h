@@ -132,8 +132,9 @@ enum {
   ET_K_SELECT, ET_K_COMPACT, ET_K_MISC, ET_K_COUNT
 };
 int et_profile_enable(et_encoder *enc, int32_t on);
-/* Adds nothing; reads the accumulators: ms[ET_K_COUNT], launches[ET_K_COUNT]; then clears
- * them if `reset` is non-zero. */
+/* Reads the accumulators into ms[2 * ET_K_COUNT] and launches[2 * ET_K_COUNT]: entry
+ * kind + ET_K_COUNT * phase, phase 0 = launches on all T*L tokens (up to and including the
+ * compression stage), phase 1 = launches on the kept tokens; clears them if `reset` != 0. */
 int et_profile_read(et_encoder *enc, double *ms, int64_t *launches, int32_t reset);
 const char *et_kernel_name(int32_t kind);
 

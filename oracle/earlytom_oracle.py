@@ -240,6 +240,8 @@ def encode_clip(shape, w, frames, merge_layer, sim_threshold, keep_ratio,
             N, k = info["kept_idx"].shape
             x = info["tokens"].reshape(N, k, -1)
         if i < n_layers:
+            if x_at_merge is not None and 0 <= merge_layer and i < merge_layer:
+                continue                      # replaced at the merge layer anyway
             x = encoder_block(x, w["layers"][i], shape.n_heads, shape.ln_eps)
     if shape.has_final_ln:
         x = layer_norm(x, np.asarray(w["final_ln_g"], dtype), np.asarray(w["final_ln_b"], dtype),

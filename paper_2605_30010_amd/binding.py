@@ -320,10 +320,12 @@ def et_profile_enable(handle, on):
 
 
 def et_profile_read(handle, reset=True):
-    ms = (C.c_double * ET_K_COUNT)()
-    cnt = (C.c_int64 * ET_K_COUNT)()
+    """Returns {(kind, phase): (milliseconds, launches)}; phase 0 = on all tokens, 1 = on kept tokens."""
+    ms = (C.c_double * (2 * ET_K_COUNT))()
+    cnt = (C.c_int64 * (2 * ET_K_COUNT))()
     _check(load_library().et_profile_read(handle, ms, cnt, int(bool(reset))))
-    return {KERNEL_KINDS[i]: (float(ms[i]), int(cnt[i])) for i in range(ET_K_COUNT)}
+    return {(KERNEL_KINDS[i % ET_K_COUNT], i // ET_K_COUNT): (float(ms[i]), int(cnt[i]))
+            for i in range(2 * ET_K_COUNT)}
 
 
 def et_kernel_name(kind):

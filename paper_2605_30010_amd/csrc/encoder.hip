@@ -251,6 +251,7 @@ int et_encode_clip(et_encoder *e, const float *frames_dev, int32_t T, int32_t me
   const int L = e->L, D = e->D;
   const EncWs w = carve_encoder(e, workspace_dev, T);
   e->prof.kinds.clear();
+  e->prof.phase = 0;
 
   // patch embedding: x = patches * Wp^T + bp + pos_emb[l]
   ET_TIMED(ET_K_IM2COL, launch_im2col(frames_dev, T, c.channels, c.image_h, c.image_w, c.patch, e->Kp_pad,
@@ -287,6 +288,7 @@ int et_encode_clip(et_encoder *e, const float *frames_dev, int32_t T, int32_t me
       rows = n_seg * k;
       max_len = k;
       cu = out->cu_tokens_dev;
+      e->prof.phase = 1;
     }
     if (i < c.n_layers) {
       int rc = run_block(e, e->layers[i], w, rows, cu, n_frames, max_len, s);
@@ -315,7 +317,7 @@ int et_profile_enable(et_encoder *e, int32_t on) {
 
 int et_profile_read(et_encoder *e, double *ms, int64_t *launches, int32_t reset) {
   ET_REQUIRE(e && ms && launches, "a pointer argument is NULL");
-  for (int i = 0; i < ET_K_COUNT; ++i) {
+  for (int i = 0; i < 2 * ET_K_COUNT; ++i) {
     ms[i] = e->prof.ms[i];
     launches[i] = e->prof.launches[i];
     if (reset) { e->prof.ms[i] = 0; e->prof.launches[i] = 0; }

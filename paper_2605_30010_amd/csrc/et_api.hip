@@ -88,7 +88,7 @@ int Profiler::begin(int kind, hipStream_t s) {
     ET_HIP(hipEventCreate(&e));
     pool.push_back(e);
   }
-  kinds.push_back(kind);
+  kinds.push_back(kind + ET_K_COUNT * phase);
   ET_HIP(hipEventRecord(pool[2 * (kinds.size() - 1)], s));
   return ET_OK;
 }

@@ -106,9 +106,10 @@ inline int nv_for(int D) { return (D + 511) / 512; }
 struct Profiler {
   bool on = false;
   std::vector<hipEvent_t> pool;
-  std::vector<int> kinds;          // kind of the i-th bracket; its events are pool[2i], pool[2i+1]
-  double ms[ET_K_COUNT] = {0};
-  int64_t launches[ET_K_COUNT] = {0};
+  std::vector<int> kinds;          // slot of the i-th bracket; its events are pool[2i], pool[2i+1]
+  int phase = 0;                   // 0: before the compression stage (and the stage itself), 1: after
+  double ms[2 * ET_K_COUNT] = {0}; // slot = kind + ET_K_COUNT * phase
+  int64_t launches[2 * ET_K_COUNT] = {0};
 
   int begin(int kind, hipStream_t s);
   int end(hipStream_t s);
