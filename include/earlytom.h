@@ -174,10 +174,19 @@ int et_layernorm(const uint16_t *x_dev, const float *gamma_dev, const float *bet
 /* C[M, N] = A[M, K] * W[N, K]^T + bias, bf16 in / fp32 accumulate / bf16 out, with an
  * epilogue: 0 bias only, 1 bias + GELU-tanh, 2 bias + residual (res_dev bf16 [M, N], may
  * alias c_dev).  bias_dev float32 [N].  Standalone form for tests: any M >= 1, N and K
- * multiples of 8; allocates and frees padded copies of the operands itself and synchronises. */
+ * multiples of 8; allocates and frees padded copies of the operands itself and synchronises.
+ * tile_config: -1 = the library's choice, else a tiling listed at et_gemm_tune. */
 int et_gemm_bf16(const uint16_t *a_dev, const uint16_t *w_dev, const float *bias_dev,
                  const uint16_t *res_dev, int32_t M, int32_t N, int32_t K, int32_t epilogue,
-                 uint16_t *c_dev, void *hip_stream);
+                 int32_t tile_config, uint16_t *c_dev, void *hip_stream);
+
+/* Times `iters` back-to-back launches of the GEMM above on library-allocated operands of the
+ * given logical shape with HIP events; *avg_ms (HOST) receives the mean milliseconds per
+ * launch.  tile_config selects a workgroup tiling (0: 128x128, 1: 256x128, 2: 256x256 with 8
+ * wavefronts, 3: 256x128 with 8 wavefronts, 4: 128x256, 5: 256x256 with 4 wavefronts;
+ * -1: the library's own choice).  For tuning sweeps; allocates, frees and synchronises. */
+int et_gemm_tune(int32_t M, int32_t N, int32_t K, int32_t epilogue, int32_t tile_config, int32_t iters,
+                 float *avg_ms, void *hip_stream);
 
 /* Per-frame multi-head attention on a fused projection buffer qkv_dev bf16 [rows, 3D]
  * (q | k | v, head h at columns h*hd): out_dev bf16 [rows, D].  cu_tokens_dev [n_frames+1]

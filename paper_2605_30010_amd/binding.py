@@ -69,7 +69,8 @@ def load_library():
         "et_topk_select": (C.c_int, [vp, i32, i32, i32, vp, vp]),
         "et_compact_tokens": (C.c_int, [vp, vp, i32, i32, i32, i32, vp, vp]),
         "et_layernorm": (C.c_int, [vp, vp, vp, f32, i32, i32, vp, vp]),
-        "et_gemm_bf16": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, vp, vp]),
+        "et_gemm_bf16": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp]),
+        "et_gemm_tune": (C.c_int, [i32, i32, i32, i32, i32, i32, C.POINTER(f32), vp]),
         "et_attention": (C.c_int, [vp, vp, i32, i32, i32, i32, vp, vp]),
         "et_encoder_create": (C.c_int, [C.POINTER(_Config), C.POINTER(_Weights), i32, C.POINTER(vp)]),
         "et_encoder_destroy": (None, [vp]),
@@ -226,7 +227,7 @@ def et_layernorm(x, gamma, beta, eps, stream=None):
     return y
 
 
-def et_gemm_bf16(a, w, bias, epilogue=0, residual=None, stream=None):
+def et_gemm_bf16(a, w, bias, epilogue=0, residual=None, tile_config=-1, stream=None):
     """C = A @ W.T + bias (+GELU-tanh | +residual).  a [M,K], w [N,K] bf16; bias fp32 [N]."""
     lib = load_library()
     _dev(a, torch.bfloat16, "a")
@@ -237,9 +238,17 @@ def et_gemm_bf16(a, w, bias, epilogue=0, residual=None, stream=None):
     M, K = a.shape
     N = w.shape[0]
     c = torch.empty((M, N), dtype=torch.bfloat16, device=a.device)
-    _check(lib.et_gemm_bf16(_ptr(a), _ptr(w), _ptr(bias), _ptr(residual), M, N, K, int(epilogue), _ptr(c),
+    _check(lib.et_gemm_bf16(_ptr(a), _ptr(w), _ptr(bias), _ptr(residual), M, N, K, int(epilogue), int(tile_config), _ptr(c),
                             _stream(stream)))
     return c
+
+
+def et_gemm_tune(M, N, K, epilogue=0, tile_config=-1, iters=20, stream=None):
+    """Mean milliseconds per launch of the GEMM kernel on library-allocated operands."""
+    ms = C.c_float(0.0)
+    _check(load_library().et_gemm_tune(M, N, K, int(epilogue), int(tile_config), int(iters), C.byref(ms),
+                                       _stream(stream)))
+    return float(ms.value)
 
 
 def et_attention(qkv, cu_tokens, max_len, n_heads, head_dim, stream=None):

@@ -13,6 +13,7 @@ namespace et {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 namespace {
 
@@ -24,6 +25,10 @@ __device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
 }
 
 __device__ __forceinline__ f32x16 mfma32(const uint4 &a, const uint4 &b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                 __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x16 mfma32(u32x4 a, u32x4 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
                                                  __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
@@ -131,6 +136,45 @@ __device__ __forceinline__ float gelu_tanh_f(float u) {
   return u / (1.0f + __expf(-y2));
 }
 
+// Epilogue shared by the GEMM kernels.  acc[a][b] is the 32 x 32 tile at rows n_base + 32a (MFMA
+// rows = output columns n) and columns m_base + 32b: the lane owns output row m = .. + r32 and,
+// per accumulator quad q, the four consecutive columns n = .. + 8q + 4grp + (0..3).
+template <int EPI, int FM, int FN>
+__device__ __forceinline__ void gemm_epilogue(f32x16 (&acc)[FN][FM], const GemmArgs &g, int m_base,
+                                              int n_base, int r32, int grp) {
+#pragma unroll
+  for (int b = 0; b < FM; ++b) {
+    const int m = m_base + b * 32 + r32;
+    if (m >= g.M) continue;
+    uint16_t *crow = g.C + (size_t)m * g.ldc;
+    const uint16_t *rrow = nullptr;
+    if (EPI == EPI_BIAS_RES) rrow = g.res + (size_t)(m % g.res_mod) * g.ldr;
+#pragma unroll
+    for (int a = 0; a < FN; ++a) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n = n_base + a * 32 + q * 8 + grp * 4;
+        if (n >= g.n_store) continue;
+        const float4 bi = *reinterpret_cast<const float4 *>(g.bias + n);
+        float v0 = acc[a][b][q * 4 + 0] + bi.x, v1 = acc[a][b][q * 4 + 1] + bi.y;
+        float v2 = acc[a][b][q * 4 + 2] + bi.z, v3 = acc[a][b][q * 4 + 3] + bi.w;
+        if (EPI == EPI_BIAS_GELU) {
+          v0 = gelu_tanh_f(v0); v1 = gelu_tanh_f(v1); v2 = gelu_tanh_f(v2); v3 = gelu_tanh_f(v3);
+        }
+        if (EPI == EPI_BIAS_RES) {
+          const uint2 rr = *reinterpret_cast<const uint2 *>(rrow + n);
+          v0 += bf16lo_to_f32(rr.x); v1 += bf16hi_to_f32(rr.x);
+          v2 += bf16lo_to_f32(rr.y); v3 += bf16hi_to_f32(rr.y);
+        }
+        uint2 o;
+        o.x = cvt_pk_bf16(v0, v1);
+        o.y = cvt_pk_bf16(v2, v3);
+        *reinterpret_cast<uint2 *>(crow + n) = o;
+      }
+    }
+  }
+}
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI>
 __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(GemmArgs g, int tiles_m, int tiles_n) {
   constexpr int NT = WAVES_M * WAVES_N * 64;
@@ -184,84 +228,232 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(GemmArgs g,
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
-  uint4 a_reg[A_CH], w_reg[W_CH];
+  u32x4 a_reg[A_CH], w_reg[W_CH];
 #pragma unroll
-  for (int i = 0; i < A_CH; ++i) a_reg[i] = *reinterpret_cast<const uint4 *>(a_src[i]);
+  for (int i = 0; i < A_CH; ++i) a_reg[i] = *reinterpret_cast<const u32x4 *>(a_src[i]);
 #pragma unroll
-  for (int i = 0; i < W_CH; ++i) w_reg[i] = *reinterpret_cast<const uint4 *>(w_src[i]);
+  for (int i = 0; i < W_CH; ++i) w_reg[i] = *reinterpret_cast<const u32x4 *>(w_src[i]);
 #pragma unroll
-  for (int i = 0; i < A_CH; ++i) *reinterpret_cast<uint4 *>(As + a_dst[i]) = a_reg[i];
+  for (int i = 0; i < A_CH; ++i) *reinterpret_cast<u32x4 *>(As + a_dst[i]) = a_reg[i];
 #pragma unroll
-  for (int i = 0; i < W_CH; ++i) *reinterpret_cast<uint4 *>(Ws + w_dst[i]) = w_reg[i];
+  for (int i = 0; i < W_CH; ++i) *reinterpret_cast<u32x4 *>(Ws + w_dst[i]) = w_reg[i];
   __syncthreads();
 
   const int kt_n = g.K / kBK;
   for (int kt = 0; kt < kt_n; ++kt) {
     const int cur = kt & 1;
-    if (kt + 1 < kt_n) {
-      const int ko = (kt + 1) * kBK;
+    // prefetch the next k-tile (the last iteration re-reads its own tile; that copy is unused)
+    const int ko = (kt + 1 < kt_n ? kt + 1 : kt) * kBK;
 #pragma unroll
-      for (int i = 0; i < A_CH; ++i) a_reg[i] = *reinterpret_cast<const uint4 *>(a_src[i] + ko);
+    for (int i = 0; i < A_CH; ++i) a_reg[i] = *reinterpret_cast<const u32x4 *>(a_src[i] + ko);
 #pragma unroll
-      for (int i = 0; i < W_CH; ++i) w_reg[i] = *reinterpret_cast<const uint4 *>(w_src[i] + ko);
-    }
+    for (int i = 0; i < W_CH; ++i) w_reg[i] = *reinterpret_cast<const u32x4 *>(w_src[i] + ko);
     const uint16_t *Ac = As + cur * BM * kLdsRow + (wm * WTM + r32) * kLdsRow + grp * 8;
     const uint16_t *Wc = Ws + cur * BN * kLdsRow + (wn * WTN + r32) * kLdsRow + grp * 8;
 #pragma unroll
     for (int ks = 0; ks < kBK / 16; ++ks) {
-      uint4 fa[FM], fw[FN];
+      u32x4 fa[FM], fw[FN];
 #pragma unroll
-      for (int b = 0; b < FM; ++b) fa[b] = *reinterpret_cast<const uint4 *>(Ac + b * 32 * kLdsRow + ks * 16);
+      for (int b = 0; b < FM; ++b) fa[b] = *reinterpret_cast<const u32x4 *>(Ac + b * 32 * kLdsRow + ks * 16);
 #pragma unroll
-      for (int a = 0; a < FN; ++a) fw[a] = *reinterpret_cast<const uint4 *>(Wc + a * 32 * kLdsRow + ks * 16);
+      for (int a = 0; a < FN; ++a) fw[a] = *reinterpret_cast<const u32x4 *>(Wc + a * 32 * kLdsRow + ks * 16);
 #pragma unroll
       for (int a = 0; a < FN; ++a)
 #pragma unroll
         for (int b = 0; b < FM; ++b) acc[a][b] = mfma32(fw[a], fa[b], acc[a][b]);
     }
-    if (kt + 1 < kt_n) {
-      uint16_t *An = As + (cur ^ 1) * BM * kLdsRow;
-      uint16_t *Wn = Ws + (cur ^ 1) * BN * kLdsRow;
+    uint16_t *An = As + (cur ^ 1) * BM * kLdsRow;
+    uint16_t *Wn = Ws + (cur ^ 1) * BN * kLdsRow;
 #pragma unroll
-      for (int i = 0; i < A_CH; ++i) *reinterpret_cast<uint4 *>(An + a_dst[i]) = a_reg[i];
+    for (int i = 0; i < A_CH; ++i) *reinterpret_cast<u32x4 *>(An + a_dst[i]) = a_reg[i];
 #pragma unroll
-      for (int i = 0; i < W_CH; ++i) *reinterpret_cast<uint4 *>(Wn + w_dst[i]) = w_reg[i];
-    }
+    for (int i = 0; i < W_CH; ++i) *reinterpret_cast<u32x4 *>(Wn + w_dst[i]) = w_reg[i];
     __syncthreads();
   }
 
-  // Epilogue: lane owns row m = .. + r32 and, per accumulator quad q, columns n = .. + 8q + 4grp + (0..3).
-#pragma unroll
-  for (int b = 0; b < FM; ++b) {
-    const int m = m0 + wm * WTM + b * 32 + r32;
-    if (m >= g.M) continue;
-    uint16_t *crow = g.C + (size_t)m * g.ldc;
-    const uint16_t *rrow = nullptr;
-    if (EPI == EPI_BIAS_RES) rrow = g.res + (size_t)(m % g.res_mod) * g.ldr;
-#pragma unroll
-    for (int a = 0; a < FN; ++a) {
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int n = n0 + wn * WTN + a * 32 + q * 8 + grp * 4;
-        if (n >= g.n_store) continue;
-        const float4 bi = *reinterpret_cast<const float4 *>(g.bias + n);
-        float v0 = acc[a][b][q * 4 + 0] + bi.x, v1 = acc[a][b][q * 4 + 1] + bi.y;
-        float v2 = acc[a][b][q * 4 + 2] + bi.z, v3 = acc[a][b][q * 4 + 3] + bi.w;
-        if (EPI == EPI_BIAS_GELU) {
-          v0 = gelu_tanh_f(v0); v1 = gelu_tanh_f(v1); v2 = gelu_tanh_f(v2); v3 = gelu_tanh_f(v3);
-        }
-        if (EPI == EPI_BIAS_RES) {
-          const uint2 rr = *reinterpret_cast<const uint2 *>(rrow + n);
-          v0 += bf16lo_to_f32(rr.x); v1 += bf16hi_to_f32(rr.x);
-          v2 += bf16lo_to_f32(rr.y); v3 += bf16hi_to_f32(rr.y);
-        }
-        uint2 o;
-        o.x = cvt_pk_bf16(v0, v1);
-        o.y = cvt_pk_bf16(v2, v3);
-        *reinterpret_cast<uint2 *>(crow + n) = o;
-      }
-    }
+  gemm_epilogue<EPI, FM, FN>(acc, g, m0 + wm * WTM, n0 + wn * WTN, r32, grp);
+}
+
+// ---------------------------------------------------------------------------------------
+// Same GEMM, operands brought in by direct global -> LDS loads (global_load_lds_dwordx4): no
+// staging registers and no LDS write instructions.  One wavefront load moves 64 x 16 bytes to
+// 1 KiB of consecutive LDS, i.e. 8 tile rows of 64 bf16; lane L lands at row L / 8, slot L % 8
+// and fetches the global 16-byte chunk (slot ^ swz(row)), an XOR swizzle that spreads the
+// MFMA fragment reads (same k-chunk, consecutive rows) over the banks.  STAGES k-tiles are in
+// flight (one per stage); waits are explicit (vmcnt) because the loads are asynchronous to the
+// wavefront: a tile is complete once this wavefront's loads have landed AND the workgroup barrier
+// after that wait has been passed.
+// ---------------------------------------------------------------------------------------
+#define ET_LDS_DMA16(gptr, lptr)                                                             \
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gptr),   \
+                                   (__attribute__((address_space(3))) void *)(lptr), 16, 0, 0)
+
+// Waits until at most N of this wavefront's vector-memory operations are outstanding.
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N <= 63, "vmcnt is a 6-bit counter");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, int EPI>
+__global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_dma_kernel(GemmArgs g, int tiles_m, int tiles_n) {
+  constexpr int NW = WAVES_M * WAVES_N;
+  constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
+  constexpr int FM = WTM / 32, FN = WTN / 32;
+  constexpr int CPR = BK / 8;                       // 16-byte chunks per tile row
+  constexpr int RPB = 64 / CPR;                     // tile rows per 1 KiB wavefront load
+  constexpr int SWZ = (BK == 64) ? 1 : 2;           // rows 2^SWZ apart share a bank base
+  constexpr int A_BLK = BM / RPB / NW, W_BLK = BN / RPB / NW;   // loads per wavefront per k-tile
+  constexpr int LOADS = A_BLK + W_BLK;
+  constexpr int STAGE_ELEMS = (BM + BN) * BK;
+  constexpr int KS = BK / 16;
+  static_assert(BK == 64 || BK == 32, "k-tile is 64 or 32");
+  static_assert(BM % (RPB * NW) == 0 && BN % (RPB * NW) == 0, "tile rows must split evenly over the wavefronts");
+  extern __shared__ __align__(16) uint16_t lds[];
+
+  const int nblk = tiles_m * tiles_n;
+  int bid = blockIdx.x;
+  {
+    const int per = nblk / 8, rem = nblk % 8, xcd = bid % 8, slot = bid / 8;
+    bid = xcd * per + (xcd < rem ? xcd : rem) + slot;
   }
+  const int tile_m = bid / tiles_n, tile_n = bid % tiles_n;
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+  const int r32 = lane & 31, grp = lane >> 5;
+
+  // global source of this lane for each of the wavefront's loads (advanced by BK elements per k-tile)
+  const uint16_t *a_src[A_BLK];
+  const uint16_t *w_src[W_BLK];
+  const int lrow = lane / CPR, lslot = lane % CPR;
+#pragma unroll
+  for (int i = 0; i < A_BLK; ++i) {
+    const int row = (wave * A_BLK + i) * RPB + lrow;
+    int m = m0 + row;
+    if (m >= g.M) m = g.M - 1;
+    a_src[i] = g.A + (size_t)m * g.lda + ((lslot ^ ((row >> SWZ) & (CPR - 1))) * 8);
+  }
+#pragma unroll
+  for (int i = 0; i < W_BLK; ++i) {
+    const int row = (wave * W_BLK + i) * RPB + lrow;
+    w_src[i] = g.W + (size_t)(n0 + row) * g.K + ((lslot ^ ((row >> SWZ) & (CPR - 1))) * 8);
+  }
+  auto issue = [&](int stage, int kt) {
+    uint16_t *as = lds + stage * STAGE_ELEMS;
+    uint16_t *ws = as + BM * BK;
+    const int ko = kt * BK;
+#pragma unroll
+    for (int i = 0; i < A_BLK; ++i) ET_LDS_DMA16(a_src[i] + ko, as + (wave * A_BLK + i) * 512);
+#pragma unroll
+    for (int i = 0; i < W_BLK; ++i) ET_LDS_DMA16(w_src[i] + ko, ws + (wave * W_BLK + i) * 512);
+  };
+
+  // fragment read offsets (elements): row R, k-chunk (2 ks + grp) lives at slot chunk ^ swz(R)
+  const int fx = (r32 >> SWZ) & (CPR - 1);
+  int koff[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) koff[ks] = (((2 * ks + grp) ^ fx) * 8);
+  const int a_row = (wm * WTM + r32) * BK, w_row = (wn * WTN + r32) * BK;
+
+  f32x16 acc[FN][FM];
+#pragma unroll
+  for (int a = 0; a < FN; ++a)
+#pragma unroll
+    for (int b = 0; b < FM; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+
+  const int kt_n = g.K / BK;
+  // prologue: every stage gets a tile (tiles past the end re-read the last one; never used)
+#pragma unroll
+  for (int st = 0; st < STAGES; ++st) issue(st, st < kt_n ? st : kt_n - 1);
+
+  // Fragments are double-buffered in registers: the LDS reads of k-step s+1 are issued under the
+  // MFMAs of step s, also across k-tiles (the one barrier per tile sits before the tile's last step).
+  u32x4 fa[2][FM], fw[2][FN];
+  auto read_frags = [&](int buf, int stage, int ks) {
+    const uint16_t *as = lds + stage * STAGE_ELEMS;
+    const uint16_t *ws = as + BM * BK;
+#pragma unroll
+    for (int b = 0; b < FM; ++b) fa[buf][b] = *reinterpret_cast<const u32x4 *>(as + a_row + b * 32 * BK + koff[ks]);
+#pragma unroll
+    for (int a = 0; a < FN; ++a) fw[buf][a] = *reinterpret_cast<const u32x4 *>(ws + w_row + a * 32 * BK + koff[ks]);
+  };
+  auto mfma_step = [&](int buf) {
+#pragma unroll
+    for (int a = 0; a < FN; ++a)
+#pragma unroll
+      for (int b = 0; b < FM; ++b) acc[a][b] = mfma32(fw[buf][a], fa[buf][b], acc[a][b]);
+  };
+  // scheduling hint for one step: alternate MFMA / LDS read until the reads are placed
+  auto interleave = [&]() {
+#pragma unroll
+    for (int i = 0; i < FM + FN; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, FM * FN - (FM + FN), 0);
+  };
+
+  wait_vmcnt<(STAGES - 1) * LOADS>();    // tile 0 has landed
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  read_frags(0, 0, 0);
+
+  for (int kt = 0; kt < kt_n; ++kt) {
+    const int stage = kt % STAGES;
+#pragma unroll
+    for (int ks = 0; ks < KS - 1; ++ks) {
+      read_frags((ks + 1) & 1, stage, ks + 1);
+      mfma_step(ks & 1);
+      interleave();
+    }
+    // last step of tile kt: tile kt+1 must have landed (at most STAGES-2 newer tiles outstanding) and
+    // this wavefront's reads of tile kt must have returned before its stage is handed to the loads
+    wait_vmcnt<(STAGES - 2) * LOADS>();
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    {
+      const int nk = kt + STAGES;
+      issue(stage, nk < kt_n ? nk : kt_n - 1);
+    }
+    read_frags(KS & 1, (kt + 1) % STAGES, 0);
+    mfma_step((KS - 1) & 1);
+    interleave();
+  }
+  wait_vmcnt<0>();                     // drain the padding loads before the workgroup's LDS is released
+  gemm_epilogue<EPI, FM, FN>(acc, g, m0 + wm * WTM, n0 + wn * WTN, r32, grp);
+}
+
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES>
+int launch_gemm_dma_cfg(const GemmArgs &g, hipStream_t s) {
+  constexpr int NT = WAVES_M * WAVES_N * 64;
+  constexpr size_t lds_bytes = (size_t)STAGES * (BM + BN) * BK * sizeof(uint16_t);
+  static_assert(lds_bytes <= 160 * 1024, "LDS budget");
+  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.n_store + BN - 1) / BN;
+  const dim3 grid(tiles_m * tiles_n), block(NT);
+#define ET_GEMM_LAUNCH(E)                                                                        \
+  {                                                                                              \
+    auto kern = gemm_dma_kernel<BM, BN, BK, WAVES_M, WAVES_N, STAGES, E>;                        \
+    static bool attr_set = false;                                                                \
+    if (!attr_set) {                                                                             \
+      ET_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                           \
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));   \
+      attr_set = true;                                                                           \
+    }                                                                                            \
+    hipLaunchKernelGGL(kern, grid, block, lds_bytes, s, g, tiles_m, tiles_n);                    \
+  }
+  switch (g.epilogue) {
+    case EPI_BIAS: ET_GEMM_LAUNCH(EPI_BIAS); break;
+    case EPI_BIAS_GELU: ET_GEMM_LAUNCH(EPI_BIAS_GELU); break;
+    case EPI_BIAS_RES: ET_GEMM_LAUNCH(EPI_BIAS_RES); break;
+    default: set_error("unknown epilogue %d", g.epilogue); return ET_ERR_INVALID_ARG;
+  }
+#undef ET_GEMM_LAUNCH
+  ET_LAUNCH_CHECK();
+  return ET_OK;
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N>
@@ -472,20 +664,46 @@ int launch_im2col(const float *frames, int T, int C, int H, int W, int P, int Kp
   return ET_OK;
 }
 
-int launch_gemm(const GemmArgs &g, hipStream_t s) {
+int gemm_config_count() { return 16; }
+
+static int launch_gemm_id(const GemmArgs &g, hipStream_t s, int cfg) {
+  switch (cfg) {
+    case 0: return launch_gemm_cfg<128, 128, 2, 2>(g, s);
+    case 1: return launch_gemm_cfg<256, 128, 2, 2>(g, s);
+    case 2: return launch_gemm_cfg<256, 256, 2, 4>(g, s);
+    case 3: return launch_gemm_cfg<256, 128, 2, 4>(g, s);
+    case 4: return launch_gemm_cfg<128, 256, 2, 2>(g, s);
+    case 5: return launch_gemm_cfg<256, 256, 2, 2>(g, s);
+    case 6: return launch_gemm_dma_cfg<256, 256, 64, 2, 4, 2>(g, s);
+    case 7: return launch_gemm_dma_cfg<256, 256, 32, 2, 4, 4>(g, s);
+    case 8: return launch_gemm_dma_cfg<128, 128, 64, 2, 2, 2>(g, s);
+    case 9: return launch_gemm_dma_cfg<128, 128, 32, 2, 2, 4>(g, s);
+    case 10: return launch_gemm_dma_cfg<128, 128, 32, 2, 2, 3>(g, s);
+    case 11: return launch_gemm_dma_cfg<256, 128, 64, 2, 2, 3>(g, s);
+    case 12: return launch_gemm_dma_cfg<256, 256, 32, 2, 2, 4>(g, s);
+    case 13: return launch_gemm_dma_cfg<256, 128, 32, 2, 4, 4>(g, s);
+    case 14: return launch_gemm_dma_cfg<256, 256, 32, 2, 4, 3>(g, s);
+    case 15: return launch_gemm_dma_cfg<256, 128, 32, 2, 2, 4>(g, s);
+    default: set_error("unknown gemm tile configuration %d", cfg); return ET_ERR_INVALID_ARG;
+  }
+}
+
+int launch_gemm(const GemmArgs &g, hipStream_t s, int force_cfg) {
   if (g.M <= 0) return ET_OK;
-  if (g.K % kBK != 0 || g.n_store % 4 != 0) {
+  if (g.K % 64 != 0 || g.n_store % 4 != 0) {
     set_error("gemm: K = %d must be a multiple of 64 and n_store = %d of 4", g.K, g.n_store);
     return ET_ERR_INVALID_ARG;
   }
-  // Large problems: 256 x 256 tiles when N divides evenly, else 256 x 128; small M falls back
-  // to 128 x 128 so that the launch still covers the 256 compute units.
-  const long tiles_big = (long)((g.M + 255) / 256) * ((g.n_store + 127) / 128);
-  if (tiles_big >= 512) {
-    if (g.n_store % 256 == 0) return launch_gemm_cfg<256, 256, 2, 4>(g, s);
-    return launch_gemm_cfg<256, 128, 2, 2>(g, s);
-  }
-  return launch_gemm_cfg<128, 128, 2, 2>(g, s);
+  if (force_cfg >= 0) return launch_gemm_id(g, s, force_cfg);
+  // Tile choice by a cost model in units of one 256 x 256 tile time.  256 x 256 workgroups run
+  // one per compute unit; 128 x 128 ones run two per compute unit (each then at about 0.6 of a
+  // big tile's time) or alone (0.3) when there are no more tiles than compute units.
+  const long t256 = (long)((g.M + 255) / 256) * ((g.n_store + 255) / 256);
+  const long t128 = (long)((g.M + 127) / 128) * ((g.n_store + 127) / 128);
+  const double cost256 = (double)((t256 + 255) / 256);
+  const double cost128 = t128 <= 256 ? 0.3 : 0.6 * (double)((t128 + 511) / 512);
+  if (cost256 <= cost128) return launch_gemm_id(g, s, 6);
+  return launch_gemm_id(g, s, t128 <= 256 ? 9 : 8);
 }
 
 bool head_dim_supported(int hd) {

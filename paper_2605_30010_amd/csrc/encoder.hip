@@ -352,7 +352,9 @@ int et_attention(const uint16_t *qkv_dev, const int32_t *cu_tokens_dev, int32_t 
 }
 
 int et_gemm_bf16(const uint16_t *a_dev, const uint16_t *w_dev, const float *bias_dev, const uint16_t *res_dev,
-                 int32_t M, int32_t N, int32_t K, int32_t epilogue, uint16_t *c_dev, void *hip_stream) {
+                 int32_t M, int32_t N, int32_t K, int32_t epilogue, int32_t tile_config, uint16_t *c_dev,
+                 void *hip_stream) {
+  ET_REQUIRE(tile_config >= -1 && tile_config < gemm_config_count(), "tile_config = %d unknown", tile_config);
   ET_REQUIRE(a_dev && w_dev && bias_dev && c_dev, "a pointer argument is NULL");
   ET_REQUIRE(M >= 1 && N >= 8 && K >= 8 && N % 8 == 0 && K % 8 == 0, "M = %d, N = %d, K = %d out of range", M, N, K);
   ET_REQUIRE(epilogue >= 0 && epilogue <= 2, "epilogue = %d unknown", epilogue);
@@ -383,12 +385,65 @@ int et_gemm_bf16(const uint16_t *a_dev, const uint16_t *w_dev, const float *bias
   }
   if (rc == ET_OK) {
     GemmArgs g{a, Kp, w, b, res_dev, N, M, c_dev, N, M, N, Kp, epilogue};
-    rc = launch_gemm(g, s);
+    rc = launch_gemm(g, s, tile_config);
   }
   hipError_t se = hipStreamSynchronize(s);
   if (rc == ET_OK && se != hipSuccess) rc = hip_fail(se, "hipStreamSynchronize", __FILE__, __LINE__);
   if (a) (void)hipFree(a);
   if (w) (void)hipFree(w);
+  if (b) (void)hipFree(b);
+  return rc;
+}
+
+
+int et_gemm_tune(int32_t M, int32_t N, int32_t K, int32_t epilogue, int32_t tile_config, int32_t iters,
+                 float *avg_ms, void *hip_stream) {
+  ET_REQUIRE(avg_ms != nullptr, "avg_ms is NULL");
+  ET_REQUIRE(M >= 1 && N >= 8 && K >= 8 && N % 8 == 0 && K % 8 == 0, "M = %d, N = %d, K = %d out of range", M, N, K);
+  ET_REQUIRE(epilogue >= 0 && epilogue <= 2, "epilogue = %d unknown", epilogue);
+  ET_REQUIRE(iters >= 1 && iters <= 10000, "iters = %d outside [1, 10000]", iters);
+  ET_REQUIRE(tile_config >= -1 && tile_config < gemm_config_count(), "tile_config = %d unknown", tile_config);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const int Kp = round_up(K, 64), Np = round_up(N, 256);
+  uint16_t *a = nullptr, *w = nullptr, *c = nullptr;
+  float *b = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  int rc = ET_OK;
+  auto step = [&](hipError_t err, const char *what) {
+    if (rc == ET_OK && err != hipSuccess) rc = hip_fail(err, what, __FILE__, __LINE__);
+  };
+  step(hipMalloc((void **)&a, (size_t)M * Kp * 2), "hipMalloc a");
+  step(hipMalloc((void **)&w, (size_t)Np * Kp * 2), "hipMalloc w");
+  step(hipMalloc((void **)&c, (size_t)M * Np * 2), "hipMalloc c");
+  step(hipMalloc((void **)&b, (size_t)Np * 4), "hipMalloc bias");
+  if (rc == ET_OK) {
+    // 0x3C15 = bf16 0.0091..., finite everywhere; timing does not depend on the values
+    step(hipMemsetD16Async((hipDeviceptr_t)a, 0x3C15, (size_t)M * Kp, s), "fill a");
+    step(hipMemsetD16Async((hipDeviceptr_t)w, 0x3C15, (size_t)Np * Kp, s), "fill w");
+    step(hipMemsetD16Async((hipDeviceptr_t)c, 0x3C15, (size_t)M * Np, s), "fill c");
+    step(hipMemsetAsync(b, 0, (size_t)Np * 4, s), "fill bias");
+    step(hipEventCreate(&e0), "hipEventCreate");
+    step(hipEventCreate(&e1), "hipEventCreate");
+  }
+  if (rc == ET_OK) {
+    GemmArgs g{a, Kp, w, b, c, N, M, c, N, M, N, Kp, epilogue};
+    rc = launch_gemm(g, s, tile_config);                       // warm-up, also sets attributes
+    if (rc == ET_OK) step(hipEventRecord(e0, s), "hipEventRecord");
+    for (int i = 0; i < iters && rc == ET_OK; ++i) rc = launch_gemm(g, s, tile_config);
+    if (rc == ET_OK) step(hipEventRecord(e1, s), "hipEventRecord");
+  }
+  hipError_t se = hipStreamSynchronize(s);
+  if (rc == ET_OK && se != hipSuccess) rc = hip_fail(se, "hipStreamSynchronize", __FILE__, __LINE__);
+  if (rc == ET_OK) {
+    float ms = 0.f;
+    step(hipEventElapsedTime(&ms, e0, e1), "hipEventElapsedTime");
+    *avg_ms = ms / (float)iters;
+  }
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  if (a) (void)hipFree(a);
+  if (w) (void)hipFree(w);
+  if (c) (void)hipFree(c);
   if (b) (void)hipFree(b);
   return rc;
 }

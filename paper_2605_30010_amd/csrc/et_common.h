@@ -170,7 +170,8 @@ struct GemmArgs {
   uint16_t *C; int ldc;
   int M, n_store, K, epilogue;
 };
-int launch_gemm(const GemmArgs &g, hipStream_t s);
+int launch_gemm(const GemmArgs &g, hipStream_t s, int force_cfg = -1);
+int gemm_config_count();
 int launch_attention(const uint16_t *qkv, const int32_t *cu, int n_frames, int max_len, int n_heads,
                      int head_dim, uint16_t *out, hipStream_t s);
 bool head_dim_supported(int hd);

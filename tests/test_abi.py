@@ -118,8 +118,9 @@ def test_single_step_entry_points_reject_bad_arguments():
     assert lib.et_segment_scan(fake, 4, math.nan, fake, fake, None) == -1
     assert lib.et_compact_tokens(fake, fake, 2, 8, 64, 9, fake, None) == -1
     assert lib.et_layernorm(fake, fake, fake, 1e-6, 4, 12, fake, None) == -1
-    assert lib.et_gemm_bf16(fake, fake, fake, None, 4, 64, 64, 2, fake, None) == -1   # residual missing
-    assert lib.et_gemm_bf16(fake, fake, fake, None, 4, 60, 64, 0, fake, None) == -1
+    assert lib.et_gemm_bf16(fake, fake, fake, None, 4, 64, 64, 2, -1, fake, None) == -1   # residual missing
+    assert lib.et_gemm_bf16(fake, fake, fake, None, 4, 60, 64, 0, -1, fake, None) == -1
+    assert lib.et_gemm_bf16(fake, fake, fake, None, 4, 64, 64, 0, 99, fake, None) == -1
     assert lib.et_attention(fake, fake, 2, 8, 4, 20, fake, None) == -5
     assert lib.et_attention(None, fake, 2, 8, 4, 16, fake, None) == -1
 

@@ -61,6 +61,27 @@ def test_gemm_matches_oracle(M, N, K, epi):
     assert rel_l2(got, ref) < 4e-3
 
 
+@pytest.mark.parametrize("cfg", list(range(16)))
+def test_gemm_every_tile_configuration(cfg):
+    """Each workgroup tiling, on a shape with ragged M, several k-tiles and a partial N tile."""
+    rng = np.random.default_rng(cfg)
+    M, N, K = 777, 1160, 448
+    a_bits, a = _bf(rng, (M, K))
+    w_bits, w = _bf(rng, (N, K), scale=0.05)
+    bias = (0.1 * rng.standard_normal(N)).astype(np.float32)
+    r_bits, r = _bf(rng, (M, N))
+    ref = O.gelu_tanh(a @ w.T + bias.astype(np.float64))
+    c = et.et_gemm_bf16(bits_to_dev(a_bits), bits_to_dev(w_bits), torch.from_numpy(bias).cuda(), 1,
+                        tile_config=cfg)
+    got = dev_to_f64(c)
+    assert np.max(np.abs(got - ref) - 2 ** -8 * np.abs(ref)) < 5e-4
+    assert rel_l2(got, ref) < 4e-3
+    ref2 = a @ w.T + bias.astype(np.float64) + r
+    c2 = et.et_gemm_bf16(bits_to_dev(a_bits), bits_to_dev(w_bits), torch.from_numpy(bias).cuda(), 2,
+                         residual=bits_to_dev(r_bits), tile_config=cfg)
+    assert rel_l2(dev_to_f64(c2), ref2) < 4e-3
+
+
 def test_gemm_residual_in_place():
     rng = np.random.default_rng(5)
     M, N, K = 333, 128, 64
@@ -73,7 +94,7 @@ def test_gemm_residual_in_place():
     import ctypes as C
     a_d, w_d = bits_to_dev(a_bits), bits_to_dev(w_bits)
     rc = lib.et_gemm_bf16(C.c_void_p(a_d.data_ptr()), C.c_void_p(w_d.data_ptr()), C.c_void_p(bias.data_ptr()),
-                          C.c_void_p(res.data_ptr()), M, N, K, 2, C.c_void_p(res.data_ptr()),
+                          C.c_void_p(res.data_ptr()), M, N, K, 2, -1, C.c_void_p(res.data_ptr()),
                           C.c_void_p(torch.cuda.current_stream().cuda_stream))
     assert rc == 0, et.et_last_error()
     assert rel_l2(dev_to_f64(res), a @ w.T + r) < 4e-3
