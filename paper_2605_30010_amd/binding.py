@@ -72,6 +72,8 @@ def load_library():
         "et_gemm_bf16": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp]),
         "et_gemm_tune": (C.c_int, [i32, i32, i32, i32, i32, i32, C.POINTER(f32), vp]),
         "et_attention": (C.c_int, [vp, vp, i32, i32, i32, i32, vp, vp]),
+        "et_attention_uniform": (C.c_int, [vp, i32, i32, i32, i32, vp, sz, vp, vp]),
+        "et_attention_uniform_scratch_bytes": (sz, [i32, i32, i32, i32]),
         "et_encoder_create": (C.c_int, [C.POINTER(_Config), C.POINTER(_Weights), i32, C.POINTER(vp)]),
         "et_encoder_destroy": (None, [vp]),
         "et_workspace_bytes": (sz, [vp, i32]),
@@ -259,6 +261,21 @@ def et_attention(qkv, cu_tokens, max_len, n_heads, head_dim, stream=None):
     out = torch.empty((rows, n_heads * head_dim), dtype=torch.bfloat16, device=qkv.device)
     _check(lib.et_attention(_ptr(qkv), _ptr(cu_tokens), cu_tokens.numel() - 1, int(max_len), n_heads,
                             head_dim, _ptr(out), _stream(stream)))
+    return out
+
+
+def et_attention_uniform_scratch_bytes(n_frames, length, n_heads, head_dim):
+    return int(load_library().et_attention_uniform_scratch_bytes(n_frames, length, n_heads, head_dim))
+
+
+def et_attention_uniform(qkv, n_frames, length, n_heads, head_dim, stream=None):
+    lib = load_library()
+    _dev(qkv, torch.bfloat16, "qkv")
+    need = et_attention_uniform_scratch_bytes(n_frames, length, n_heads, head_dim)
+    scratch = torch.empty((max(need, 1),), dtype=torch.uint8, device=qkv.device)
+    out = torch.empty((qkv.shape[0], n_heads * head_dim), dtype=torch.bfloat16, device=qkv.device)
+    _check(lib.et_attention_uniform(_ptr(qkv), n_frames, int(length), n_heads, head_dim, _ptr(scratch),
+                                    scratch.numel(), _ptr(out), _stream(stream)))
     return out
 
 

@@ -643,6 +643,216 @@ __global__ __launch_bounds__(kAttWaves * 64) void attention_kernel(
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// Fast attention path for frames of equal length (always the case on the hot path).
+//
+// Step 1, transpose_v_kernel: V^T per (frame, head) as vt[frame][head][d][Lpad], Lpad = length
+// rounded up to 64, tokens past the length written as zeros.  MFMA wants the contraction index
+// (the key) contiguous per lane for the P V product; doing the transpose once per layer in a
+// bandwidth-bound pass removes all 2-byte LDS scatter writes from the attention loop.
+//
+// Step 2, attention_dma_kernel: same transposed online-softmax scheme as attention_kernel, but
+// K and V^T tiles are brought in by direct global -> LDS loads, double buffered, one barrier per
+// 64-key tile.  K rows sit back to back in LDS (row stride = head_dim * 2 bytes; 144 bytes for
+// head_dim 72 spreads 16-byte reads of consecutive rows over all banks); V^T rows are 128 bytes
+// with the 16-byte slots XOR-swizzled by (row >> 1) & 7.  When head_dim is not a multiple of 16
+// the last contraction chunk of a K row runs 16 bytes into the next row; those values meet the
+// zero padding of Q, and the data behind the last row is the (finite) V^T tile.
+// ---------------------------------------------------------------------------------------
+template <int HD>
+__global__ __launch_bounds__(256) void transpose_v_kernel(const uint16_t *__restrict__ qkv, int n, int n_heads,
+                                                          int Lpad, uint16_t *__restrict__ vt) {
+  constexpr int NCH = HD / 8;
+  constexpr int TROW = HD + 2;                          // 2-byte pad: column reads spread over banks
+  __shared__ uint16_t tile[64 * TROW];
+  const int f = blockIdx.z, h = blockIdx.y, t0 = blockIdx.x * 64;
+  const int D = n_heads * HD, ld = 3 * D;
+  const uint16_t *vbase = qkv + (size_t)f * n * ld + 2 * D + h * HD;
+  for (int i = threadIdx.x; i < 64 * NCH; i += 256) {
+    const int tok = i / NCH, ch = i % NCH;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (t0 + tok < n) v = *reinterpret_cast<const uint4 *>(vbase + (size_t)(t0 + tok) * ld + ch * 8);
+    uint32_t *dst = reinterpret_cast<uint32_t *>(tile + tok * TROW + ch * 8);   // 4-byte aligned: TROW even
+    dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+  }
+  __syncthreads();
+  uint16_t *obase = vt + ((size_t)(f * n_heads + h) * HD) * Lpad + t0;
+  for (int i = threadIdx.x; i < HD * 8; i += 256) {
+    const int d = i / 8, tc = i % 8;
+    uint32_t w[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t lo = tile[(tc * 8 + 2 * j) * TROW + d], hi = tile[(tc * 8 + 2 * j + 1) * TROW + d];
+      w[j] = lo | (hi << 16);
+    }
+    *reinterpret_cast<uint4 *>(obase + (size_t)d * Lpad + tc * 8) = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+}
+
+template <int HD>
+__global__ __launch_bounds__(kAttWaves * 64) void attention_dma_kernel(
+    const uint16_t *__restrict__ qkv, const uint16_t *__restrict__ vt, int n, int n_heads, int Lpad,
+    float scale_log2, uint16_t *__restrict__ out) {
+  constexpr int NC = (HD + 15) / 16;
+  constexpr int NDB = (HD + 31) / 32;
+  constexpr int K_LOADS = HD / 8;            // 1 KiB loads per K tile  (64 keys * HD * 2 bytes)
+  constexpr int V_LOADS = HD / 8;            // 1 KiB loads per V^T tile (HD rows * 128 bytes)
+  constexpr int K_ELEMS = kAttBKV * HD, V_ELEMS = HD * kAttBKV;
+  constexpr int STAGE = K_ELEMS + V_ELEMS;
+  // tail pad: O^T row blocks past head_dim read rows behind the V^T tile; whatever they hold only
+  // reaches accumulator rows >= head_dim, which are never stored (MFMA output rows are independent)
+  constexpr int PAD = (NDB * 32 - HD) * kAttBKV;
+  __shared__ __align__(16) uint16_t lds[2 * STAGE + PAD];
+
+  const int f = blockIdx.z, h = blockIdx.y, q0 = blockIdx.x * kAttBQ;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r32 = lane & 31, grp = lane >> 5;
+  const int D = n_heads * HD, ld = 3 * D;
+  const uint16_t *qbase = qkv + (size_t)f * n * ld + h * HD;
+  const uint16_t *kbase = qbase + D;
+  const uint16_t *vtb = vt + ((size_t)(f * n_heads + h) * HD) * Lpad;
+
+  // loads j = wave, wave + 4, ... < K_LOADS + V_LOADS belong to this wavefront
+  auto issue = [&](int stage, int kv0) {
+    uint16_t *ks = lds + stage * STAGE;
+    uint16_t *vs = ks + K_ELEMS;
+#pragma unroll
+    for (int j = 0; j < (K_LOADS + V_LOADS + kAttWaves - 1) / kAttWaves; ++j) {
+      const int ld_id = j * kAttWaves + wave;
+      if (ld_id < K_LOADS) {
+        const int q = ld_id * 64 + lane, key = q / (HD / 8), ch = q % (HD / 8);
+        int kk = kv0 + key;
+        if (kk >= n) kk = n - 1;                       // clamp: masked later, stays in bounds
+        ET_LDS_DMA16(kbase + (size_t)kk * ld + ch * 8, ks + ld_id * 512);
+      } else if (ld_id < K_LOADS + V_LOADS) {
+        const int vl = ld_id - K_LOADS;
+        const int q = vl * 64 + lane, d = q >> 3, slot = q & 7;
+        ET_LDS_DMA16(vtb + (size_t)d * Lpad + kv0 + ((slot ^ ((d >> 1) & 7)) * 8), vs + vl * 512);
+      }
+    }
+  };
+
+  issue(0, 0);
+
+  u32x4 qf[NC];
+  {
+    const int q = q0 + wave * 32 + r32;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      const int d = c * 16 + grp * 8;
+      if (q < n && d < HD) qf[c] = *reinterpret_cast<const u32x4 *>(qbase + (size_t)q * ld + d);
+      else qf[c] = u32x4{0u, 0u, 0u, 0u};
+    }
+  }
+  f32x16 o_acc[NDB];
+#pragma unroll
+  for (int b = 0; b < NDB; ++b)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o_acc[b][i] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;        // m_run in raw logit units
+  const int vfx = (r32 >> 1) & 7;              // swizzle of this lane's V^T rows (32 b + r32: same low bits)
+
+  const int n_tiles = (n + kAttBKV - 1) / kAttBKV;
+  for (int t = 0; t < n_tiles; ++t) {
+    const int kv0 = t * kAttBKV;
+    wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();              // tile t is in LDS; everyone is done with tile t-1
+    asm volatile("" ::: "memory");
+    if (t + 1 < n_tiles) issue((t + 1) & 1, kv0 + kAttBKV);
+    const uint16_t *ks = lds + (t & 1) * STAGE;
+    const uint16_t *vs = ks + K_ELEMS;
+
+    f32x16 s_acc[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s_acc[kb][i] = 0.f;
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        const u32x4 kf = *reinterpret_cast<const u32x4 *>(ks + (kb * 32 + r32) * HD + c * 16 + grp * 8);
+        s_acc[kb] = mfma32(kf, qf[c], s_acc[kb]);
+      }
+    }
+    if (kv0 + kAttBKV > n) {                   // only the last tile can hold keys past the frame
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int key = kv0 + kb * 32 + (i >> 2) * 8 + grp * 4 + (i & 3);
+          if (key >= n) s_acc[kb][i] = -INFINITY;
+        }
+    }
+    float m_tile = s_acc[0][0];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) m_tile = fmaxf(m_tile, s_acc[kb][i]);
+    m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32, 64));
+    const float m_new = fmaxf(m_run, m_tile);
+    if (__any(m_new > m_run)) {                // rescale only when some query's maximum moved
+      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2);
+      l_run *= alpha;
+#pragma unroll
+      for (int b = 0; b < NDB; ++b)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o_acc[b][i] *= alpha;
+      m_run = m_new;
+    }
+    const float mc = m_run * scale_log2;
+    float l_tile = 0.f;
+    u32x4 pf[4];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      float p[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        p[i] = __builtin_amdgcn_exp2f(fmaf(s_acc[kb][i], scale_log2, -mc));
+        l_tile += p[i];
+      }
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh) {
+        u32x4 v;
+        v.x = cvt_pk_bf16(p[hh * 8 + 0], p[hh * 8 + 1]); v.y = cvt_pk_bf16(p[hh * 8 + 2], p[hh * 8 + 3]);
+        v.z = cvt_pk_bf16(p[hh * 8 + 4], p[hh * 8 + 5]); v.w = cvt_pk_bf16(p[hh * 8 + 6], p[hh * 8 + 7]);
+        pf[kb * 2 + hh] = v;
+      }
+    }
+    l_run += l_tile;
+    // O^T += V^T P^T.  P's k-slots of chunk c are keys 16c + 4 grp + (0..3) and 16c + 8 + 4 grp + (0..3):
+    // two 8-byte reads from 16-byte slots 2c and 2c + 1 of the V^T row, offset 8 grp bytes.
+#pragma unroll
+    for (int b = 0; b < NDB; ++b) {
+      const uint16_t *vrow = vs + (b * 32 + r32) * kAttBKV + grp * 4;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const uint2 lo = *reinterpret_cast<const uint2 *>(vrow + (((2 * c) ^ vfx) * 8));
+        const uint2 hi = *reinterpret_cast<const uint2 *>(vrow + (((2 * c + 1) ^ vfx) * 8));
+        const u32x4 vf = u32x4{lo.x, lo.y, hi.x, hi.y};
+        o_acc[b] = mfma32(vf, pf[c], o_acc[b]);
+      }
+    }
+  }
+
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const float inv = 1.0f / l_tot;
+  const int q = q0 + wave * 32 + r32;
+  if (q < n) {
+    uint16_t *orow = out + ((size_t)f * n + q) * D + h * HD;
+#pragma unroll
+    for (int b = 0; b < NDB; ++b)
+#pragma unroll
+      for (int qd = 0; qd < 4; ++qd) {
+        const int d = b * 32 + qd * 8 + grp * 4;
+        if (d < HD) {
+          uint2 o;
+          o.x = cvt_pk_bf16(o_acc[b][qd * 4 + 0] * inv, o_acc[b][qd * 4 + 1] * inv);
+          o.y = cvt_pk_bf16(o_acc[b][qd * 4 + 2] * inv, o_acc[b][qd * 4 + 3] * inv);
+          *reinterpret_cast<uint2 *>(orow + d) = o;
+        }
+      }
+  }
+}
+
 }  // namespace
 
 int launch_layernorm(const uint16_t *x, const float *g, const float *b, float eps, int rows, int D,
@@ -717,6 +927,34 @@ int launch_attention(const uint16_t *qkv, const int32_t *cu, int n_frames, int m
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)head_dim);
 #define ET_ATT(HD) \
   case HD: hipLaunchKernelGGL(attention_kernel<HD>, grid, block, 0, s, qkv, cu, n_heads, scale_log2, out); break;
+  switch (head_dim) {
+    ET_ATT(16) ET_ATT(32) ET_ATT(64) ET_ATT(72) ET_ATT(80) ET_ATT(96) ET_ATT(128)
+    default: set_error("head_dim %d is not instantiated", head_dim); return ET_ERR_UNSUPPORTED;
+  }
+#undef ET_ATT
+  ET_LAUNCH_CHECK();
+  return ET_OK;
+}
+
+size_t attention_uniform_workspace_bytes(int n_frames, int len, int n_heads, int head_dim) {
+  const size_t Lpad = (size_t)(len + 63) / 64 * 64;
+  return (size_t)n_frames * n_heads * head_dim * Lpad * sizeof(uint16_t);
+}
+
+bool attention_uniform_supported(int head_dim) { return head_dim == 72 || head_dim == 64 || head_dim == 128 || head_dim == 16 || head_dim == 32 || head_dim == 80 || head_dim == 96; }
+
+int launch_attention_uniform(const uint16_t *qkv, int n_frames, int len, int n_heads, int head_dim,
+                             uint16_t *vt_ws, uint16_t *out, hipStream_t s) {
+  if (n_frames <= 0 || len <= 0) return ET_OK;
+  const int Lpad = (len + 63) / 64 * 64;
+  const dim3 tgrid(Lpad / 64, n_heads, n_frames), agrid((len + kAttBQ - 1) / kAttBQ, n_heads, n_frames);
+  const float scale_log2 = 1.4426950408889634f / sqrtf((float)head_dim);
+#define ET_ATT(HD)                                                                                        \
+  case HD:                                                                                                \
+    hipLaunchKernelGGL(transpose_v_kernel<HD>, tgrid, dim3(256), 0, s, qkv, len, n_heads, Lpad, vt_ws);   \
+    hipLaunchKernelGGL(attention_dma_kernel<HD>, agrid, dim3(kAttWaves * 64), 0, s, qkv, vt_ws, len,      \
+                       n_heads, Lpad, scale_log2, out);                                                   \
+    break;
   switch (head_dim) {
     ET_ATT(16) ET_ATT(32) ET_ATT(64) ET_ATT(72) ET_ATT(80) ET_ATT(96) ET_ATT(128)
     default: set_error("head_dim %d is not instantiated", head_dim); return ET_ERR_UNSUPPORTED;

@@ -74,7 +74,7 @@ static int upload_f32(et_encoder *e, const float *src, int n, int n_pad, float *
 }
 
 struct EncWs {
-  uint16_t *x, *xn, *qkv, *att, *hid;
+  uint16_t *x, *xn, *qkv, *att, *hid, *vt;
   int32_t *cu_full;
   void *merge;
   size_t bytes;
@@ -96,6 +96,7 @@ static EncWs carve_encoder(const et_encoder *e, void *ws, int T) {
   w.att = static_cast<uint16_t *>(take(R * e->D * 2));
   const size_t hid_cols = (size_t)(e->Mhp > e->Kp_pad ? e->Mhp : e->Kp_pad);
   w.hid = static_cast<uint16_t *>(take(R * hid_cols * 2));
+  w.vt = static_cast<uint16_t *>(take(attention_uniform_workspace_bytes(T, e->L, e->cfg.n_heads, e->hd)));
   w.cu_full = static_cast<int32_t *>(take((size_t)(T + 1) * 4));
   w.merge = take(carve_merge(nullptr, T, e->L, e->D).bytes);
   w.bytes = off;
@@ -112,7 +113,8 @@ static int run_block(et_encoder *e, const LayerDev &lw, const EncWs &w, int rows
   GemmArgs g;
   g = GemmArgs{w.xn, D, lw.wqkv, lw.bqkv, nullptr, 0, 1, w.qkv, 3 * D, rows, 3 * D, D, EPI_BIAS};
   ET_TIMED(ET_K_GEMM_QKV, launch_gemm(g, s));
-  ET_TIMED(ET_K_ATTENTION, launch_attention(w.qkv, cu, n_frames, max_len, c.n_heads, e->hd, w.att, s));
+  (void)cu;   // every frame has max_len tokens on this path
+  ET_TIMED(ET_K_ATTENTION, launch_attention_uniform(w.qkv, n_frames, max_len, c.n_heads, e->hd, w.vt, w.att, s));
   g = GemmArgs{w.att, D, lw.wo, lw.bo, w.x, D, rows, w.x, D, rows, D, D, EPI_BIAS_RES};
   ET_TIMED(ET_K_GEMM_OUT, launch_gemm(g, s));
   ET_TIMED(ET_K_LAYERNORM, launch_layernorm(w.x, lw.ln2_g, lw.ln2_b, c.ln_eps, rows, D, w.xn, s));
@@ -349,6 +351,31 @@ int et_attention(const uint16_t *qkv_dev, const int32_t *cu_tokens_dev, int32_t 
   }
   return launch_attention(qkv_dev, cu_tokens_dev, n_frames, max_len, n_heads, head_dim, out_dev,
                           static_cast<hipStream_t>(hip_stream));
+}
+
+size_t et_attention_uniform_scratch_bytes(int32_t n_frames, int32_t len, int32_t n_heads, int32_t head_dim) {
+  if (n_frames < 1 || len < 1 || n_heads < 1 || !head_dim_supported(head_dim)) return 0;
+  return attention_uniform_workspace_bytes(n_frames, len, n_heads, head_dim);
+}
+
+int et_attention_uniform(const uint16_t *qkv_dev, int32_t n_frames, int32_t len, int32_t n_heads,
+                         int32_t head_dim, void *scratch_dev, size_t scratch_bytes, uint16_t *out_dev,
+                         void *hip_stream) {
+  ET_REQUIRE(qkv_dev && scratch_dev && out_dev, "a pointer argument is NULL");
+  ET_REQUIRE(n_frames >= 0 && len >= 0 && n_heads >= 1, "n_frames/len/n_heads out of range");
+  if (!head_dim_supported(head_dim)) {
+    set_error("head_dim = %d is not instantiated (16, 32, 64, 72, 80, 96, 128)", head_dim);
+    return ET_ERR_UNSUPPORTED;
+  }
+  ET_REQUIRE((double)n_frames * len * n_heads * head_dim * 3 < 2.0e9, "qkv exceeds 2^31 elements");
+  if (n_frames == 0 || len == 0) return ET_OK;
+  const size_t need = attention_uniform_workspace_bytes(n_frames, len, n_heads, head_dim);
+  if (scratch_bytes < need) {
+    set_error("scratch of %zu bytes is smaller than the %zu needed", scratch_bytes, need);
+    return ET_ERR_WORKSPACE;
+  }
+  return launch_attention_uniform(qkv_dev, n_frames, len, n_heads, head_dim, static_cast<uint16_t *>(scratch_dev),
+                                  out_dev, static_cast<hipStream_t>(hip_stream));
 }
 
 int et_gemm_bf16(const uint16_t *a_dev, const uint16_t *w_dev, const float *bias_dev, const uint16_t *res_dev,

@@ -135,3 +135,26 @@ def test_attention_matches_oracle(n_heads, hd):
     # a one-token frame attends to itself only: output = its own v, exactly
     one = int(cu[lens.index(1)])
     assert np.array_equal(got[one], qkv_s[one, 2 * D:])
+
+
+@pytest.mark.parametrize("n_heads,hd,n_frames,length", [(16, 72, 3, 729), (16, 72, 5, 364), (16, 72, 2, 182),
+                                                        (4, 16, 8, 64), (4, 16, 2, 32), (2, 64, 3, 130),
+                                                        (2, 128, 2, 70), (3, 32, 2, 1), (2, 80, 2, 129),
+                                                        (2, 96, 2, 65), (16, 72, 1, 218)])
+def test_attention_uniform_matches_oracle(n_heads, hd, n_frames, length):
+    rng = np.random.default_rng(n_heads * hd + length)
+    D, rows = n_heads * hd, n_frames * length
+    _, qkv = _bf(rng, (rows, 3 * D))
+    qkv[:, :D] *= 2.0
+    bits = f32_to_bf16_bits(qkv.astype(np.float32))
+    qkv = bf16_bits_to_f32(bits).astype(np.float64)
+    cu = (np.arange(n_frames + 1) * length).astype(np.int32)
+    ref = _attention_ref(qkv, cu, n_heads, hd)
+    out = et.et_attention_uniform(bits_to_dev(bits), n_frames, length, n_heads, hd)
+    got = dev_to_f64(out)
+    assert np.all(np.isfinite(got))
+    assert rel_l2(got, ref) < 6e-3
+    assert np.max(np.abs(got - ref)) < 0.05
+    # the general (ragged) kernel agrees on the same input
+    gen = et.et_attention(bits_to_dev(bits), torch.from_numpy(cu).cuda(), length, n_heads, hd)
+    assert rel_l2(dev_to_f64(gen), got) < 6e-3
