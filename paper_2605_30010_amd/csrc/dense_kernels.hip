@@ -295,8 +295,8 @@ __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, int EPI>
-__global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_dma_kernel(GemmArgs g, int tiles_m, int tiles_n) {
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, int MINB, int EPI>
+__global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_dma_kernel(GemmArgs g, int tiles_m, int tiles_n) {
   constexpr int NW = WAVES_M * WAVES_N;
   constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
   constexpr int FM = WTM / 32, FN = WTN / 32;
@@ -427,7 +427,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_dma_kernel(GemmArg
   gemm_epilogue<EPI, FM, FN>(acc, g, m0 + wm * WTM, n0 + wn * WTN, r32, grp);
 }
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, int MINB = 1>
 int launch_gemm_dma_cfg(const GemmArgs &g, hipStream_t s) {
   constexpr int NT = WAVES_M * WAVES_N * 64;
   constexpr size_t lds_bytes = (size_t)STAGES * (BM + BN) * BK * sizeof(uint16_t);
@@ -436,7 +436,7 @@ int launch_gemm_dma_cfg(const GemmArgs &g, hipStream_t s) {
   const dim3 grid(tiles_m * tiles_n), block(NT);
 #define ET_GEMM_LAUNCH(E)                                                                        \
   {                                                                                              \
-    auto kern = gemm_dma_kernel<BM, BN, BK, WAVES_M, WAVES_N, STAGES, E>;                        \
+    auto kern = gemm_dma_kernel<BM, BN, BK, WAVES_M, WAVES_N, STAGES, MINB, E>;                        \
     static bool attr_set = false;                                                                \
     if (!attr_set) {                                                                             \
       ET_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                           \
@@ -874,7 +874,7 @@ int launch_im2col(const float *frames, int T, int C, int H, int W, int P, int Kp
   return ET_OK;
 }
 
-int gemm_config_count() { return 16; }
+int gemm_config_count() { return 20; }
 
 static int launch_gemm_id(const GemmArgs &g, hipStream_t s, int cfg) {
   switch (cfg) {
@@ -894,6 +894,10 @@ static int launch_gemm_id(const GemmArgs &g, hipStream_t s, int cfg) {
     case 13: return launch_gemm_dma_cfg<256, 128, 32, 2, 4, 4>(g, s);
     case 14: return launch_gemm_dma_cfg<256, 256, 32, 2, 4, 3>(g, s);
     case 15: return launch_gemm_dma_cfg<256, 128, 32, 2, 2, 4>(g, s);
+    case 16: return launch_gemm_dma_cfg<256, 128, 32, 2, 2, 3, 2>(g, s);
+    case 17: return launch_gemm_dma_cfg<256, 128, 32, 2, 2, 2, 2>(g, s);
+    case 18: return launch_gemm_dma_cfg<128, 256, 32, 2, 2, 3, 2>(g, s);
+    case 19: return launch_gemm_dma_cfg<256, 128, 64, 2, 2, 2, 1>(g, s);
     default: set_error("unknown gemm tile configuration %d", cfg); return ET_ERR_INVALID_ARG;
   }
 }

@@ -444,10 +444,10 @@ int et_gemm_tune(int32_t M, int32_t N, int32_t K, int32_t epilogue, int32_t tile
   step(hipMalloc((void **)&c, (size_t)M * Np * 2), "hipMalloc c");
   step(hipMalloc((void **)&b, (size_t)Np * 4), "hipMalloc bias");
   if (rc == ET_OK) {
-    // 0x3C15 = bf16 0.0091..., finite everywhere; timing does not depend on the values
-    step(hipMemsetD16Async((hipDeviceptr_t)a, 0x3C15, (size_t)M * Kp, s), "fill a");
-    step(hipMemsetD16Async((hipDeviceptr_t)w, 0x3C15, (size_t)Np * Kp, s), "fill w");
-    step(hipMemsetD16Async((hipDeviceptr_t)c, 0x3C15, (size_t)M * Np, s), "fill c");
+    // pseudo-random finite values: switching activity (hence clocks under power limits) depends on the data
+    if (rc == ET_OK) rc = launch_fill_random_bf16(a, (size_t)M * Kp, 1u, s);
+    if (rc == ET_OK) rc = launch_fill_random_bf16(w, (size_t)Np * Kp, 2u, s);
+    if (rc == ET_OK) rc = launch_fill_random_bf16(c, (size_t)M * Np, 3u, s);
     step(hipMemsetAsync(b, 0, (size_t)Np * 4, s), "fill bias");
     step(hipEventCreate(&e0), "hipEventCreate");
     step(hipEventCreate(&e1), "hipEventCreate");

@@ -153,6 +153,8 @@ int launch_compact(const uint16_t *merged, const int32_t *kept, int n_rows_max,
 int launch_identity_maps(int T, int L, int32_t *kept, int32_t *cu_tokens, int32_t *seg_start,
                          hipStream_t s);
 int launch_cu_uniform(int n, int step, int32_t *cu, hipStream_t s);
+// Fills with bf16 values in (-1, 1) from a counter hash (benchmark operands only).
+int launch_fill_random_bf16(uint16_t *p, size_t n, uint32_t seed, hipStream_t s);
 
 // ---- launchers implemented in dense_kernels.hip ----
 int launch_layernorm(const uint16_t *x, const float *g, const float *b, float eps, int rows, int D,

@@ -310,6 +310,16 @@ __global__ void cu_uniform_kernel(int n, int step, int32_t *cu) {
   if (i <= n) cu[i] = i * step;
 }
 
+__global__ void fill_random_bf16_kernel(uint16_t *p, size_t n, uint32_t seed) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+    uint32_t h = (uint32_t)i * 2654435761u ^ (seed * 0x9E3779B9u) ^ (uint32_t)(i >> 32);
+    h ^= h >> 15; h *= 2246822519u; h ^= h >> 13; h *= 3266489917u; h ^= h >> 16;
+    // sign 1 bit, exponent 0x70..0x7E (2^-15 .. 2^-1), mantissa 7 bits
+    const uint32_t e = 0x70u + (h >> 8) % 15u;
+    p[i] = (uint16_t)(((h & 1u) << 15) | (e << 7) | ((h >> 1) & 0x7Fu));
+  }
+}
+
 }  // namespace
 
 int launch_similarity(const uint16_t *x, int T, int L, int D, float *cos_out, hipStream_t s) {
@@ -366,6 +376,13 @@ int launch_identity_maps(int T, int L, int32_t *kept, int32_t *cu_tokens, int32_
   int n = T * L > T + 1 ? T * L : T + 1;
   hipLaunchKernelGGL(identity_maps_kernel, dim3((n + 255) / 256), dim3(256), 0, s, T, L, kept,
                      cu_tokens, seg_start);
+  ET_LAUNCH_CHECK();
+  return ET_OK;
+}
+
+int launch_fill_random_bf16(uint16_t *p, size_t n, uint32_t seed, hipStream_t s) {
+  if (n == 0) return ET_OK;
+  hipLaunchKernelGGL(fill_random_bf16_kernel, dim3(4096), dim3(256), 0, s, p, n, seed);
   ET_LAUNCH_CHECK();
   return ET_OK;
 }

@@ -156,3 +156,84 @@ def test_siglip_shape_8_frames_stagewise(siglip8):
     assert got["n_tokens"] == got["n_frames_out"] * 364
     print("config 2: rel-L2 %.4g, safe margins %s" % (err, safe))
     enc.close()
+
+
+# ------------------------------------------------------------------ full-size workloads
+
+@pytest.fixture(scope="module")
+def siglip_weights(siglip8):
+    # one set of SigLIP-shaped weights serves every full-size case (generating 415 M values takes ~15 s)
+    return siglip8["weights"]
+
+
+def _full_size_check(name, w, variant_range, sample_segments=2, keep=None, m=None):
+    """Whole-clip decisions bit-exact (oracle fed the GPU's hidden states at the merge layer);
+    tokens of a few sampled output frames against the oracle continued from those states; one
+    short segment end to end from pixels."""
+    for variant in variant_range:
+        rec = build_workload(name, variant=variant, with_weights=False)
+        shape, frames, T = rec["shape"], rec["frames"], rec["T"]
+        m_ = rec["merge_layer"] if m is None else m
+        keep_ = rec["keep_ratio"] if keep is None else keep
+        tau = rec["sim_threshold"]
+        L, D = shape.tokens_per_frame, shape.d_model
+        trunc = _truncated(shape, w, m_, T)
+        xm = _encode(trunc, frames, -1, 0.0, 1.0)["tokens"]
+        trunc.close()
+        x_gpu = bf16_bits_to_f32(dev_to_bits(xm)).astype(np.float64).reshape(T, L, D)
+        st = O.merge_select(x_gpu, tau, np.float32(keep_))
+        k = st["k"]
+        gaps_ok = all((np.sort(z)[::-1][k - 1] - np.sort(z)[::-1][k]) >= 1e-5 * np.sort(z)[::-1][k - 1]
+                      for z in st["score"])
+        if np.min(np.abs(st["frame_sim"] - tau)) >= 1e-2 and gaps_ok:
+            break
+    else:
+        pytest.fail("no variant with safe decision margins")
+    enc = et.Encoder(shape, w, T)
+    got = _encode(enc, frames, m_, tau, keep_)
+    enc.close()
+    truth = np.concatenate([[0], np.cumsum(rec["lengths"])]).tolist()
+    assert st["seg_start"].tolist() == truth
+    assert got["seg_start"].tolist() == truth
+    assert got["cu_tokens"].tolist() == st["cu_tokens"].tolist()
+    assert np.array_equal(got["kept_idx"].cpu().numpy(), st["kept_idx"].reshape(-1))
+    np.testing.assert_allclose(got["frame_sim"].cpu().numpy(), st["frame_sim"], atol=5e-6, rtol=0)
+    N = got["n_frames_out"]
+    tok = dev_to_f64(got["tokens"]).reshape(N, k, D)
+    assert np.all(np.isfinite(tok))
+    # sampled output frames: remaining blocks + final LayerNorm on the oracle side
+    lens = np.diff(st["seg_start"])
+    picks = sorted(set([int(np.argmax(lens)), int(np.argmin(lens)), N - 1]))[:sample_segments + 1]
+    worst = 0.0
+    for n in picks:
+        x = st["tokens"].reshape(N, k, D)[n:n + 1]
+        for lw in w["layers"][m_:]:
+            x = O.encoder_block(x, lw, shape.n_heads, shape.ln_eps)
+        x = O.layer_norm(x, w["final_ln_g"].astype(np.float64), w["final_ln_b"].astype(np.float64),
+                         shape.ln_eps)
+        err = rel_l2(tok[n], x[0])
+        worst = max(worst, err)
+        assert err <= TOL, (n, err)
+    # one short segment fully end to end (pixels -> tokens) with the decisions forced to the GPU's
+    n = int(np.argmin(lens))
+    a, b = int(st["seg_start"][n]), int(st["seg_start"][n + 1])
+    ref = O.encode_clip(shape, w, frames[a:b], m_, -np.inf, np.float32(keep_),
+                        force_kept=st["kept_idx"][n:n + 1])
+    e2e = rel_l2(tok[n], ref["tokens"])
+    assert e2e <= TOL, e2e
+    print("%s variant %d: N=%d k=%d, sampled-frame rel-L2 <= %.4g, end-to-end rel-L2 %.4g"
+          % (name, variant, N, k, worst, e2e))
+
+
+def test_full_size_32_frame_clip(siglip_weights):
+    """Config 3 at the size and launch configuration bench.py times (32 x 729 tokens, merge after 8)."""
+    _full_size_check("c3_siglip_t32", siglip_weights, range(0, 6))
+
+
+def test_full_size_32_frame_clip_other_settings(siglip_weights):
+    _full_size_check("c3_siglip_t32", siglip_weights, range(0, 6), keep=0.25, m=4, sample_segments=1)
+
+
+def test_full_size_64_frame_clip(siglip_weights):
+    """Config 4: 64 frames, noisier scenes with abrupt cuts, merge after 4 blocks, keep 0.25."""
+    _full_size_check("c4_siglip_t64", siglip_weights, range(0, 6), sample_segments=1)
