@@ -83,7 +83,7 @@ def main():
     ap.add_argument("--merge-layer", type=int, default=None)
     ap.add_argument("--keep-ratio", type=float, default=None)
     ap.add_argument("--variant", type=int, default=0)
-    ap.add_argument("--cpu-frames", type=int, default=4)
+    ap.add_argument("--cpu-frames", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile-pass", action="store_true")
     args = ap.parse_args()
