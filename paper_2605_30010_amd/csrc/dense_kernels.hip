@@ -132,8 +132,12 @@ constexpr int kLdsRow = kBK + 8;   // 144-byte row stride: 16-byte reads of 16 r
 
 __device__ __forceinline__ float gelu_tanh_f(float u) {
   // 0.5 u (1 + tanh(y)) = u / (1 + exp(-2y)),  y = sqrt(2/pi) (u + 0.044715 u^3)
-  const float y2 = 1.5957691216057308f * (u + 0.044715f * u * u * u);
-  return u / (1.0f + __expf(-y2));
+  // exp(-2y) = exp2(u (c1 + c3 u^2)) with the factor -2 log2(e) sqrt(2/pi) folded into c1, c3;
+  // hardware exp2 and reciprocal (1 ulp) are ample for a result that is rounded to bf16.
+  const float c1 = -2.0f * 1.4426950408889634f * 0.7978845608028654f;
+  const float c3 = c1 * 0.044715f;
+  const float t = u * fmaf(u * u, c3, c1);
+  return u * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(t));
 }
 
 // Epilogue shared by the GEMM kernels.  acc[a][b] is the 32 x 32 tile at rows n_base + 32a (MFMA
@@ -171,6 +175,70 @@ __device__ __forceinline__ void gemm_epilogue(f32x16 (&acc)[FN][FM], const GemmA
         o.y = cvt_pk_bf16(v2, v3);
         *reinterpret_cast<uint2 *>(crow + n) = o;
       }
+    }
+  }
+}
+
+// Epilogue for wavefront tiles 64 columns wide, staged through a private 4 KiB LDS slice per
+// wavefront so that every global access is a full 128-byte row segment (8 lanes x 16 bytes)
+// instead of 8-byte pieces scattered over 32 rows.  Per 32-row block: (residual only) the
+// residual block is fetched coalesced into the slice; each lane then adds bias (+GELU | +its
+// residual values read back from the slice) in fp32, rounds once to bf16 and writes its 4-column
+// pieces to the slice; finally the slice is read row-wise and stored.  16-byte slots of a row are
+// XOR-swizzled by (row >> 1) & 7.  LDS operations of one wavefront execute in order, so the phases
+// need no barrier.
+template <int EPI, int FM, int FN>
+__device__ __forceinline__ void gemm_epilogue_lds(f32x16 (&acc)[FN][FM], const GemmArgs &g, int m_base,
+                                                  int n_base, int lane, uint16_t *slice) {
+  static_assert(FN == 2, "the staged epilogue handles 64-column wavefront tiles");
+  const int r32 = lane & 31, grp = lane >> 5;
+  const int prow = lane >> 3, pch = lane & 7;                 // row-wise phase: 8 rows x 8 chunks per pass
+  const int n_lane = n_base + pch * 8;
+  const bool n_ok = n_lane < g.n_store;                       // n_store is a multiple of 8 on this path
+  const int wsw = (r32 >> 1) & 7;
+#pragma unroll
+  for (int b = 0; b < FM; ++b) {
+    const int mb = m_base + b * 32;
+    if (mb >= g.M) break;                                     // wave-uniform: whole block past the last row
+    if (EPI == EPI_BIAS_RES) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int row = j * 8 + prow, m = mb + row;
+        u32x4 rv = u32x4{0u, 0u, 0u, 0u};
+        if (m < g.M && n_ok)
+          rv = *reinterpret_cast<const u32x4 *>(g.res + (size_t)(m % g.res_mod) * g.ldr + n_lane);
+        *reinterpret_cast<u32x4 *>(slice + row * 64 + ((pch ^ ((row >> 1) & 7)) * 8)) = rv;
+      }
+    }
+#pragma unroll
+    for (int a = 0; a < FN; ++a) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n = n_base + a * 32 + q * 8 + grp * 4;
+        float4 bi = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (n < g.n_store) bi = *reinterpret_cast<const float4 *>(g.bias + n);
+        float v0 = acc[a][b][q * 4 + 0] + bi.x, v1 = acc[a][b][q * 4 + 1] + bi.y;
+        float v2 = acc[a][b][q * 4 + 2] + bi.z, v3 = acc[a][b][q * 4 + 3] + bi.w;
+        if (EPI == EPI_BIAS_GELU) {
+          v0 = gelu_tanh_f(v0); v1 = gelu_tanh_f(v1); v2 = gelu_tanh_f(v2); v3 = gelu_tanh_f(v3);
+        }
+        uint2 *cell = reinterpret_cast<uint2 *>(slice + r32 * 64 + (((a * 4 + q) ^ wsw) * 8) + grp * 4);
+        if (EPI == EPI_BIAS_RES) {
+          const uint2 rr = *cell;
+          v0 += bf16lo_to_f32(rr.x); v1 += bf16hi_to_f32(rr.x);
+          v2 += bf16lo_to_f32(rr.y); v3 += bf16hi_to_f32(rr.y);
+        }
+        uint2 o;
+        o.x = cvt_pk_bf16(v0, v1);
+        o.y = cvt_pk_bf16(v2, v3);
+        *cell = o;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int row = j * 8 + prow, m = mb + row;
+      const u32x4 v = *reinterpret_cast<const u32x4 *>(slice + row * 64 + ((pch ^ ((row >> 1) & 7)) * 8));
+      if (m < g.M && n_ok) *reinterpret_cast<u32x4 *>(g.C + (size_t)m * g.ldc + n_lane) = v;
     }
   }
 }
@@ -425,6 +493,214 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_dma_kernel(G
   }
   wait_vmcnt<0>();                     // drain the padding loads before the workgroup's LDS is released
   gemm_epilogue<EPI, FM, FN>(acc, g, m0 + wm * WTM, n0 + wn * WTN, r32, grp);
+}
+
+// ---------------------------------------------------------------------------------------
+// Persistent form of the kernel above: one workgroup per compute-unit slot walks over its output
+// tiles t = b, b + G, b + 2G, ... and treats their k-tiles as ONE stream through the LDS stages,
+// so the loads of the next output tile are already in flight (and its first fragments already in
+// registers) while the finished tile's epilogue runs.  That removes the per-tile prologue latency
+// and the workgroup relaunch between tiles.
+// ---------------------------------------------------------------------------------------
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, int MINB, int EPI>
+__global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kernel(GemmArgs g, int tiles_m, int tiles_n) {
+  constexpr int NW = WAVES_M * WAVES_N;
+  constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
+  constexpr int FM = WTM / 32, FN = WTN / 32;
+  constexpr int CPR = BK / 8;
+  constexpr int RPB = 64 / CPR;
+  constexpr int SWZ = (BK == 64) ? 1 : 2;
+  constexpr int A_BLK = BM / RPB / NW, W_BLK = BN / RPB / NW;
+  constexpr int LOADS = A_BLK + W_BLK;
+  constexpr int STAGE_ELEMS = (BM + BN) * BK;
+  constexpr int KS = BK / 16;
+  static_assert(BK == 64 || BK == 32, "k-tile is 64 or 32");
+  static_assert(BM % (RPB * NW) == 0 && BN % (RPB * NW) == 0, "tile rows must split evenly over the wavefronts");
+  extern __shared__ __align__(16) uint16_t lds[];
+
+  const int n_tiles = tiles_m * tiles_n;
+  const int G = gridDim.x;
+  const int n_my = (n_tiles - (int)blockIdx.x + G - 1) / G;       // >= 1: the grid never exceeds n_tiles
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+  const int r32 = lane & 31, grp = lane >> 5;
+  const int lrow = lane / CPR, lslot = lane % CPR;
+
+  // j-th tile of this workgroup.  Within a round of G tiles each XCD (blockIdx % 8) takes a
+  // contiguous run, n fastest, so tiles sharing an activation row block meet in one L2.
+  auto tile_of = [&](int j, int &m0, int &n0) {
+    const int base = j * G;
+    const int cnt = (n_tiles - base < G) ? (n_tiles - base) : G;
+    const int per = cnt / 8, rem = cnt % 8, xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
+    const int t = base + xcd * per + (xcd < rem ? xcd : rem) + slot;
+    m0 = (t / tiles_n) * BM;
+    n0 = (t % tiles_n) * BN;
+  };
+
+  const uint16_t *a_src[A_BLK];
+  const uint16_t *w_src[W_BLK];
+  auto set_load_tile = [&](int j) {
+    int m0, n0;
+    tile_of(j, m0, n0);
+#pragma unroll
+    for (int i = 0; i < A_BLK; ++i) {
+      const int row = (wave * A_BLK + i) * RPB + lrow;
+      int m = m0 + row;
+      if (m >= g.M) m = g.M - 1;
+      a_src[i] = g.A + (size_t)m * g.lda + ((lslot ^ ((row >> SWZ) & (CPR - 1))) * 8);
+    }
+#pragma unroll
+    for (int i = 0; i < W_BLK; ++i) {
+      const int row = (wave * W_BLK + i) * RPB + lrow;
+      w_src[i] = g.W + (size_t)(n0 + row) * g.K + ((lslot ^ ((row >> SWZ) & (CPR - 1))) * 8);
+    }
+  };
+  const int kt_n = g.K / BK;
+  int load_tile = 0, load_kt = 0;                   // next k-tile of the stream to be fetched
+  auto issue_next = [&](int stage) {
+    uint16_t *as = lds + stage * STAGE_ELEMS;
+    uint16_t *ws = as + BM * BK;
+    const int ko = load_kt * BK;
+#pragma unroll
+    for (int i = 0; i < A_BLK; ++i) ET_LDS_DMA16(a_src[i] + ko, as + (wave * A_BLK + i) * 512);
+#pragma unroll
+    for (int i = 0; i < W_BLK; ++i) ET_LDS_DMA16(w_src[i] + ko, ws + (wave * W_BLK + i) * 512);
+    if (++load_kt == kt_n) {                        // past the stream's end the last k-tile is re-read (unused)
+      if (load_tile + 1 < n_my) {
+        load_kt = 0;
+        set_load_tile(++load_tile);
+      } else {
+        load_kt = kt_n - 1;
+      }
+    }
+  };
+
+  const int fx = (r32 >> SWZ) & (CPR - 1);
+  int koff[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) koff[ks] = (((2 * ks + grp) ^ fx) * 8);
+  const int a_row = (wm * WTM + r32) * BK, w_row = (wn * WTN + r32) * BK;
+
+  f32x16 acc[FN][FM];
+#pragma unroll
+  for (int a = 0; a < FN; ++a)
+#pragma unroll
+    for (int b = 0; b < FM; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+
+  set_load_tile(0);
+#pragma unroll
+  for (int st = 0; st < STAGES; ++st) issue_next(st);
+
+  u32x4 fa[2][FM], fw[2][FN];
+  auto read_frags = [&](int buf, int stage, int ks) {
+    const uint16_t *as = lds + stage * STAGE_ELEMS;
+    const uint16_t *ws = as + BM * BK;
+#pragma unroll
+    for (int b = 0; b < FM; ++b) fa[buf][b] = *reinterpret_cast<const u32x4 *>(as + a_row + b * 32 * BK + koff[ks]);
+#pragma unroll
+    for (int a = 0; a < FN; ++a) fw[buf][a] = *reinterpret_cast<const u32x4 *>(ws + w_row + a * 32 * BK + koff[ks]);
+  };
+  auto mfma_step = [&](int buf) {
+#pragma unroll
+    for (int a = 0; a < FN; ++a)
+#pragma unroll
+      for (int b = 0; b < FM; ++b) acc[a][b] = mfma32(fw[buf][a], fa[buf][b], acc[a][b]);
+  };
+  auto interleave = [&]() {
+#pragma unroll
+    for (int i = 0; i < FM + FN; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, FM * FN - (FM + FN), 0);
+  };
+
+  wait_vmcnt<(STAGES - 1) * LOADS>();
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  read_frags(0, 0, 0);
+
+  int stage = 0, kt = 0, my_tile = 0;
+  const int units = n_my * kt_n;
+  for (int u = 0; u < units; ++u) {
+#pragma unroll
+    for (int ks = 0; ks < KS - 1; ++ks) {
+      read_frags((ks + 1) & 1, stage, ks + 1);
+      mfma_step(ks & 1);
+      interleave();
+    }
+    wait_vmcnt<(STAGES - 2) * LOADS>();
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    issue_next(stage);
+    const int next_stage = (stage + 1 == STAGES) ? 0 : stage + 1;
+    read_frags(KS & 1, next_stage, 0);
+    mfma_step((KS - 1) & 1);
+    interleave();
+    stage = next_stage;
+    if (++kt == kt_n) {                             // an output tile is complete
+      int m0, n0;
+      tile_of(my_tile, m0, n0);
+      if constexpr (WTN == 64) {
+        gemm_epilogue_lds<EPI, FM, FN>(acc, g, m0 + wm * WTM, n0 + wn * WTN, lane,
+                                       lds + STAGES * STAGE_ELEMS + wave * (32 * 64));
+      } else {
+        gemm_epilogue<EPI, FM, FN>(acc, g, m0 + wm * WTM, n0 + wn * WTN, r32, grp);
+      }
+#pragma unroll
+      for (int a = 0; a < FN; ++a)
+#pragma unroll
+        for (int b = 0; b < FM; ++b)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+      kt = 0;
+      ++my_tile;
+    }
+  }
+  wait_vmcnt<0>();
+}
+
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, int MINB = 1>
+int launch_gemm_stream_cfg(const GemmArgs &g, hipStream_t s) {
+  constexpr int NT = WAVES_M * WAVES_N * 64;
+  // k-tile stages plus, for 64-column wavefront tiles, one 4 KiB epilogue slice per wavefront
+  constexpr size_t lds_bytes = (size_t)STAGES * (BM + BN) * BK * sizeof(uint16_t) +
+                               ((BN / WAVES_N == 64) ? (size_t)WAVES_M * WAVES_N * 32 * 64 * sizeof(uint16_t) : 0);
+  static_assert(lds_bytes <= 160 * 1024, "LDS budget");
+  static int n_cu = 0;
+  if (n_cu == 0) {
+    int dev = 0;
+    ET_HIP(hipGetDevice(&dev));
+    ET_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+    if (n_cu <= 0) n_cu = 256;
+  }
+  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.n_store + BN - 1) / BN;
+  const int n_tiles = tiles_m * tiles_n;
+  const int slots = n_cu * MINB;
+  const dim3 grid(n_tiles < slots ? n_tiles : slots), block(NT);
+#define ET_GEMM_LAUNCH(E)                                                                        \
+  {                                                                                              \
+    auto kern = gemm_stream_kernel<BM, BN, BK, WAVES_M, WAVES_N, STAGES, MINB, E>;               \
+    static bool attr_set = false;                                                                \
+    if (!attr_set) {                                                                             \
+      ET_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                           \
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));   \
+      attr_set = true;                                                                           \
+    }                                                                                            \
+    hipLaunchKernelGGL(kern, grid, block, lds_bytes, s, g, tiles_m, tiles_n);                    \
+  }
+  switch (g.epilogue) {
+    case EPI_BIAS: ET_GEMM_LAUNCH(EPI_BIAS); break;
+    case EPI_BIAS_GELU: ET_GEMM_LAUNCH(EPI_BIAS_GELU); break;
+    case EPI_BIAS_RES: ET_GEMM_LAUNCH(EPI_BIAS_RES); break;
+    default: set_error("unknown epilogue %d", g.epilogue); return ET_ERR_INVALID_ARG;
+  }
+#undef ET_GEMM_LAUNCH
+  ET_LAUNCH_CHECK();
+  return ET_OK;
 }
 
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, int MINB = 1>
@@ -874,7 +1150,7 @@ int launch_im2col(const float *frames, int T, int C, int H, int W, int P, int Kp
   return ET_OK;
 }
 
-int gemm_config_count() { return 20; }
+int gemm_config_count() { return 26; }
 
 static int launch_gemm_id(const GemmArgs &g, hipStream_t s, int cfg) {
   switch (cfg) {
@@ -898,6 +1174,12 @@ static int launch_gemm_id(const GemmArgs &g, hipStream_t s, int cfg) {
     case 17: return launch_gemm_dma_cfg<256, 128, 32, 2, 2, 2, 2>(g, s);
     case 18: return launch_gemm_dma_cfg<128, 256, 32, 2, 2, 3, 2>(g, s);
     case 19: return launch_gemm_dma_cfg<256, 128, 64, 2, 2, 2, 1>(g, s);
+    case 20: return launch_gemm_stream_cfg<256, 256, 64, 2, 4, 2>(g, s);
+    case 21: return launch_gemm_stream_cfg<256, 256, 32, 2, 4, 3>(g, s);
+    case 22: return launch_gemm_stream_cfg<128, 128, 64, 2, 2, 2, 2>(g, s);
+    case 23: return launch_gemm_stream_cfg<128, 128, 32, 2, 2, 4, 2>(g, s);
+    case 24: return launch_gemm_stream_cfg<256, 128, 64, 2, 4, 2>(g, s);
+    case 25: return launch_gemm_stream_cfg<256, 128, 32, 4, 2, 4>(g, s);
     default: set_error("unknown gemm tile configuration %d", cfg); return ET_ERR_INVALID_ARG;
   }
 }
@@ -916,8 +1198,9 @@ int launch_gemm(const GemmArgs &g, hipStream_t s, int force_cfg) {
   const long t128 = (long)((g.M + 127) / 128) * ((g.n_store + 127) / 128);
   const double cost256 = (double)((t256 + 255) / 256);
   const double cost128 = t128 <= 256 ? 0.3 : 0.6 * (double)((t128 + 511) / 512);
-  if (cost256 <= cost128) return launch_gemm_id(g, s, 6);
-  return launch_gemm_id(g, s, t128 <= 256 ? 9 : 8);
+  if (cost256 <= cost128 && g.n_store % 8 == 0) return launch_gemm_id(g, s, 20);
+  if (g.n_store % 8 != 0) return launch_gemm_id(g, s, t128 <= 256 ? 9 : 8);   // 4-column granularity
+  return launch_gemm_id(g, s, t128 <= 256 ? 23 : 22);
 }
 
 bool head_dim_supported(int hd) {
