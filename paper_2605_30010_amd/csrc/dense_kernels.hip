@@ -931,7 +931,8 @@ __global__ __launch_bounds__(kAttWaves * 64) void attention_kernel(
 // K and V^T tiles are brought in by direct global -> LDS loads, double buffered, one barrier per
 // 64-key tile.  K rows sit back to back in LDS (row stride = head_dim * 2 bytes; 144 bytes for
 // head_dim 72 spreads 16-byte reads of consecutive rows over all banks); V^T rows are 128 bytes
-// with the 16-byte slots XOR-swizzled by (row >> 1) & 7.  When head_dim is not a multiple of 16
+// (keys permuted inside each 16-key chunk, see transpose_v_kernel) with the 16-byte slots
+// XOR-swizzled by (row >> 1) & 7.  When head_dim is not a multiple of 16
 // the last contraction chunk of a K row runs 16 bytes into the next row; those values meet the
 // zero padding of Q, and the data behind the last row is the (finite) V^T tile.
 // ---------------------------------------------------------------------------------------
@@ -955,60 +956,92 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const uint16_t *__rest
   uint16_t *obase = vt + ((size_t)(f * n_heads + h) * HD) * Lpad + t0;
   for (int i = threadIdx.x; i < HD * 8; i += 256) {
     const int d = i / 8, tc = i % 8;
+    // 8 output positions tc*8 .. tc*8+7 of the row; position p of a 16-key chunk holds key
+    // (p & 3) + 4 * (p >> 3) + 8 * ((p >> 2) & 1): the order in which the S^T accumulator of the
+    // attention kernel presents keys to one lane group, so that its 8 keys are one 16-byte read
     uint32_t w[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const uint32_t lo = tile[(tc * 8 + 2 * j) * TROW + d], hi = tile[(tc * 8 + 2 * j + 1) * TROW + d];
+      const int p0 = (tc & 1) * 8 + 2 * j, p1 = p0 + 1;
+      const int k0 = (tc >> 1) * 16 + (p0 & 3) + 4 * (p0 >> 3) + 8 * ((p0 >> 2) & 1);
+      const int k1 = (tc >> 1) * 16 + (p1 & 3) + 4 * (p1 >> 3) + 8 * ((p1 >> 2) & 1);
+      const uint32_t lo = tile[k0 * TROW + d], hi = tile[k1 * TROW + d];
       w[j] = lo | (hi << 16);
     }
     *reinterpret_cast<uint4 *>(obase + (size_t)d * Lpad + tc * 8) = make_uint4(w[0], w[1], w[2], w[3]);
   }
 }
 
-template <int HD>
-__global__ __launch_bounds__(kAttWaves * 64) void attention_dma_kernel(
+template <int HD, int STAGES>
+__global__ __launch_bounds__(kAttWaves * 64, (HD <= 96 ? 2 : 1)) void attention_dma_kernel(
     const uint16_t *__restrict__ qkv, const uint16_t *__restrict__ vt, int n, int n_heads, int Lpad,
     float scale_log2, uint16_t *__restrict__ out) {
   constexpr int NC = (HD + 15) / 16;
   constexpr int NDB = (HD + 31) / 32;
   constexpr int K_LOADS = HD / 8;            // 1 KiB loads per K tile  (64 keys * HD * 2 bytes)
   constexpr int V_LOADS = HD / 8;            // 1 KiB loads per V^T tile (HD rows * 128 bytes)
+  constexpr int LOADS = (K_LOADS + V_LOADS + kAttWaves - 1) / kAttWaves;   // per wavefront per tile
   constexpr int K_ELEMS = kAttBKV * HD, V_ELEMS = HD * kAttBKV;
   constexpr int STAGE = K_ELEMS + V_ELEMS;
   // tail pad: O^T row blocks past head_dim read rows behind the V^T tile; whatever they hold only
-  // reaches accumulator rows >= head_dim, which are never stored (MFMA output rows are independent)
-  constexpr int PAD = (NDB * 32 - HD) * kAttBKV;
-  __shared__ __align__(16) uint16_t lds[2 * STAGE + PAD];
+  // reaches accumulator rows >= head_dim, which are never stored (MFMA output rows are independent).
+  // The last 512 elements absorb the filler loads that keep every wavefront at LOADS loads per tile.
+  constexpr int PAD = (NDB * 32 - HD) * kAttBKV + 512;
+  __shared__ __align__(16) uint16_t lds[STAGES * STAGE + PAD];
 
   const int f = blockIdx.z, h = blockIdx.y, q0 = blockIdx.x * kAttBQ;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps load dispatch scalar
   const int r32 = lane & 31, grp = lane >> 5;
   const int D = n_heads * HD, ld = 3 * D;
   const uint16_t *qbase = qkv + (size_t)f * n * ld + h * HD;
   const uint16_t *kbase = qbase + D;
   const uint16_t *vtb = vt + ((size_t)(f * n_heads + h) * HD) * Lpad;
+  const int n_tiles = (n + kAttBKV - 1) / kAttBKV;
 
-  // loads j = wave, wave + 4, ... < K_LOADS + V_LOADS belong to this wavefront
-  auto issue = [&](int stage, int kv0) {
+  // loads j = wave, wave + 4, ... of a tile belong to this wavefront; ids past the tile's 2*HD/8
+  // loads are fillers (same count for every wavefront, so one vmcnt immediate serves all).
+  // Per-lane source offsets are computed once: tiles advance by a constant stride, and only the
+  // last tile needs its key rows clamped to the frame (its offsets are kept separately).
+  int off_first[LOADS], off_last[LOADS];
+#pragma unroll
+  for (int j = 0; j < LOADS; ++j) {
+    const int ld_id = j * kAttWaves + wave;
+    if (ld_id < K_LOADS) {
+      const int q = ld_id * 64 + lane, key = q / (HD / 8), ch = q % (HD / 8);
+      int kl = (n_tiles - 1) * kAttBKV + key;
+      if (kl >= n) kl = n - 1;                         // clamp: masked later, stays in bounds
+      off_first[j] = key * ld + ch * 8;
+      off_last[j] = kl * ld + ch * 8;
+    } else if (ld_id < K_LOADS + V_LOADS) {
+      const int q = (ld_id - K_LOADS) * 64 + lane, d = q >> 3, slot = q & 7;
+      off_first[j] = d * Lpad + ((slot ^ ((d >> 1) & 7)) * 8);
+      off_last[j] = off_first[j] + (n_tiles - 1) * kAttBKV;
+    } else {
+      off_first[j] = off_last[j] = lane * 8;
+    }
+  }
+  auto issue = [&](int stage, int tile) {
+    const bool last = tile >= n_tiles - 1;             // past the end: re-read the last tile, unused
     uint16_t *ks = lds + stage * STAGE;
     uint16_t *vs = ks + K_ELEMS;
 #pragma unroll
-    for (int j = 0; j < (K_LOADS + V_LOADS + kAttWaves - 1) / kAttWaves; ++j) {
+    for (int j = 0; j < LOADS; ++j) {
       const int ld_id = j * kAttWaves + wave;
       if (ld_id < K_LOADS) {
-        const int q = ld_id * 64 + lane, key = q / (HD / 8), ch = q % (HD / 8);
-        int kk = kv0 + key;
-        if (kk >= n) kk = n - 1;                       // clamp: masked later, stays in bounds
-        ET_LDS_DMA16(kbase + (size_t)kk * ld + ch * 8, ks + ld_id * 512);
+        const int off = last ? off_last[j] : off_first[j] + tile * (kAttBKV * ld);
+        ET_LDS_DMA16(kbase + off, ks + ld_id * 512);
       } else if (ld_id < K_LOADS + V_LOADS) {
-        const int vl = ld_id - K_LOADS;
-        const int q = vl * 64 + lane, d = q >> 3, slot = q & 7;
-        ET_LDS_DMA16(vtb + (size_t)d * Lpad + kv0 + ((slot ^ ((d >> 1) & 7)) * 8), vs + vl * 512);
+        const int off = last ? off_last[j] : off_first[j] + tile * kAttBKV;
+        ET_LDS_DMA16(vtb + off, vs + (ld_id - K_LOADS) * 512);
+      } else {
+        ET_LDS_DMA16(vtb + off_first[j], lds + STAGES * STAGE + PAD - 512);
       }
     }
   };
 
-  issue(0, 0);
+#pragma unroll
+  for (int st = 0; st < STAGES - 1; ++st) issue(st, st);
 
   u32x4 qf[NC];
   {
@@ -1028,27 +1061,43 @@ __global__ __launch_bounds__(kAttWaves * 64) void attention_dma_kernel(
   float m_run = -INFINITY, l_run = 0.f;        // m_run in raw logit units
   const int vfx = (r32 >> 1) & 7;              // swizzle of this lane's V^T rows (32 b + r32: same low bits)
 
-  const int n_tiles = (n + kAttBKV - 1) / kAttBKV;
+  int stage = 0;
   for (int t = 0; t < n_tiles; ++t) {
     const int kv0 = t * kAttBKV;
-    wait_vmcnt<0>();
-    __builtin_amdgcn_s_barrier();              // tile t is in LDS; everyone is done with tile t-1
+    wait_vmcnt<(STAGES - 2) * LOADS>();        // tile t has landed (newer tiles may be in flight)
+    __builtin_amdgcn_s_barrier();              // ... for every wavefront; everyone is done with tile t-1
     asm volatile("" ::: "memory");
-    if (t + 1 < n_tiles) issue((t + 1) & 1, kv0 + kAttBKV);
-    const uint16_t *ks = lds + (t & 1) * STAGE;
+    issue(stage == 0 ? STAGES - 1 : stage - 1, t + STAGES - 1);
+    const uint16_t *ks = lds + stage * STAGE;
     const uint16_t *vs = ks + K_ELEMS;
+    stage = (stage + 1 == STAGES) ? 0 : stage + 1;
 
+    // S^T = K Q^T for the tile's two 32-key blocks.  K fragments are double-buffered: the LDS
+    // reads of contraction chunk c+1 are issued before the MFMAs of chunk c (scheduling barriers
+    // keep that order), and the two key blocks alternate as independent MFMA chains.
     f32x16 s_acc[2];
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    u32x4 kf[2][2];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
+    for (int kb = 0; kb < 2; ++kb) kf[0][kb] = *reinterpret_cast<const u32x4 *>(ks + (kb * 32 + r32) * HD + grp * 8);
 #pragma unroll
-      for (int i = 0; i < 16; ++i) s_acc[kb][i] = 0.f;
+    for (int c = 0; c < NC; ++c) {
+      if (c + 1 < NC) {
 #pragma unroll
-      for (int c = 0; c < NC; ++c) {
-        const u32x4 kf = *reinterpret_cast<const u32x4 *>(ks + (kb * 32 + r32) * HD + c * 16 + grp * 8);
-        s_acc[kb] = mfma32(kf, qf[c], s_acc[kb]);
+        for (int kb = 0; kb < 2; ++kb)
+          kf[(c + 1) & 1][kb] = *reinterpret_cast<const u32x4 *>(ks + (kb * 32 + r32) * HD + (c + 1) * 16 + grp * 8);
       }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) s_acc[kb] = mfma32(kf[c & 1][kb], qf[c], c == 0 ? zero16 : s_acc[kb]);
+      __builtin_amdgcn_sched_barrier(0);
     }
+    // first V^T fragments: fetched now, consumed after the softmax arithmetic below
+    u32x4 vf[2][NDB];
+#pragma unroll
+    for (int b = 0; b < NDB; ++b)
+      vf[0][b] = *reinterpret_cast<const u32x4 *>(vs + (b * 32 + r32) * kAttBKV + ((grp ^ vfx) * 8));
+    __builtin_amdgcn_sched_barrier(0);
     if (kv0 + kAttBKV > n) {                   // only the last tile can hold keys past the frame
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
@@ -1094,21 +1143,25 @@ __global__ __launch_bounds__(kAttWaves * 64) void attention_dma_kernel(
       }
     }
     l_run += l_tile;
-    // O^T += V^T P^T.  P's k-slots of chunk c are keys 16c + 4 grp + (0..3) and 16c + 8 + 4 grp + (0..3):
-    // two 8-byte reads from 16-byte slots 2c and 2c + 1 of the V^T row, offset 8 grp bytes.
+    // O^T += V^T P^T.  P's k-slots of chunk c, lane group grp, are keys 16c + 4 grp + (0..3) and
+    // 16c + 8 + 4 grp + (0..3); transpose_v_kernel stored exactly those 8 keys in 16-byte slot
+    // 2c + grp of the V^T row.  Row blocks alternate inside a chunk: independent MFMA chains.
 #pragma unroll
-    for (int b = 0; b < NDB; ++b) {
-      const uint16_t *vrow = vs + (b * 32 + r32) * kAttBKV + grp * 4;
+    for (int c = 0; c < 4; ++c) {
+      if (c + 1 < 4) {
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const uint2 lo = *reinterpret_cast<const uint2 *>(vrow + (((2 * c) ^ vfx) * 8));
-        const uint2 hi = *reinterpret_cast<const uint2 *>(vrow + (((2 * c + 1) ^ vfx) * 8));
-        const u32x4 vf = u32x4{lo.x, lo.y, hi.x, hi.y};
-        o_acc[b] = mfma32(vf, pf[c], o_acc[b]);
+        for (int b = 0; b < NDB; ++b)
+          vf[(c + 1) & 1][b] =
+              *reinterpret_cast<const u32x4 *>(vs + (b * 32 + r32) * kAttBKV + (((2 * (c + 1) + grp) ^ vfx) * 8));
       }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int b = 0; b < NDB; ++b) o_acc[b] = mfma32(vf[c & 1][b], pf[c], o_acc[b]);
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
 
+  wait_vmcnt<0>();                            // drain filler / past-the-end loads before LDS is released
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   const float inv = 1.0f / l_tot;
   const int q = q0 + wave * 32 + r32;
@@ -1150,7 +1203,7 @@ int launch_im2col(const float *frames, int T, int C, int H, int W, int P, int Kp
   return ET_OK;
 }
 
-int gemm_config_count() { return 26; }
+int gemm_config_count() { return 30; }
 
 static int launch_gemm_id(const GemmArgs &g, hipStream_t s, int cfg) {
   switch (cfg) {
@@ -1180,6 +1233,10 @@ static int launch_gemm_id(const GemmArgs &g, hipStream_t s, int cfg) {
     case 23: return launch_gemm_stream_cfg<128, 128, 32, 2, 2, 4, 2>(g, s);
     case 24: return launch_gemm_stream_cfg<256, 128, 64, 2, 4, 2>(g, s);
     case 25: return launch_gemm_stream_cfg<256, 128, 32, 4, 2, 4>(g, s);
+    case 26: return launch_gemm_stream_cfg<64, 128, 64, 2, 2, 2, 2>(g, s);
+    case 27: return launch_gemm_stream_cfg<64, 128, 64, 2, 2, 3, 2>(g, s);
+    case 28: return launch_gemm_stream_cfg<128, 64, 64, 4, 1, 2, 2>(g, s);
+    case 29: return launch_gemm_stream_cfg<128, 128, 64, 2, 2, 3, 1>(g, s);
     default: set_error("unknown gemm tile configuration %d", cfg); return ET_ERR_INVALID_ARG;
   }
 }
@@ -1191,16 +1248,24 @@ int launch_gemm(const GemmArgs &g, hipStream_t s, int force_cfg) {
     return ET_ERR_INVALID_ARG;
   }
   if (force_cfg >= 0) return launch_gemm_id(g, s, force_cfg);
-  // Tile choice by a cost model in units of one 256 x 256 tile time.  256 x 256 workgroups run
-  // one per compute unit; 128 x 128 ones run two per compute unit (each then at about 0.6 of a
-  // big tile's time) or alone (0.3) when there are no more tiles than compute units.
+  // Tile choice (persistent stream kernels; measured on MI355X at the encoder's shapes).
+  //  - n_store not a multiple of 8: the 4-column epilogue of the non-persistent kernels.
+  //  - at least ~150 tiles of 256 x 256: one workgroup of 8 wavefronts per compute unit.  Above 256
+  //    tiles the makespan is whole rounds of tiles; 128 x 128 tiles (two workgroups per compute
+  //    unit, each at about 0.6 of a big tile's time) win only when they save a round.
+  //  - fewer: 128 x 128 tiles if that gives ~300 workgroups, else 64 x 128 (k-tile 64, so the
+  //    latency-bound barrier-per-k-tile loop has few trips) to cover the compute units.
   const long t256 = (long)((g.M + 255) / 256) * ((g.n_store + 255) / 256);
   const long t128 = (long)((g.M + 127) / 128) * ((g.n_store + 127) / 128);
-  const double cost256 = (double)((t256 + 255) / 256);
-  const double cost128 = t128 <= 256 ? 0.3 : 0.6 * (double)((t128 + 511) / 512);
-  if (cost256 <= cost128 && g.n_store % 8 == 0) return launch_gemm_id(g, s, 20);
-  if (g.n_store % 8 != 0) return launch_gemm_id(g, s, t128 <= 256 ? 9 : 8);   // 4-column granularity
-  return launch_gemm_id(g, s, t128 <= 256 ? 23 : 22);
+  if (g.n_store % 8 != 0) return launch_gemm_id(g, s, t128 <= 256 ? 9 : 8);
+  if (t256 > 256) {
+    const double cost256 = (double)((t256 + 255) / 256);
+    const double cost128 = 0.6 * (double)((t128 + 511) / 512);
+    return launch_gemm_id(g, s, cost256 <= cost128 ? 20 : 22);
+  }
+  if (t256 >= 150) return launch_gemm_id(g, s, 20);
+  if (t128 >= 300) return launch_gemm_id(g, s, 22);
+  return launch_gemm_id(g, s, 26);
 }
 
 bool head_dim_supported(int hd) {
@@ -1239,7 +1304,7 @@ int launch_attention_uniform(const uint16_t *qkv, int n_frames, int len, int n_h
 #define ET_ATT(HD)                                                                                        \
   case HD:                                                                                                \
     hipLaunchKernelGGL(transpose_v_kernel<HD>, tgrid, dim3(256), 0, s, qkv, len, n_heads, Lpad, vt_ws);   \
-    hipLaunchKernelGGL(attention_dma_kernel<HD>, agrid, dim3(kAttWaves * 64), 0, s, qkv, vt_ws, len,      \
+    hipLaunchKernelGGL((attention_dma_kernel<HD, 3>), agrid, dim3(kAttWaves * 64), 0, s, qkv, vt_ws, len,      \
                        n_heads, Lpad, scale_log2, out);                                                   \
     break;
   switch (head_dim) {
