@@ -42,7 +42,7 @@ typedef struct et_encoder et_encoder; /* opaque; owns the packed device weights 
 
 /* Encoder shape.  Tokens per frame L = (image_h / patch) * (image_w / patch); pixels past the
  * last whole patch are ignored.  head_dim = d_model / n_heads must be 16, 32, 64, 72, 80, 96
- * or 128; d_model must be a multiple of 8. */
+ * or 128; d_model must be a multiple of 64, at most 4096. */
 typedef struct {
   int32_t n_layers, d_model, n_heads, d_mlp, patch, image_h, image_w, channels;
   float ln_eps;
@@ -182,9 +182,10 @@ int et_gemm_bf16(const uint16_t *a_dev, const uint16_t *w_dev, const float *bias
 
 /* Times `iters` back-to-back launches of the GEMM above on library-allocated operands of the
  * given logical shape with HIP events; *avg_ms (HOST) receives the mean milliseconds per
- * launch.  tile_config selects a workgroup tiling (0: 128x128, 1: 256x128, 2: 256x256 with 8
- * wavefronts, 3: 256x128 with 8 wavefronts, 4: 128x256, 5: 256x256 with 4 wavefronts;
- * -1: the library's own choice).  For tuning sweeps; allocates, frees and synchronises. */
+ * launch.  tile_config selects one of the library's workgroup tilings: 0-5 register-staged
+ * kernels, 6-19 direct-to-LDS kernels (one tile per workgroup), 20-32 persistent k-tile stream
+ * kernels (20: 256x256x64 with 8 wavefronts, 22: 128x128x64, 26: 64x128x64; the full table is in
+ * launch_gemm_id); -1: the library's own choice.  For tuning sweeps; allocates, frees, synchronises. */
 int et_gemm_tune(int32_t M, int32_t N, int32_t K, int32_t epilogue, int32_t tile_config, int32_t iters,
                  float *avg_ms, void *hip_stream);
 

@@ -21,11 +21,12 @@ library primitives; nothing is blocked, fused or reordered.  Only tests,
 `__graft_entry__.smoke()` and `bench.py`'s cpu_baseline leg may import this
 file; the product path never does, and this file imports nothing of the product.
 
-Parity pins (tests/test_oracle_*.py): closed forms for the similarity, hand
+Parity pins (tests/test_oracle_pins.py): closed forms for the similarity, hand
 cases for the boundary scan, brute-force selection for the top-k, textbook
-special cases for LayerNorm / softmax / GELU, an independent per-token loop
-implementation of one encoder block, and the end-to-end invariants
-(compression disabled == plain encoder; identical frames == single frame).
+special cases for LayerNorm / softmax / GELU, one encoder block assembled from
+torch library routines, patch embedding as a strided convolution, and the
+end-to-end invariants (compression disabled == plain encoder; identical frames
+== single frame).
 """
 import math
 

@@ -190,12 +190,15 @@ __device__ __forceinline__ void gemm_epilogue(f32x16 (&acc)[FN][FM], const GemmA
 template <int EPI, int FM, int FN>
 __device__ __forceinline__ void gemm_epilogue_lds(f32x16 (&acc)[FN][FM], const GemmArgs &g, int m_base,
                                                   int n_base, int lane, uint16_t *slice) {
-  static_assert(FN == 2, "the staged epilogue handles 64-column wavefront tiles");
+  static_assert(FN % 2 == 0, "the staged epilogue handles 64-column pieces of the wavefront tile");
   const int r32 = lane & 31, grp = lane >> 5;
   const int prow = lane >> 3, pch = lane & 7;                 // row-wise phase: 8 rows x 8 chunks per pass
-  const int n_lane = n_base + pch * 8;
-  const bool n_ok = n_lane < g.n_store;                       // n_store is a multiple of 8 on this path
   const int wsw = (r32 >> 1) & 7;
+#pragma unroll
+  for (int half = 0; half < FN / 2; ++half) {
+  const int nb = n_base + half * 64;
+  const int n_lane = nb + pch * 8;
+  const bool n_ok = n_lane < g.n_store;                       // n_store is a multiple of 8 on this path
 #pragma unroll
   for (int b = 0; b < FM; ++b) {
     const int mb = m_base + b * 32;
@@ -211,14 +214,15 @@ __device__ __forceinline__ void gemm_epilogue_lds(f32x16 (&acc)[FN][FM], const G
       }
     }
 #pragma unroll
-    for (int a = 0; a < FN; ++a) {
+    for (int a = 0; a < 2; ++a) {
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int n = n_base + a * 32 + q * 8 + grp * 4;
+        const int n = nb + a * 32 + q * 8 + grp * 4;
         float4 bi = make_float4(0.f, 0.f, 0.f, 0.f);
         if (n < g.n_store) bi = *reinterpret_cast<const float4 *>(g.bias + n);
-        float v0 = acc[a][b][q * 4 + 0] + bi.x, v1 = acc[a][b][q * 4 + 1] + bi.y;
-        float v2 = acc[a][b][q * 4 + 2] + bi.z, v3 = acc[a][b][q * 4 + 3] + bi.w;
+        const f32x16 &av = acc[half * 2 + a][b];
+        float v0 = av[q * 4 + 0] + bi.x, v1 = av[q * 4 + 1] + bi.y;
+        float v2 = av[q * 4 + 2] + bi.z, v3 = av[q * 4 + 3] + bi.w;
         if (EPI == EPI_BIAS_GELU) {
           v0 = gelu_tanh_f(v0); v1 = gelu_tanh_f(v1); v2 = gelu_tanh_f(v2); v3 = gelu_tanh_f(v3);
         }
@@ -240,6 +244,7 @@ __device__ __forceinline__ void gemm_epilogue_lds(f32x16 (&acc)[FN][FM], const G
       const u32x4 v = *reinterpret_cast<const u32x4 *>(slice + row * 64 + ((pch ^ ((row >> 1) & 7)) * 8));
       if (m < g.M && n_ok) *reinterpret_cast<u32x4 *>(g.C + (size_t)m * g.ldc + n_lane) = v;
     }
+  }
   }
 }
 
@@ -622,7 +627,8 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
   asm volatile("" ::: "memory");
   read_frags(0, 0, 0);
 
-  int stage = 0, kt = 0, my_tile = 0;
+  int stage = 0, kt = 0, my_tile = 0, relax = 0;
+  constexpr int N_ST = FM * (FN / 2) * 4;            // global stores per wavefront in the staged epilogue
   const int units = n_my * kt_n;
   for (int u = 0; u < units; ++u) {
 #pragma unroll
@@ -631,7 +637,16 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
       mfma_step(ks & 1);
       interleave();
     }
-    wait_vmcnt<(STAGES - 2) * LOADS>();
+    // Vector-memory operations retire in issue order.  For STAGES - 1 units after the epilogue of
+    // an interior tile (every lane stored: exactly N_ST store instructions per wavefront) those
+    // stores are younger than the loads awaited here, so they may stay in flight and drain under
+    // the next tile's MFMAs.
+    if (relax > 0) {
+      wait_vmcnt<(STAGES - 2) * LOADS + N_ST>();
+      --relax;
+    } else {
+      wait_vmcnt<(STAGES - 2) * LOADS>();
+    }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
@@ -644,9 +659,10 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
     if (++kt == kt_n) {                             // an output tile is complete
       int m0, n0;
       tile_of(my_tile, m0, n0);
-      if constexpr (WTN == 64) {
+      if constexpr (WTN % 64 == 0) {
         gemm_epilogue_lds<EPI, FM, FN>(acc, g, m0 + wm * WTM, n0 + wn * WTN, lane,
                                        lds + STAGES * STAGE_ELEMS + wave * (32 * 64));
+        if (m0 + BM <= g.M && n0 + BN <= g.n_store) relax = STAGES - 1;
       } else {
         gemm_epilogue<EPI, FM, FN>(acc, g, m0 + wm * WTM, n0 + wn * WTN, r32, grp);
       }
@@ -668,7 +684,7 @@ int launch_gemm_stream_cfg(const GemmArgs &g, hipStream_t s) {
   constexpr int NT = WAVES_M * WAVES_N * 64;
   // k-tile stages plus, for 64-column wavefront tiles, one 4 KiB epilogue slice per wavefront
   constexpr size_t lds_bytes = (size_t)STAGES * (BM + BN) * BK * sizeof(uint16_t) +
-                               ((BN / WAVES_N == 64) ? (size_t)WAVES_M * WAVES_N * 32 * 64 * sizeof(uint16_t) : 0);
+                               (((BN / WAVES_N) % 64 == 0) ? (size_t)WAVES_M * WAVES_N * 32 * 64 * sizeof(uint16_t) : 0);
   static_assert(lds_bytes <= 160 * 1024, "LDS budget");
   static int n_cu = 0;
   if (n_cu == 0) {
@@ -1203,7 +1219,7 @@ int launch_im2col(const float *frames, int T, int C, int H, int W, int P, int Kp
   return ET_OK;
 }
 
-int gemm_config_count() { return 30; }
+int gemm_config_count() { return 33; }
 
 static int launch_gemm_id(const GemmArgs &g, hipStream_t s, int cfg) {
   switch (cfg) {
@@ -1237,6 +1253,9 @@ static int launch_gemm_id(const GemmArgs &g, hipStream_t s, int cfg) {
     case 27: return launch_gemm_stream_cfg<64, 128, 64, 2, 2, 3, 2>(g, s);
     case 28: return launch_gemm_stream_cfg<128, 64, 64, 4, 1, 2, 2>(g, s);
     case 29: return launch_gemm_stream_cfg<128, 128, 64, 2, 2, 3, 1>(g, s);
+    case 30: return launch_gemm_stream_cfg<256, 256, 32, 2, 4, 4, 1>(g, s);
+    case 31: return launch_gemm_stream_cfg<256, 256, 32, 4, 2, 4, 1>(g, s);
+    case 32: return launch_gemm_stream_cfg<256, 256, 32, 4, 2, 3, 1>(g, s);
     default: set_error("unknown gemm tile configuration %d", cfg); return ET_ERR_INVALID_ARG;
   }
 }
