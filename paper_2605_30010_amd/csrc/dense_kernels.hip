@@ -531,15 +531,22 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
   const int r32 = lane & 31, grp = lane >> 5;
   const int lrow = lane / CPR, lslot = lane % CPR;
 
-  // j-th tile of this workgroup.  Within a round of G tiles each XCD (blockIdx % 8) takes a
-  // contiguous run, n fastest, so tiles sharing an activation row block meet in one L2.
+  // j-th tile of this workgroup.  Tiles are ordered in bands of 8 tile rows, inside a band in
+  // column blocks of 4 tile columns, inside a block row-major; within a round of G tiles each XCD
+  // (blockIdx % 8) takes a contiguous run of that order.  The ~32 tiles an XCD works on at once
+  // then form an 8 x 4 patch that shares 8 activation and 4 weight k-slices through its L2
+  // (12 slice fetches per 32 tiles instead of 19 for a 2 x 17 strip).
   auto tile_of = [&](int j, int &m0, int &n0) {
     const int base = j * G;
     const int cnt = (n_tiles - base < G) ? (n_tiles - base) : G;
     const int per = cnt / 8, rem = cnt % 8, xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
     const int t = base + xcd * per + (xcd < rem ? xcd : rem) + slot;
-    m0 = (t / tiles_n) * BM;
-    n0 = (t % tiles_n) * BN;
+    const int band = t / (8 * tiles_n), r = t - band * 8 * tiles_n;
+    const int hb = (tiles_m - band * 8 < 8) ? (tiles_m - band * 8) : 8;
+    const int cb = r / (hb * 4), r2 = r - cb * hb * 4;
+    const int wcb = (tiles_n - cb * 4 < 4) ? (tiles_n - cb * 4) : 4;
+    m0 = (band * 8 + r2 / wcb) * BM;
+    n0 = (cb * 4 + r2 % wcb) * BN;
   };
 
   const uint16_t *a_src[A_BLK];
