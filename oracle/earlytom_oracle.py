@@ -15,6 +15,9 @@ clip, with the paper's early token compression applied once inside the encoder:
             norm of the merged token; ties go to the lower position);
   Eq. 7     kept tokens are gathered in their original order and the remaining
             encoder blocks run on the shorter sequence.
+The paper-exact forms (Eq. 1 with smoothing, Alg. 1's head/tail + weighted middle
+pairs, Alg. 2's dynamic top-k / static local windows with the re-scaled count of
+Eq. 5) are the *_policy functions further down.
 
 Everything is float64 unless `dtype` says otherwise; matmul/einsum are the only
 library primitives; nothing is blocked, fused or reordered.  Only tests,
@@ -210,6 +213,183 @@ def merge_select(x, sim_threshold, keep_ratio, force_seg_start=None, force_kept=
     cu = (np.arange(N + 1) * k).astype(np.int32)
     return dict(frame_sim=s, cos=c, seg_start=seg, merged=xm, score=z, k=k,
                 kept_idx=kept, cu_tokens=cu, tokens=compact(xm, kept))
+
+
+# --------------------------------------------------------------------------
+# Paper-exact Stage I (Alg. 1) and Stage II (Alg. 2)
+#
+# Readings where the paper is silent or inconsistent (also listed in the design notes):
+#  - Eq. 1: the smoothed similarity restarts at every segment start (the first pair of a segment
+#    uses its raw similarity); the paper gives no initial value.
+#  - Alg. 1: a pair (F_i, F_{i+1}) of middle frames is eligible only if both are middle frames
+#    (i + 1 <= k - 1); as printed the loop would read past the segment and merge the tail frame
+#    that it appends afterwards.  tau_merge has no value in the paper; callers pass one.
+#  - Eq. 3: frame-level scalar weights, F_i by s_i = Sim(F_i, F_{i+1}), F_{i+1} by s_{i+1}.
+#  - Eq. 5 as printed is not a count and divides by zero when nothing merges; here
+#    r_hat = clamp(floor(r * B * L / N + 0.5), 1, L): per-frame count that keeps about r of the
+#    original B * L tokens.
+#  - Eq. 6: windows are contiguous ranges of the flattened position index; the last one may be short.
+# No worked example exists in the paper: beyond hand cases derived from the text, parity of these
+# functions is UNPINNED.
+# --------------------------------------------------------------------------
+
+def ema_segment_starts(s, alpha, tau, T):
+    """Eq. 1: s_hat_t = alpha s_t + (1 - alpha) s_hat_{t-1}; frame t opens a segment iff s_hat_t < tau.
+    The recursion restarts after every break.  Returns (seg_start [n_seg+1], s_hat [T-1])."""
+    starts, s_hat = [0], np.zeros(max(T - 1, 0), dtype=np.float64)
+    prev, fresh = 0.0, True
+    for t in range(1, T):
+        st = float(s[t - 1])
+        cur = st if fresh else alpha * st + (1.0 - alpha) * prev
+        s_hat[t - 1] = cur
+        if cur < tau or math.isnan(cur):
+            starts.append(t)
+            fresh = True
+        else:
+            prev, fresh = cur, False
+    starts.append(T)
+    return np.asarray(starts, dtype=np.int32), s_hat
+
+
+def merge_plan(s, seg_start, tau_merge, mode):
+    """Output-frame plan: list of dicts {first, count, weights, dynamic, segment}.
+
+    mode "mean": one output frame per segment, uniform weights 1/len.
+    mode "alg1": Alg. 1 — head and tail of a segment are kept; middle frames are walked left to
+    right and (F_i, F_{i+1}) are fused with weights (s_i, s_{i+1}) / (s_i + s_{i+1}) iff
+    s_i > tau_merge and s_i > s_{i+1} (Eq. 2-3), where s_i = Sim(F_i, F_{i+1}).
+    `dynamic` marks head and tail frames (Sec. 3.3)."""
+    plan = []
+    for n in range(len(seg_start) - 1):
+        a, b = int(seg_start[n]), int(seg_start[n + 1])
+        if mode == "mean":
+            plan.append(dict(first=a, count=b - a, weights=[1.0 / (b - a)] * (b - a), dynamic=True, segment=n))
+            continue
+        k = b - a - 1                                  # frames F_0 .. F_k
+        sim = lambda i: float(s[a + i])                # Sim(F_i, F_{i+1}): pair of global frames a+i, a+i+1
+        plan.append(dict(first=a, count=1, weights=[1.0], dynamic=True, segment=n))
+        i = 1
+        while i < k:
+            if i + 1 <= k - 1 and sim(i) > tau_merge and sim(i) > sim(i + 1):
+                si, sj = sim(i), sim(i + 1)
+                plan.append(dict(first=a + i, count=2, weights=[si / (si + sj), sj / (si + sj)],
+                                 dynamic=False, segment=n))
+                i += 2
+            else:
+                plan.append(dict(first=a + i, count=1, weights=[1.0], dynamic=False, segment=n))
+                i += 1
+        if k >= 1:
+            plan.append(dict(first=a + k, count=1, weights=[1.0], dynamic=True, segment=n))
+    return plan
+
+
+def apply_plan(x, plan):
+    """[T, L, D] -> [N, L, D]: each output frame is the weighted sum of its source frames (a plain
+    mean, summed in ascending frame order and divided by the length, for uniform plans)."""
+    out = np.empty((len(plan),) + x.shape[1:], dtype=x.dtype)
+    for n, p in enumerate(plan):
+        a, c = p["first"], p["count"]
+        if all(w == p["weights"][0] for w in p["weights"]):
+            acc = np.zeros(x.shape[1:], dtype=x.dtype)
+            for t in range(a, a + c):
+                acc = acc + x[t]
+            out[n] = acc / c
+        else:
+            acc = np.zeros(x.shape[1:], dtype=x.dtype)
+            for j in range(c):
+                acc = acc + p["weights"][j] * x[a + j]
+            out[n] = acc
+    return out
+
+
+def rescaled_count(r, B, L, N):
+    """Reading of Eq. 5: tokens kept per dynamic frame so that N frames keep about r * B * L."""
+    v = int(math.floor(float(r) * B * L / N + 0.5))
+    return max(1, min(L, v))
+
+
+def window_positions(z, r_hat):
+    """Eq. 6: w = floor(L / r_hat), M = ceil(L / w) windows of consecutive positions; keep the
+    arg-max score of each window (lowest position on ties; NaN ranks last; float32 ranking)."""
+    L = len(z)
+    w = L // r_hat
+    M = -(-L // w)
+    z32 = np.asarray(z, dtype=np.float32)
+    key = np.where(np.isnan(z32), -np.inf, z32.astype(np.float64))
+    kept = []
+    for j in range(M):
+        lo, hi = j * w, min((j + 1) * w, L)
+        kept.append(lo + int(np.argmax(key[lo:hi])))      # argmax returns the first maximum
+    return np.asarray(kept, dtype=np.int32)
+
+
+def merge_select_policy(x, policy, force_kept=None):
+    """Compression stage under a policy dict: alpha, tau_seg, tau_merge, merge_mode ("mean" | "alg1"),
+    select_mode ("uniform" | "decoupled"), ratio.  Returns the fields of merge_select plus `plan`,
+    `s_hat`, `frame_dynamic`; kept_idx is a flat list (frames may keep different counts)."""
+    T, L, D = x.shape
+    if T > 1:
+        c, s = frame_similarity(x)
+    else:
+        c, s = np.zeros((0, L), x.dtype), np.zeros((0,), x.dtype)
+    seg, s_hat = ema_segment_starts(s, policy["alpha"], policy["tau_seg"], T)
+    plan = merge_plan(s, seg, policy["tau_merge"], policy["merge_mode"])
+    xm = apply_plan(x, plan)
+    z = token_score(xm)
+    N = len(plan)
+    if policy["select_mode"] == "uniform":
+        k = keep_count(L, policy["ratio"])
+        per_frame = [topk_positions(z[n], k) for n in range(N)]
+    else:
+        r_hat = rescaled_count(policy["ratio"], T, L, N)
+        per_frame = [topk_positions(z[n], r_hat) if plan[n]["dynamic"] else window_positions(z[n], r_hat)
+                     for n in range(N)]
+    if force_kept is not None:                        # one array of positions per output frame
+        per_frame = [np.asarray(p, dtype=np.int32) for p in force_kept]
+        assert len(per_frame) == N
+    counts = [len(p) for p in per_frame]
+    cu = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    kept = np.concatenate(per_frame).astype(np.int32)
+    tokens = np.concatenate([xm[n][per_frame[n]] for n in range(N)], axis=0)
+    return dict(frame_sim=s, s_hat=s_hat, cos=c, seg_start=seg, plan=plan, merged=xm, score=z,
+                kept_idx=kept, cu_tokens=cu, tokens=tokens,
+                frame_dynamic=np.asarray([p["dynamic"] for p in plan], dtype=np.int32),
+                frame_first=np.asarray([p["first"] for p in plan], dtype=np.int32),
+                frame_count=np.asarray([p["count"] for p in plan], dtype=np.int32))
+
+
+def encode_clip_policy(shape, w, frames, merge_layer, policy, dtype=np.float64, x_at_merge=None,
+                       force_kept=None):
+    """Encoder forward with the policy-driven compression after `merge_layer` blocks; the blocks
+    after it attend inside each output frame over that frame's kept tokens (ragged lengths)."""
+    n_layers = len(w["layers"])
+    x = patch_embed(frames, w, shape.patch, dtype)
+    info, cu = None, None
+    for i in range(n_layers + 1):
+        if i == merge_layer:
+            if x_at_merge is not None:
+                x = np.asarray(x_at_merge, dtype=dtype)
+            info = merge_select_policy(x, policy, force_kept)
+            info["hidden_at_merge"] = x
+            cu = info["cu_tokens"]
+            rows = info["tokens"]
+        if i < n_layers:
+            if info is None:
+                if x_at_merge is not None and i < merge_layer:
+                    continue
+                x = encoder_block(x, w["layers"][i], shape.n_heads, shape.ln_eps)
+            else:                                          # ragged frames: block by block per frame
+                rows = np.concatenate([encoder_block(rows[cu[n]:cu[n + 1]][None], w["layers"][i],
+                                                     shape.n_heads, shape.ln_eps)[0]
+                                       for n in range(len(cu) - 1)], axis=0)
+    out_rows = rows
+    if shape.has_final_ln:
+        out_rows = layer_norm(out_rows, np.asarray(w["final_ln_g"], dtype), np.asarray(w["final_ln_b"], dtype),
+                              shape.ln_eps)
+    info = dict(info)
+    info["tokens"] = out_rows
+    info["n_frames_out"] = len(cu) - 1
+    return info
 
 
 # --------------------------------------------------------------------------

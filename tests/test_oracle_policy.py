@@ -1,0 +1,190 @@
+"""Pins for the oracle's paper-exact Stage I / Stage II functions (Eq. 1-7, Alg. 1-2).
+
+The paper prints no worked example, so these are hand cases derived from the algorithm text
+under the readings stated in the oracle, reductions to the already pinned simple forms,
+brute force, and invariants.  Parity of these forms beyond that is unpinned (documented).
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+
+from et_inputs import TINY, make_clip, make_weights
+from oracle import earlytom_oracle as O
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _alg1_cases():
+    out = []
+    for line in open(os.path.join(GOLD, "alg1_cases.txt")):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        p = [q.strip() for q in line.split("|")]
+        alpha, tau_seg, tau_merge = [float(v) for v in p[0].split()]
+        s = [float(v) for v in p[1].split()]
+        seg = [int(v) for v in p[2].split()]
+        frames = []
+        for tok in p[3].split():
+            first, rest = tok.split(":")
+            if "(" in rest:
+                cnt, ws = rest.split("(")
+                frames.append((int(first), int(cnt), [float(v) for v in ws.rstrip(")").split(",")]))
+            else:
+                frames.append((int(first), int(rest), None))
+        out.append((alpha, tau_seg, tau_merge, s, seg, frames))
+    return out
+
+
+@pytest.mark.parametrize("case", _alg1_cases())
+def test_alg1_hand_cases(case):
+    alpha, tau_seg, tau_merge, s, seg, frames = case
+    T = len(s) + 1
+    got_seg, _ = O.ema_segment_starts(np.array(s), alpha, tau_seg, T)
+    assert got_seg.tolist() == seg
+    plan = O.merge_plan(np.array(s), got_seg, tau_merge, "alg1")
+    assert [(p["first"], p["count"]) for p in plan] == [(f, c) for f, c, _ in frames]
+    for p, (_, c, ws) in zip(plan, frames):
+        assert abs(sum(p["weights"]) - 1.0) < 1e-12
+        if ws is not None:
+            np.testing.assert_allclose(p["weights"], ws, atol=6e-5)
+    # frames are covered exactly once, in order
+    covered = [t for p in plan for t in range(p["first"], p["first"] + p["count"])]
+    assert covered == list(range(T))
+    # head and tail of every segment are dynamic, everything else static
+    for n in range(len(seg) - 1):
+        mine = [p for p in plan if p["segment"] == n]
+        assert mine[0]["dynamic"] and mine[-1]["dynamic"]
+        assert all(not p["dynamic"] for p in mine[1:-1])
+        assert mine[0]["first"] == seg[n] and mine[-1]["first"] + mine[-1]["count"] == seg[n + 1]
+
+
+def test_ema_reduces_to_plain_threshold_and_smooths():
+    rng = np.random.default_rng(0)
+    for _ in range(40):
+        T = int(rng.integers(1, 30))
+        s = rng.random(T - 1)
+        seg, s_hat = O.ema_segment_starts(s, 1.0, 0.5, T)
+        assert seg.tolist() == O.segment_starts(s, 0.5, T).tolist()
+        np.testing.assert_array_equal(s_hat, s)
+    # hand-worked recursion: 0.9*0.97 + 0.1*0.95 = 0.968 ; 0.9*0.5 + 0.1*0.968 = 0.5468
+    seg, s_hat = O.ema_segment_starts(np.array([0.95, 0.97, 0.5, 0.6]), 0.9, 0.8, 5)
+    np.testing.assert_allclose(s_hat, [0.95, 0.968, 0.5468, 0.6], atol=1e-12)
+    assert seg.tolist() == [0, 3, 4, 5]          # the recursion restarts after the break at frame 3
+    # smoothing can keep a segment together across one dip (alg1_cases line 6) and NaN breaks
+    assert O.ema_segment_starts(np.array([0.99, np.nan, 0.99]), 0.9, 0.5, 4)[0].tolist() == [0, 2, 4]
+
+
+def test_identical_frames_never_merge_under_the_strict_rule():
+    s = np.ones(7)
+    seg, _ = O.ema_segment_starts(s, 0.9, 0.8, 8)
+    plan = O.merge_plan(s, seg, 0.8, "alg1")
+    assert seg.tolist() == [0, 8] and len(plan) == 8 and all(p["count"] == 1 for p in plan)
+
+
+def test_plan_mean_mode_is_the_segment_mean_and_weighted_pairs_are_convex():
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal((9, 4, 6))
+    seg = np.array([0, 3, 4, 9], dtype=np.int32)
+    plan = O.merge_plan(np.zeros(8), seg, 0.0, "mean")
+    np.testing.assert_array_equal(O.apply_plan(x, plan), O.segment_mean(x, seg))
+    # a fused pair is s_i F_i + s_{i+1} F_{i+1} over their sum (Eq. 3): check one by hand
+    s = np.array([0.9, 0.8, 0.6, 0.9])
+    plan = O.merge_plan(s, np.array([0, 5]), 0.5, "alg1")
+    assert [(p["first"], p["count"]) for p in plan] == [(0, 1), (1, 2), (3, 1), (4, 1)]
+    y = O.apply_plan(x[:5], plan)
+    np.testing.assert_allclose(y[1], (0.8 * x[1] + 0.6 * x[2]) / 1.4, rtol=1e-13)
+    np.testing.assert_array_equal(y[0], x[0])
+    np.testing.assert_array_equal(y[3], x[4])
+    # fusing two identical frames returns the frame
+    xx = x.copy(); xx[2] = xx[1]
+    np.testing.assert_allclose(O.apply_plan(xx[:5], plan)[1], xx[1], rtol=1e-14)
+
+
+def test_rescaled_count_keeps_the_overall_ratio():
+    assert O.rescaled_count(0.25, 32, 729, 32) == 182          # nothing merged: r * L = 182.25
+    assert O.rescaled_count(0.2, 32, 729, 8) == 583            # 0.2 * 32 * 729 / 8 = 583.2
+    assert O.rescaled_count(0.5, 32, 729, 8) == 729            # clamps at L
+    assert O.rescaled_count(1e-6, 32, 729, 8) == 1
+    for B, L, r in [(32, 729, 0.1), (64, 729, 0.15), (8, 64, 0.3)]:
+        for N in range(max(1, int(B * r) + 1), B + 1):
+            rh = O.rescaled_count(r, B, L, N)
+            assert abs(N * rh - r * B * L) <= 0.5 * N + 1e-9
+
+
+def _brute_windows(z, r_hat):
+    L = len(z)
+    w = L // r_hat
+    kept, lo = [], 0
+    while lo < L:
+        hi = min(lo + w, L)
+        best = lo
+        for j in range(lo, hi):
+            zj, zb = z[j], z[best]
+            if (not math.isnan(zj)) and (math.isnan(zb) or zj > zb):
+                best = j
+        kept.append(best)
+        lo = hi
+    return kept
+
+
+def test_window_selection_hand_and_brute_force():
+    assert O.window_positions(np.array([1, 5, 2, 7, 7, 0, 3.]), 3).tolist() == [1, 3, 4, 6]
+    assert O.window_positions(np.array([4., 4., 4., 4.]), 2).tolist() == [0, 2]        # ties: lowest position
+    assert O.window_positions(np.array([1., 2., 3.]), 3).tolist() == [0, 1, 2]         # w = 1: identity
+    rng = np.random.default_rng(2)
+    for trial in range(200):
+        L = int(rng.integers(1, 80))
+        z = rng.integers(0, 4, L).astype(np.float64) if trial % 2 else rng.random(L)
+        r_hat = int(rng.integers(1, L + 1))
+        got = O.window_positions(z, r_hat)
+        assert got.tolist() == _brute_windows(z.tolist(), r_hat)
+        w = L // r_hat
+        assert len(got) == -(-L // w)
+    # L = 729: r_hat 182 -> w = 4 -> 183 windows ; r_hat 400 -> w = 1 -> all 729 positions
+    assert len(O.window_positions(rng.random(729), 182)) == 183
+    assert len(O.window_positions(rng.random(729), 400)) == 729
+
+
+@pytest.fixture(scope="module")
+def tiny():
+    return make_weights(TINY, 11), make_clip(TINY, [4, 4], 12, base="uniform", sigma=0.02)
+
+
+def test_default_policy_reproduces_the_simple_path(tiny):
+    w, frames = tiny
+    pol = dict(alpha=1.0, tau_seg=0.9, tau_merge=0.9, merge_mode="mean", select_mode="uniform", ratio=0.5)
+    a = O.encode_clip(TINY, w, frames, 2, 0.9, 0.5)
+    b = O.encode_clip_policy(TINY, w, frames, 2, pol)
+    assert b["seg_start"].tolist() == a["seg_start"].tolist()
+    assert b["cu_tokens"].tolist() == a["cu_tokens"].tolist()
+    assert b["kept_idx"].tolist() == a["kept_idx"].tolist()
+    np.testing.assert_allclose(b["tokens"], a["tokens"], rtol=1e-12, atol=1e-12)
+
+
+def test_paper_policy_end_to_end_bookkeeping(tiny):
+    w, _ = tiny
+    frames = make_clip(TINY, [6, 1, 5], 21, base="uniform", sigma=0.02)
+    pol = dict(alpha=0.9, tau_seg=0.9, tau_merge=0.9, merge_mode="alg1", select_mode="decoupled", ratio=0.25)
+    r = O.encode_clip_policy(TINY, w, frames, 2, pol)
+    assert r["seg_start"].tolist() == [0, 6, 7, 12]
+    N = r["n_frames_out"]
+    assert N == len(r["plan"]) and N <= 12 and N >= 3 * 2 - 1
+    r_hat = O.rescaled_count(0.25, 12, 64, N)
+    w_ = 64 // r_hat
+    M = -(-64 // w_)
+    counts = np.diff(r["cu_tokens"])
+    assert all(c == (r_hat if d else M) for c, d in zip(counts, r["frame_dynamic"]))
+    assert r["tokens"].shape == (int(r["cu_tokens"][-1]), 64)
+    for n in range(N):
+        kept = r["kept_idx"][r["cu_tokens"][n]:r["cu_tokens"][n + 1]]
+        assert np.all(np.diff(kept) > 0)
+    # an output frame's tokens depend only on its own source frames and kept positions:
+    # re-encoding the single-frame middle segment alone gives the same tokens for that frame
+    n_mid = [i for i, p in enumerate(r["plan"]) if p["segment"] == 1][0]
+    kept_mid = r["kept_idx"][r["cu_tokens"][n_mid]:r["cu_tokens"][n_mid + 1]]
+    solo = O.encode_clip_policy(TINY, w, frames[6:7], 2, pol, force_kept=[kept_mid])
+    np.testing.assert_allclose(solo["tokens"], r["tokens"][r["cu_tokens"][n_mid]:r["cu_tokens"][n_mid + 1]],
+                               rtol=1e-10, atol=1e-10)
