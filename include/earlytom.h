@@ -122,6 +122,50 @@ int32_t et_keep_count(int32_t L, float keep_ratio);
 
 const char *et_last_error(void); /* thread-local, never NULL */
 
+/* ---- the paper-exact compression forms -------------------------------------------------
+ * A policy selects, per stage, between the simple form used by et_encode_clip / et_merge_select
+ * and the form the paper describes:
+ *   merge_mode   ET_MERGE_MEAN: a segment becomes one frame (per-position mean).
+ *                ET_MERGE_ALG1: Alg. 1 — head and tail frame of a segment are kept, middle frames
+ *                are walked left to right and (F_i, F_{i+1}) are fused with weights
+ *                (s_i, s_{i+1}) / (s_i + s_{i+1}) iff s_i > tau_merge and s_i > s_{i+1} (Eq. 2-3),
+ *                s_i = Sim(F_i, F_{i+1}); a pair is eligible only if both are middle frames.
+ *   select_mode  ET_SELECT_UNIFORM: every output frame keeps k = et_keep_count(L, ratio) tokens.
+ *                ET_SELECT_DECOUPLED: Alg. 2 — head/tail ("dynamic") frames keep the top r_hat
+ *                tokens, r_hat = clamp(floor(ratio*T*L/N + 0.5), 1, L) (this library's reading of
+ *                Eq. 5: `ratio` is the overall retention relative to the T*L input tokens); other
+ *                ("static") frames keep the arg-max of each of ceil(L / w) windows of
+ *                w = floor(L / r_hat) consecutive positions (Eq. 6).
+ *   alpha        smoothing factor of Eq. 1 in (0, 1]; the smoothed similarity restarts at every
+ *                segment start.  tau_seg: segment threshold.  tau_merge: Eq. 2 threshold.
+ * Scores, tie-breaks and ordering are those of the simple path.  With these forms output frames
+ * keep different token counts: cu_tokens_dev is ragged, seg_start_dev has n_segments + 1 entries
+ * and n_frames_out counts output frames (>= segments). */
+enum { ET_MERGE_MEAN = 0, ET_MERGE_ALG1 = 1 };
+enum { ET_SELECT_UNIFORM = 0, ET_SELECT_DECOUPLED = 1 };
+typedef struct {
+  int32_t merge_mode, select_mode;
+  float alpha, tau_seg, tau_merge, ratio;
+} et_policy;
+
+/* Optional description of the output frames (device arrays of capacity T, or NULL). */
+typedef struct {
+  int32_t *frame_first_dev;   /* first input frame merged into output frame n                  */
+  int32_t *frame_count_dev;   /* number of consecutive input frames merged into it             */
+  int32_t *frame_dynamic_dev; /* 1 = head or tail frame of its segment ("dynamic"), 0 = static */
+  int32_t n_segments;         /* HOST, valid on return                                         */
+} et_plan_out;
+
+/* et_merge_select / et_encode_clip under a policy.  Same buffers, workspace sizes and
+ * synchronisation as the simple entry points; `plan` may be NULL.  Errors as there, plus
+ * INVALID_ARG for alpha outside (0, 1], NaN thresholds, ratio outside (0, 1] or unknown modes. */
+int et_merge_select_policy(const uint16_t *x_dev, int32_t T, int32_t L, int32_t D, const et_policy *policy,
+                           void *workspace_dev, size_t workspace_bytes, void *hip_stream, et_output *out,
+                           et_plan_out *plan);
+int et_encode_clip_policy(et_encoder *enc, const float *frames_dev, int32_t T, int32_t merge_layer,
+                          const et_policy *policy, void *workspace_dev, size_t workspace_bytes,
+                          void *hip_stream, et_output *out, et_plan_out *plan);
+
 /* ---- per-kernel timing (optional) ----------------------------------------------------
  * With profiling on, et_encode_clip brackets every kernel launch with HIP events on
  * `hip_stream` and accumulates elapsed time and launch counts per kernel kind.  Off by

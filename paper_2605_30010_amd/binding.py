@@ -44,6 +44,20 @@ class _Output(C.Structure):
                 ("n_frames_out", C.c_int32), ("n_tokens", C.c_int32)]
 
 
+class _Policy(C.Structure):
+    _fields_ = [("merge_mode", C.c_int32), ("select_mode", C.c_int32), ("alpha", C.c_float),
+                ("tau_seg", C.c_float), ("tau_merge", C.c_float), ("ratio", C.c_float)]
+
+
+class _PlanOut(C.Structure):
+    _fields_ = [("frame_first_dev", C.c_void_p), ("frame_count_dev", C.c_void_p),
+                ("frame_dynamic_dev", C.c_void_p), ("n_segments", C.c_int32)]
+
+
+ET_MERGE_MEAN, ET_MERGE_ALG1 = 0, 1
+ET_SELECT_UNIFORM, ET_SELECT_DECOUPLED = 0, 1
+
+
 def library_path():
     return _LIB_PATH
 
@@ -63,6 +77,10 @@ def load_library():
         "et_keep_count": (i32, [i32, f32]),
         "et_merge_workspace_bytes": (sz, [i32, i32, i32]),
         "et_merge_select": (C.c_int, [vp, i32, i32, i32, f32, f32, vp, sz, vp, C.POINTER(_Output)]),
+        "et_merge_select_policy": (C.c_int, [vp, i32, i32, i32, C.POINTER(_Policy), vp, sz, vp,
+                                            C.POINTER(_Output), C.POINTER(_PlanOut)]),
+        "et_encode_clip_policy": (C.c_int, [vp, vp, i32, i32, C.POINTER(_Policy), vp, sz, vp,
+                                           C.POINTER(_Output), C.POINTER(_PlanOut)]),
         "et_frame_similarity": (C.c_int, [vp, i32, i32, i32, vp, vp, vp]),
         "et_segment_scan": (C.c_int, [vp, i32, f32, vp, vp, vp]),
         "et_segment_mean": (C.c_int, [vp, i32, i32, i32, vp, vp, vp, vp, vp]),
@@ -164,6 +182,69 @@ def et_merge_select(x, sim_threshold, keep_ratio, workspace=None, outputs=None, 
     _check(lib.et_merge_select(_ptr(x), T, L, D, float(sim_threshold), float(keep_ratio), _ptr(workspace),
                                workspace.numel(), _stream(stream), C.byref(o)))
     return _trim(bufs, o, T)
+
+
+def _policy_struct(policy):
+    """policy: dict with merge_mode ("mean" | "alg1"), select_mode ("uniform" | "decoupled"), alpha,
+    tau_seg, tau_merge, ratio."""
+    p = _Policy()
+    p.merge_mode = {"mean": ET_MERGE_MEAN, "alg1": ET_MERGE_ALG1}[policy["merge_mode"]]
+    p.select_mode = {"uniform": ET_SELECT_UNIFORM, "decoupled": ET_SELECT_DECOUPLED}[policy["select_mode"]]
+    p.alpha, p.tau_seg = float(policy["alpha"]), float(policy["tau_seg"])
+    p.tau_merge, p.ratio = float(policy["tau_merge"]), float(policy["ratio"])
+    return p
+
+
+def _plan_bufs(T, device):
+    bufs = {k: torch.empty((T,), dtype=torch.int32, device=device)
+            for k in ("frame_first", "frame_count", "frame_dynamic")}
+    po = _PlanOut()
+    po.frame_first_dev = bufs["frame_first"].data_ptr()
+    po.frame_count_dev = bufs["frame_count"].data_ptr()
+    po.frame_dynamic_dev = bufs["frame_dynamic"].data_ptr()
+    return bufs, po
+
+
+def _trim_policy(bufs, o, plan_bufs, po, T):
+    n, nt, ns = int(o.n_frames_out), int(o.n_tokens), int(po.n_segments)
+    res = dict(n_frames_out=n, n_tokens=nt, n_segments=ns, tokens=bufs["tokens"][:nt],
+               kept_idx=bufs["kept_idx"][:nt], cu_tokens=bufs["cu_tokens"][:n + 1],
+               seg_start=bufs["seg_start"][:ns + 1], frame_sim=bufs["frame_sim"][:max(T - 1, 0)])
+    for k, v in plan_bufs.items():
+        res[k] = v[:n]
+    return res
+
+
+def et_merge_select_policy(x, policy, workspace=None, stream=None):
+    """Paper-exact compression stage on x (bf16 CUDA [T, L, D]) under `policy` (see _policy_struct)."""
+    lib = load_library()
+    _dev(x, torch.bfloat16, "x")
+    T, L, D = x.shape
+    if workspace is None:
+        workspace = torch.empty((max(et_merge_workspace_bytes(T, L, D), 1),), dtype=torch.uint8, device=x.device)
+    bufs = _alloc_outputs(T, L, D, x.device)
+    o = _out_struct(bufs)
+    plan_bufs, po = _plan_bufs(T, x.device)
+    pol = _policy_struct(policy)
+    _check(lib.et_merge_select_policy(_ptr(x), T, L, D, C.byref(pol), _ptr(workspace), workspace.numel(),
+                                      _stream(stream), C.byref(o), C.byref(po)))
+    return _trim_policy(bufs, o, plan_bufs, po, T)
+
+
+def et_encode_clip_policy(handle, frames, merge_layer, policy, L, D, workspace=None, stream=None):
+    lib = load_library()
+    _dev(frames, torch.float32, "frames")
+    T = frames.shape[0]
+    if workspace is None:
+        workspace = torch.empty((max(et_workspace_bytes(handle, T), 1),), dtype=torch.uint8,
+                                device=frames.device)
+    bufs = _alloc_outputs(T, L, D, frames.device)
+    o = _out_struct(bufs)
+    plan_bufs, po = _plan_bufs(T, frames.device)
+    pol = _policy_struct(policy)
+    _check(lib.et_encode_clip_policy(handle, _ptr(frames), T, int(merge_layer), C.byref(pol), _ptr(workspace),
+                                     workspace.numel(), _stream(stream), C.byref(o), C.byref(po)))
+    return _trim_policy(bufs, o, plan_bufs, po, T)
 
 
 def et_frame_similarity(x, stream=None):
@@ -380,6 +461,14 @@ class Encoder:
             self._bufs[T] = _alloc_outputs(T, L, D, self.device)
         return et_encode_clip(self.handle, frames, merge_layer, sim_threshold, keep_ratio, L, D,
                               workspace=self._ws, outputs=self._bufs[T], stream=stream)
+
+    def encode_policy(self, frames, merge_layer, policy, stream=None):
+        T = frames.shape[0]
+        need = et_workspace_bytes(self.handle, T)
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = torch.empty((need,), dtype=torch.uint8, device=self.device)
+        return et_encode_clip_policy(self.handle, frames, merge_layer, policy, self.shape.tokens_per_frame,
+                                     self.shape.d_model, workspace=self._ws, stream=stream)
 
     def close(self):
         if self.handle is not None:

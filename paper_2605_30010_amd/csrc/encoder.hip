@@ -106,15 +106,18 @@ static EncWs carve_encoder(const et_encoder *e, void *ws, int T) {
 #define ET_TIMED(kind, call) ET_TIMED_P(&e->prof, kind, call)
 
 static int run_block(et_encoder *e, const LayerDev &lw, const EncWs &w, int rows, const int32_t *cu,
-                     int n_frames, int max_len, hipStream_t s) {
+                     int n_frames, int max_len, bool ragged, hipStream_t s) {
   const et_config &c = e->cfg;
   const int D = e->D;
   ET_TIMED(ET_K_LAYERNORM, launch_layernorm(w.x, lw.ln1_g, lw.ln1_b, c.ln_eps, rows, D, w.xn, s));
   GemmArgs g;
   g = GemmArgs{w.xn, D, lw.wqkv, lw.bqkv, nullptr, 0, 1, w.qkv, 3 * D, rows, 3 * D, D, EPI_BIAS};
   ET_TIMED(ET_K_GEMM_QKV, launch_gemm(g, s));
-  (void)cu;   // every frame has max_len tokens on this path
-  ET_TIMED(ET_K_ATTENTION, launch_attention_uniform(w.qkv, n_frames, max_len, c.n_heads, e->hd, w.vt, w.att, s));
+  if (ragged) {   // frames of different lengths (decoupled selection): the general kernel
+    ET_TIMED(ET_K_ATTENTION, launch_attention(w.qkv, cu, n_frames, max_len, c.n_heads, e->hd, w.att, s));
+  } else {        // every frame has max_len tokens
+    ET_TIMED(ET_K_ATTENTION, launch_attention_uniform(w.qkv, n_frames, max_len, c.n_heads, e->hd, w.vt, w.att, s));
+  }
   g = GemmArgs{w.att, D, lw.wo, lw.bo, w.x, D, rows, w.x, D, rows, D, D, EPI_BIAS_RES};
   ET_TIMED(ET_K_GEMM_OUT, launch_gemm(g, s));
   ET_TIMED(ET_K_LAYERNORM, launch_layernorm(w.x, lw.ln2_g, lw.ln2_b, c.ln_eps, rows, D, w.xn, s));
@@ -226,9 +229,13 @@ size_t et_workspace_bytes(const et_encoder *e, int32_t T) {
   return carve_encoder(e, nullptr, T).bytes;
 }
 
-int et_encode_clip(et_encoder *e, const float *frames_dev, int32_t T, int32_t merge_layer,
-                   float sim_threshold, float keep_ratio, void *workspace_dev, size_t workspace_bytes,
-                   void *hip_stream, et_output *out) {
+}  // extern "C"
+
+// Shared body of et_encode_clip (policy == nullptr: simple stage with sim_threshold / keep_ratio)
+// and et_encode_clip_policy.
+static int encode_impl(et_encoder *e, const float *frames_dev, int32_t T, int32_t merge_layer,
+                       float sim_threshold, float keep_ratio, const et_policy *policy, void *workspace_dev,
+                       size_t workspace_bytes, void *hip_stream, et_output *out, et_plan_out *plan) {
   ET_REQUIRE(e != nullptr, "encoder is NULL");
   ET_REQUIRE(frames_dev != nullptr, "frames_dev is NULL");
   ET_REQUIRE(T >= 1 && T <= e->max_frames, "T = %d outside [1, max_frames = %d]", T, e->max_frames);
@@ -238,7 +245,10 @@ int et_encode_clip(et_encoder *e, const float *frames_dev, int32_t T, int32_t me
   ET_REQUIRE(out->tokens_dev && out->kept_idx_dev && out->cu_tokens_dev && out->seg_start_dev,
              "an output buffer is NULL (tokens_dev, kept_idx_dev, cu_tokens_dev, seg_start_dev are required)");
   const bool compress = merge_layer >= 0;
-  if (compress) {
+  if (compress && policy) {
+    int prc = check_policy(policy);
+    if (prc) return prc;
+  } else if (compress) {
     ET_REQUIRE(!isnan(sim_threshold), "sim_threshold is NaN");
     ET_REQUIRE(keep_ratio > 0.f && keep_ratio <= 1.f, "keep_ratio = %g outside (0, 1]", (double)keep_ratio);
   }
@@ -263,6 +273,7 @@ int et_encode_clip(et_encoder *e, const float *frames_dev, int32_t T, int32_t me
   ET_TIMED(ET_K_GEMM_PATCH, launch_gemm(g, s));
 
   int rows = T * L, n_frames = T, max_len = L, k = L;
+  (void)k;
   const int32_t *cu = w.cu_full;
   if (!compress) {
     ET_TIMED(ET_K_MISC, launch_identity_maps(T, L, out->kept_idx_dev, out->cu_tokens_dev,
@@ -272,31 +283,55 @@ int et_encode_clip(et_encoder *e, const float *frames_dev, int32_t T, int32_t me
     ET_TIMED(ET_K_MISC, launch_cu_uniform(T, L, w.cu_full, s));
   }
 
+  bool ragged = false;
+  int n_segments = T;
   for (int i = 0; i <= c.n_layers; ++i) {
     if (compress && i == merge_layer) {
-      k = et_keep_count(L, keep_ratio);
       const MergeWs mw = carve_merge(w.merge, T, L, D);
-      int rc = enqueue_merge_stage(w.x, T, L, D, sim_threshold, k, mw, out->frame_sim_dev, out->seg_start_dev,
-                                   out->kept_idx_dev, out->cu_tokens_dev, w.x, s, &e->prof);
-      if (rc) return rc;
-      int32_t n_seg = 0;
-      ET_HIP(hipMemcpyAsync(&n_seg, mw.n_seg, sizeof(int32_t), hipMemcpyDeviceToHost, s));
-      ET_HIP(hipStreamSynchronize(s));
-      if (n_seg < 1 || n_seg > T) {
-        set_error("segment count %d read back from the device is outside [1, T = %d]", n_seg, T);
-        return ET_ERR_HIP;
+      if (policy) {
+        int32_t *info = mw.n_seg + 8;
+        int rc = enqueue_policy_stage(w.x, T, L, D, *policy, mw, out->frame_sim_dev, out->seg_start_dev,
+                                      out->kept_idx_dev, out->cu_tokens_dev, w.x, info, s, &e->prof);
+        if (rc) return rc;
+        int32_t hi[5] = {0, 0, 0, 0, 0};
+        ET_HIP(hipMemcpyAsync(hi, info, sizeof(hi), hipMemcpyDeviceToHost, s));
+        ET_HIP(hipStreamSynchronize(s));
+        if (hi[0] < 1 || hi[0] > T || hi[2] < hi[0] || hi[2] > T * L || hi[3] < 1 || hi[3] > L || hi[4] < 1 ||
+            hi[4] > L) {
+          set_error("plan read back from the device is inconsistent (N = %d, tokens = %d)", hi[0], hi[2]);
+          return ET_ERR_HIP;
+        }
+        if ((rc = copy_plan_out(mw, hi[0], plan, s))) return rc;
+        n_frames = hi[0];
+        n_segments = hi[1];
+        rows = hi[2];
+        max_len = hi[3] > hi[4] ? hi[3] : hi[4];
+        ragged = policy->select_mode == ET_SELECT_DECOUPLED && hi[3] != hi[4];
+      } else {
+        k = et_keep_count(L, keep_ratio);
+        int rc = enqueue_merge_stage(w.x, T, L, D, sim_threshold, k, mw, out->frame_sim_dev, out->seg_start_dev,
+                                     out->kept_idx_dev, out->cu_tokens_dev, w.x, s, &e->prof);
+        if (rc) return rc;
+        int32_t n_seg = 0;
+        ET_HIP(hipMemcpyAsync(&n_seg, mw.n_seg, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+        ET_HIP(hipStreamSynchronize(s));
+        if (n_seg < 1 || n_seg > T) {
+          set_error("segment count %d read back from the device is outside [1, T = %d]", n_seg, T);
+          return ET_ERR_HIP;
+        }
+        n_frames = n_segments = n_seg;
+        rows = n_seg * k;
+        max_len = k;
       }
-      n_frames = n_seg;
-      rows = n_seg * k;
-      max_len = k;
       cu = out->cu_tokens_dev;
       e->prof.phase = 1;
     }
     if (i < c.n_layers) {
-      int rc = run_block(e, e->layers[i], w, rows, cu, n_frames, max_len, s);
+      int rc = run_block(e, e->layers[i], w, rows, cu, n_frames, max_len, ragged, s);
       if (rc) return rc;
     }
   }
+  if (plan) plan->n_segments = n_segments;
   if (c.has_final_ln) {
     ET_TIMED(ET_K_LAYERNORM, launch_layernorm(w.x, e->final_g, e->final_b, c.ln_eps, rows, D,
                                               out->tokens_dev, s));
@@ -309,6 +344,23 @@ int et_encode_clip(et_encoder *e, const float *frames_dev, int32_t T, int32_t me
   out->n_frames_out = n_frames;
   out->n_tokens = rows;
   return ET_OK;
+}
+
+extern "C" {
+
+int et_encode_clip(et_encoder *e, const float *frames_dev, int32_t T, int32_t merge_layer,
+                   float sim_threshold, float keep_ratio, void *workspace_dev, size_t workspace_bytes,
+                   void *hip_stream, et_output *out) {
+  return encode_impl(e, frames_dev, T, merge_layer, sim_threshold, keep_ratio, nullptr, workspace_dev,
+                     workspace_bytes, hip_stream, out, nullptr);
+}
+
+int et_encode_clip_policy(et_encoder *e, const float *frames_dev, int32_t T, int32_t merge_layer,
+                          const et_policy *policy, void *workspace_dev, size_t workspace_bytes,
+                          void *hip_stream, et_output *out, et_plan_out *plan) {
+  ET_REQUIRE(merge_layer < 0 || policy != nullptr, "policy is NULL");
+  return encode_impl(e, frames_dev, T, merge_layer, 0.f, 1.f, policy, workspace_dev, workspace_bytes,
+                     hip_stream, out, plan);
 }
 
 int et_profile_enable(et_encoder *e, int32_t on) {

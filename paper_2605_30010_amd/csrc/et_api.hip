@@ -46,6 +46,10 @@ MergeWs carve_merge(void *ws, int T, int L, int D) {
   m.sim = c.take<float>((size_t)T);
   m.score = c.take<float>((size_t)T * L);
   m.n_seg = c.take<int32_t>(64);
+  m.frame_first = c.take<int32_t>((size_t)T);
+  m.frame_count = c.take<int32_t>((size_t)T);
+  m.frame_dyn = c.take<int32_t>((size_t)T);
+  m.frame_w = c.take<float>((size_t)2 * T);
   m.merged = c.take<uint16_t>((size_t)T * L * D);
   m.bytes = c.off;
   return m;
@@ -77,6 +81,44 @@ int enqueue_merge_stage(const uint16_t *x, int T, int L, int D, float tau, int k
   ET_TIMED_P(prof, ET_K_MERGE, launch_segment_mean(x, T, L, D, seg_start, w.n_seg, w.merged, w.score, s));
   ET_TIMED_P(prof, ET_K_SELECT, launch_topk(w.score, T, w.n_seg, L, k, kept, cu_tokens, s));
   ET_TIMED_P(prof, ET_K_COMPACT, launch_compact(w.merged, kept, T, w.n_seg, L, D, k, packed, s));
+  return ET_OK;
+}
+
+int check_policy(const et_policy *p) {
+  ET_REQUIRE(p != nullptr, "policy is NULL");
+  ET_REQUIRE(p->merge_mode == ET_MERGE_MEAN || p->merge_mode == ET_MERGE_ALG1, "merge_mode = %d unknown", p->merge_mode);
+  ET_REQUIRE(p->select_mode == ET_SELECT_UNIFORM || p->select_mode == ET_SELECT_DECOUPLED,
+             "select_mode = %d unknown", p->select_mode);
+  ET_REQUIRE(p->alpha > 0.f && p->alpha <= 1.f, "alpha = %g outside (0, 1]", (double)p->alpha);
+  ET_REQUIRE(!isnan(p->tau_seg) && !isnan(p->tau_merge), "a threshold is NaN");
+  ET_REQUIRE(p->ratio > 0.f && p->ratio <= 1.f, "ratio = %g outside (0, 1]", (double)p->ratio);
+  return ET_OK;
+}
+
+int enqueue_policy_stage(const uint16_t *x, int T, int L, int D, const et_policy &pol, const MergeWs &w,
+                         float *sim_out, int32_t *seg_start, int32_t *kept, int32_t *cu_tokens,
+                         uint16_t *packed, int32_t *info, hipStream_t s, Profiler *prof) {
+  float *sim = sim_out ? sim_out : w.sim;
+  const PolicyArgs pa{pol.merge_mode, pol.select_mode, pol.alpha, pol.tau_seg, pol.tau_merge, pol.ratio};
+  const int k_uniform = et_keep_count(L, pol.ratio);
+  ET_TIMED_P(prof, ET_K_SIMILARITY, launch_similarity(x, T, L, D, w.cos, s));
+  ET_TIMED_P(prof, ET_K_SCAN, launch_sim_mean_scan(w.cos, T, L, 0.f, sim, nullptr, nullptr, true, false, s));
+  ET_TIMED_P(prof, ET_K_SCAN, launch_plan(sim, T, L, pa, k_uniform, seg_start, w.frame_first, w.frame_count,
+                                          w.frame_dyn, w.frame_w, cu_tokens, info, s));
+  ET_TIMED_P(prof, ET_K_MERGE, launch_plan_merge(x, T, L, D, info, w.frame_first, w.frame_count, w.frame_w,
+                                                 pol.merge_mode == ET_MERGE_MEAN, w.merged, w.score, s));
+  ET_TIMED_P(prof, ET_K_SELECT, launch_select_policy(w.score, T, info, w.frame_dyn, cu_tokens, L,
+                                                     pol.select_mode == ET_SELECT_UNIFORM, kept, s));
+  ET_TIMED_P(prof, ET_K_COMPACT, launch_compact_ragged(w.merged, kept, T, info, cu_tokens, L, D, packed, s));
+  return ET_OK;
+}
+
+int copy_plan_out(const MergeWs &w, int N, et_plan_out *plan, hipStream_t s) {
+  if (!plan || N <= 0) return ET_OK;
+  const size_t bytes = (size_t)N * sizeof(int32_t);
+  if (plan->frame_first_dev) ET_HIP(hipMemcpyAsync(plan->frame_first_dev, w.frame_first, bytes, hipMemcpyDeviceToDevice, s));
+  if (plan->frame_count_dev) ET_HIP(hipMemcpyAsync(plan->frame_count_dev, w.frame_count, bytes, hipMemcpyDeviceToDevice, s));
+  if (plan->frame_dynamic_dev) ET_HIP(hipMemcpyAsync(plan->frame_dynamic_dev, w.frame_dyn, bytes, hipMemcpyDeviceToDevice, s));
   return ET_OK;
 }
 
@@ -165,6 +207,39 @@ int et_merge_select(const uint16_t *x_dev, int32_t T, int32_t L, int32_t D, floa
   ET_HIP(hipStreamSynchronize(s));
   out->n_frames_out = n_seg;
   out->n_tokens = n_seg * k;
+  return ET_OK;
+}
+
+int et_merge_select_policy(const uint16_t *x_dev, int32_t T, int32_t L, int32_t D, const et_policy *policy,
+                           void *workspace_dev, size_t workspace_bytes, void *hip_stream, et_output *out,
+                           et_plan_out *plan) {
+  int rc;
+  ET_REQUIRE(x_dev != nullptr, "x_dev is NULL");
+  if ((rc = check_merge_shape(T, L, D))) return rc;
+  if ((rc = check_outputs(out))) return rc;
+  if ((rc = check_policy(policy))) return rc;
+  ET_REQUIRE(workspace_dev != nullptr, "workspace_dev is NULL");
+  size_t need = et_merge_workspace_bytes(T, L, D);
+  if (workspace_bytes < need) {
+    set_error("workspace of %zu bytes is smaller than the %zu needed", workspace_bytes, need);
+    return ET_ERR_WORKSPACE;
+  }
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  MergeWs w = carve_merge(workspace_dev, T, L, D);
+  int32_t *info = w.n_seg + 8;
+  if ((rc = enqueue_policy_stage(x_dev, T, L, D, *policy, w, out->frame_sim_dev, out->seg_start_dev,
+                                 out->kept_idx_dev, out->cu_tokens_dev, out->tokens_dev, info, s, nullptr)))
+    return rc;
+  int32_t host_info[5] = {0, 0, 0, 0, 0};
+  ET_HIP(hipMemcpyAsync(host_info, info, sizeof(host_info), hipMemcpyDeviceToHost, s));
+  ET_HIP(hipStreamSynchronize(s));
+  if ((rc = copy_plan_out(w, host_info[0], plan, s))) return rc;
+  if (plan) {
+    plan->n_segments = host_info[1];
+    ET_HIP(hipStreamSynchronize(s));
+  }
+  out->n_frames_out = host_info[0];
+  out->n_tokens = host_info[2];
   return ET_OK;
 }
 

@@ -130,9 +130,24 @@ struct Profiler {
 struct MergeWs {
   float *cos, *sim, *score;
   uint16_t *merged;
-  int32_t *n_seg;
+  int32_t *n_seg;                 // 64 ints: [0] segment count of the simple path; [8..12] policy info
+  int32_t *frame_first, *frame_count, *frame_dyn;   // [T] each: output-frame plan (policy path)
+  float *frame_w;                 // [2T]
   size_t bytes;
 };
+
+// Policy of the paper-exact stage as the kernels take it (mirrors et_policy).
+struct PolicyArgs {
+  int merge_mode, select_mode;
+  float alpha, tau_seg, tau_merge, ratio;
+};
+int check_policy(const et_policy *p);
+// Enqueues similarity -> plan -> weighted merge -> selection -> ragged gather; no host sync.
+// info (device, >= 5 ints) receives N, segments, total tokens, tokens per dynamic / static frame.
+int enqueue_policy_stage(const uint16_t *x, int T, int L, int D, const et_policy &pol, const MergeWs &w,
+                         float *sim_out, int32_t *seg_start, int32_t *kept, int32_t *cu_tokens,
+                         uint16_t *packed, int32_t *info, hipStream_t s, struct Profiler *prof);
+int copy_plan_out(const MergeWs &w, int N, et_plan_out *plan, hipStream_t s);
 MergeWs carve_merge(void *ws, int T, int L, int D);
 // Enqueues similarity -> scan -> segment mean (+score) -> top-k -> compaction; no host sync.
 int enqueue_merge_stage(const uint16_t *x, int T, int L, int D, float tau, int k, const MergeWs &w,
@@ -155,6 +170,18 @@ int launch_identity_maps(int T, int L, int32_t *kept, int32_t *cu_tokens, int32_
 int launch_cu_uniform(int n, int step, int32_t *cu, hipStream_t s);
 // Fills with bf16 values in (-1, 1) from a counter hash (benchmark operands only).
 int launch_fill_random_bf16(uint16_t *p, size_t n, uint32_t seed, hipStream_t s);
+
+// ---- launchers implemented in policy_kernels.hip ----
+int launch_plan(const float *sim, int T, int L, const PolicyArgs &p, int k_uniform, int32_t *seg_start,
+                int32_t *frame_first, int32_t *frame_count, int32_t *frame_dyn, float *frame_w,
+                int32_t *cu_tokens, int32_t *info, hipStream_t s);
+int launch_plan_merge(const uint16_t *x, int T, int L, int D, const int32_t *info, const int32_t *frame_first,
+                      const int32_t *frame_count, const float *frame_w, bool uniform_mean, uint16_t *merged,
+                      float *score, hipStream_t s);
+int launch_select_policy(const float *score, int T, const int32_t *info, const int32_t *frame_dyn,
+                         const int32_t *cu_tokens, int L, bool all_topk, int32_t *kept, hipStream_t s);
+int launch_compact_ragged(const uint16_t *merged, const int32_t *kept, int T, const int32_t *info,
+                          const int32_t *cu_tokens, int L, int D, uint16_t *out, hipStream_t s);
 
 // ---- launchers implemented in dense_kernels.hip ----
 int launch_layernorm(const uint16_t *x, const float *g, const float *b, float eps, int rows, int D,

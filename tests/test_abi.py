@@ -130,3 +130,21 @@ def test_no_cpu_fallback_when_library_missing(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_LIB_PATH", str(tmp_path / "absent.so"))
     with pytest.raises(ImportError):
         B.load_library()
+
+
+def test_policy_entry_points_reject_bad_arguments():
+    lib = et.load_library()
+    fake = C.c_void_p(4096)
+    out = B._Output()
+    out.tokens_dev = out.kept_idx_dev = out.cu_tokens_dev = out.seg_start_dev = 4096
+    good = B._Policy(merge_mode=1, select_mode=1, alpha=0.9, tau_seg=0.8, tau_merge=0.8, ratio=0.2)
+    call = lambda pol: lib.et_merge_select_policy(fake, 4, 8, 64, pol, fake, 1 << 30, None, C.byref(out), None)
+    assert call(None) == -1 and "policy" in et.et_last_error()
+    for field, bad in (("merge_mode", 7), ("select_mode", -1), ("alpha", 0.0), ("alpha", 1.5),
+                       ("tau_seg", math.nan), ("tau_merge", math.nan), ("ratio", 0.0), ("ratio", 2.0)):
+        pol = B._Policy(merge_mode=1, select_mode=1, alpha=0.9, tau_seg=0.8, tau_merge=0.8, ratio=0.2)
+        setattr(pol, field, bad)
+        assert call(C.byref(pol)) == -1, field
+    assert lib.et_merge_select_policy(None, 4, 8, 64, C.byref(good), fake, 1 << 30, None, C.byref(out), None) == -1
+    assert lib.et_merge_select_policy(fake, 4, 8, 64, C.byref(good), fake, 16, None, C.byref(out), None) == -2
+    assert lib.et_encode_clip_policy(None, fake, 4, 2, C.byref(good), fake, 1 << 30, None, C.byref(out), None) == -1

@@ -1,0 +1,198 @@
+"""GPU parity of the paper-exact compression forms (Eq. 1 with smoothing, Alg. 1, Alg. 2) against
+the oracle's *_policy functions, through the C boundary.  Same bars as the simple path: integer
+outputs bit-exact on inputs with safe decision margins, merged tokens within one bf16 step,
+encoder tokens within relative L2 2e-2."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2605_30010_amd as et
+from et_inputs import (TINY, SIGLIP, bf16_bits_to_f32, build_workload, make_clip, make_hidden_states,
+                       scene_lengths_geometric)
+from oracle import earlytom_oracle as O
+from tests._util import bits_to_dev, dev_to_bits, dev_to_f64, bf16_ulp_distance, f64_to_bits, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+POLICIES = [
+    dict(merge_mode="alg1", select_mode="decoupled", alpha=0.9, tau_seg=0.8, tau_merge=0.8, ratio=0.2),
+    dict(merge_mode="alg1", select_mode="uniform", alpha=0.9, tau_seg=0.8, tau_merge=0.8, ratio=0.3),
+    dict(merge_mode="mean", select_mode="decoupled", alpha=1.0, tau_seg=0.9, tau_merge=0.9, ratio=0.1),
+    dict(merge_mode="mean", select_mode="uniform", alpha=1.0, tau_seg=0.9, tau_merge=0.9, ratio=0.3),
+    dict(merge_mode="alg1", select_mode="decoupled", alpha=0.5, tau_seg=0.9, tau_merge=0.995, ratio=0.6),
+]
+
+
+def _f32_policy(p):
+    q = dict(p)
+    for k in ("alpha", "tau_seg", "tau_merge", "ratio"):
+        q[k] = float(np.float32(p[k]))
+    return q
+
+
+def _margins_ok(ref, pol, L):
+    """Decisions are only promised bit-exact away from ties: smoothed similarities 1e-2 from tau_seg,
+    Alg. 1 comparisons s_i vs s_{i+1} 1e-6 apart (float32 similarities agree to ~1e-7), selection gaps (k-th vs next score; best vs second in a window)
+    2e-6 relative, ten times the float32 rounding of a 1152-term sum of squares."""
+    if len(ref["s_hat"]) and np.min(np.abs(ref["s_hat"] - pol["tau_seg"])) < 1e-2:
+        return False
+    s = ref["frame_sim"]
+    if pol["merge_mode"] == "alg1" and len(s) > 1:
+        if np.min(np.abs(np.diff(s))) < 1e-6 or np.min(np.abs(s - pol["tau_merge"])) < 1e-5:
+            return False
+    cu = ref["cu_tokens"]
+    for n, z in enumerate(ref["score"]):
+        k = int(cu[n + 1] - cu[n])
+        if ref["frame_dynamic"][n] or pol["select_mode"] == "uniform":
+            zs = np.sort(z)[::-1]
+            if k < L and (zs[k - 1] - zs[k]) < 2e-6 * zs[k - 1]:
+                return False
+        else:                                          # static frame: top-2 gap inside every window
+            w = -(-L // k) if k > 0 else L
+            w = L // O.rescaled_count(pol["ratio"], len(ref["frame_sim"]) + 1, L, len(ref["plan"]))
+            for lo in range(0, L, w):
+                win = np.sort(z[lo:lo + w])[::-1]
+                if len(win) > 1 and (win[0] - win[1]) < 2e-6 * win[0]:
+                    return False
+    return True
+
+
+def _check_stage(r, ref, exact_tokens=False):
+    assert r["n_frames_out"] == len(ref["plan"])
+    assert r["n_segments"] == len(ref["seg_start"]) - 1
+    assert r["seg_start"].tolist() == ref["seg_start"].tolist()
+    assert r["frame_first"].tolist() == ref["frame_first"].tolist()
+    assert r["frame_count"].tolist() == ref["frame_count"].tolist()
+    assert r["frame_dynamic"].tolist() == ref["frame_dynamic"].tolist()
+    assert r["cu_tokens"].tolist() == ref["cu_tokens"].tolist()
+    assert r["n_tokens"] == int(ref["cu_tokens"][-1])
+    assert np.array_equal(r["kept_idx"].cpu().numpy(), ref["kept_idx"])
+    got_bits = dev_to_bits(r["tokens"])
+    dist = bf16_ulp_distance(got_bits, f64_to_bits(ref["tokens"]))
+    if exact_tokens:
+        assert dist.max() == 0
+    else:
+        # one bf16 step at most, except where a fused pair cancels to almost nothing: there the float32
+        # rounding of w0 x0 + w1 x1 (about 1e-8 absolute) is no longer small against the result
+        got = bf16_bits_to_f32(got_bits).astype(np.float64)
+        assert np.all((dist <= 1) | (np.abs(got - ref["tokens"]) <= 1e-7))
+        # Fused pairs have weights within 1e-5 of 1/2, so (x0 + x1) / 2 of two bf16 values lands on or
+        # next to a bf16 rounding tie for a large share of elements; which way those round depends on
+        # the last float32 bits of the weights.  Hence a looser bound on how many differ (by one step).
+        assert (dist > 0).mean() < 0.05
+
+
+@pytest.mark.parametrize("pi", range(len(POLICIES)))
+@pytest.mark.parametrize("T,L,D,mean_len", [(14, 100, 256, 4), (40, 729, 1152, 6), (33, 64, 64, 5)])
+def test_merge_select_policy_matches_oracle(pi, T, L, D, mean_len):
+    pol = _f32_policy(POLICIES[pi])
+    for variant in range(80):
+        rng = np.random.default_rng(1000 * pi + 10 * T + variant)
+        lengths = scene_lengths_geometric(rng, T, mean_len)
+        bits = make_hidden_states(T, L, D, lengths, 31 * T + variant, sigma=0.1)
+        ref = O.merge_select_policy(bf16_bits_to_f32(bits).astype(np.float64), pol)
+        if _margins_ok(ref, pol, L):
+            break
+    else:
+        pytest.fail("no seed with safe margins")
+    r = et.et_merge_select_policy(bits_to_dev(bits), pol)
+    _check_stage(r, ref)
+    if pol["merge_mode"] == "alg1":
+        assert r["n_frames_out"] >= r["n_segments"]
+    # the default policy is the simple entry point, bit for bit
+    if pol["merge_mode"] == "mean" and pol["select_mode"] == "uniform":
+        simple = et.et_merge_select(bits_to_dev(bits), pol["tau_seg"], pol["ratio"])
+        assert torch.equal(simple["tokens"], r["tokens"]) and torch.equal(simple["kept_idx"], r["kept_idx"])
+        assert simple["cu_tokens"].tolist() == r["cu_tokens"].tolist()
+
+
+def test_policy_degenerate_cases():
+    rng = np.random.default_rng(5)
+    from et_inputs import f32_to_bf16_bits
+    L, D = 48, 128
+    one = f32_to_bf16_bits(rng.standard_normal((1, L, D)).astype(np.float32))
+    pol = _f32_policy(POLICIES[0])
+    ref = O.merge_select_policy(bf16_bits_to_f32(one).astype(np.float64), pol)
+    _check_stage(et.et_merge_select_policy(bits_to_dev(one), pol), ref, exact_tokens=True)
+    # identical frames: similarities tie at 1, the strict rule of Eq. 2 fuses nothing
+    same = np.repeat(one, 7, axis=0)
+    r = et.et_merge_select_policy(bits_to_dev(same), dict(pol, ratio=1.0))
+    assert r["n_segments"] == 1 and r["n_frames_out"] == 7 and r["frame_count"].tolist() == [1] * 7
+    assert r["frame_dynamic"].tolist() == [1, 0, 0, 0, 0, 0, 1]
+    # ratio 1 with nothing merged keeps everything in order
+    many = f32_to_bf16_bits(rng.standard_normal((5, L, D)).astype(np.float32))
+    r = et.et_merge_select_policy(bits_to_dev(many), dict(pol, tau_seg=math.inf, ratio=1.0))
+    assert r["n_frames_out"] == 5 and r["n_tokens"] == 5 * L
+    assert np.array_equal(dev_to_bits(r["tokens"]), many.reshape(5 * L, D))
+    lib = et.load_library()
+    with pytest.raises(et.EtError):
+        et.et_merge_select_policy(bits_to_dev(many), dict(pol, alpha=0.0))
+    with pytest.raises(et.EtError):
+        et.et_merge_select_policy(bits_to_dev(many), dict(pol, ratio=1.5))
+
+
+def _encode_check(shape, w, frames, m, pol, tol=2e-2):
+    T = frames.shape[0]
+    L, D = shape.tokens_per_frame, shape.d_model
+    from dataclasses import replace
+    trunc = et.Encoder(replace(shape, n_layers=m, has_final_ln=0), dict(w, layers=w["layers"][:m]), T)
+    xm = trunc.encode(torch.from_numpy(frames).cuda(), -1, 0.0, 1.0)["tokens"].clone()
+    trunc.close()
+    x_gpu = bf16_bits_to_f32(dev_to_bits(xm)).astype(np.float64).reshape(T, L, D)
+    enc = et.Encoder(shape, w, T)
+    got = enc.encode_policy(torch.from_numpy(frames).cuda(), m, pol)
+    got = {k: (v.clone() if isinstance(v, torch.Tensor) else v) for k, v in got.items()}
+    enc.close()
+    ref = O.encode_clip_policy(shape, w, frames, m, pol, x_at_merge=x_gpu)
+    assert got["seg_start"].tolist() == ref["seg_start"].tolist()
+    assert got["frame_first"].tolist() == ref["frame_first"].tolist()
+    assert got["frame_count"].tolist() == ref["frame_count"].tolist()
+    assert got["cu_tokens"].tolist() == ref["cu_tokens"].tolist()
+    same = np.array_equal(got["kept_idx"].cpu().numpy(), ref["kept_idx"])
+    if not same:      # near-tied scores: separate arithmetic error from rank flips
+        cu = ref["cu_tokens"]
+        kept = got["kept_idx"].cpu().numpy()
+        ref = O.encode_clip_policy(shape, w, frames, m, pol, x_at_merge=x_gpu,
+                                   force_kept=[kept[cu[n]:cu[n + 1]] for n in range(len(cu) - 1)])
+    err = rel_l2(dev_to_f64(got["tokens"]), ref["tokens"])
+    assert err <= tol, err
+    return got, ref, err, same
+
+
+def test_tiny_encoder_with_paper_policy():
+    rec = build_workload("c1_tiny")
+    w = rec["weights"]
+    frames = make_clip(TINY, [6, 1, 5], 21, base="uniform", sigma=0.02)
+    pol = _f32_policy(dict(merge_mode="alg1", select_mode="decoupled", alpha=0.9, tau_seg=0.9, tau_merge=0.9,
+                           ratio=0.25))
+    got, ref, err, same = _encode_check(TINY, w, frames, 2, pol)
+    assert got["seg_start"].tolist() == [0, 6, 7, 12]
+    assert same
+    counts = np.diff(got["cu_tokens"].cpu().numpy())
+    assert len(set(counts.tolist())) == 2                     # ragged: dynamic and static counts differ
+    # the default policy equals the simple entry point bit for bit
+    enc = et.Encoder(TINY, w, 12)
+    a = enc.encode(torch.from_numpy(frames).cuda(), 2, 0.9, 0.5)
+    a = {k: (v.clone() if isinstance(v, torch.Tensor) else v) for k, v in a.items()}
+    b = enc.encode_policy(torch.from_numpy(frames).cuda(), 2,
+                          dict(merge_mode="mean", select_mode="uniform", alpha=1.0, tau_seg=0.9, tau_merge=0.9,
+                               ratio=0.5))
+    assert torch.equal(a["tokens"], b["tokens"]) and torch.equal(a["kept_idx"], b["kept_idx"])
+    enc.close()
+
+
+def test_siglip_32_frames_with_paper_policy():
+    """32-frame SigLIP-shaped clip under the paper's settings (alpha 0.9, three-frame-plus segments
+    fused by Alg. 1, 20 % overall retention with decoupled selection)."""
+    rec = build_workload("c3_siglip_t32")
+    pol = _f32_policy(dict(merge_mode="alg1", select_mode="decoupled", alpha=0.9, tau_seg=0.8, tau_merge=0.8,
+                           ratio=0.2))
+    got, ref, err, same = _encode_check(SIGLIP, rec["weights"], rec["frames"], 8, pol)
+    truth = np.concatenate([[0], np.cumsum(rec["lengths"])]).tolist()
+    assert got["seg_start"].tolist() == truth
+    total_in = 32 * 729
+    assert abs(got["n_tokens"] / total_in - 0.2) < 0.03
+    print("paper policy, 32 frames: N=%d tokens=%d (%.1f%%) rel-L2 %.4g, indices identical: %s"
+          % (got["n_frames_out"], got["n_tokens"], 100.0 * got["n_tokens"] / total_in, err, same))
