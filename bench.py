@@ -55,6 +55,17 @@ def bytes_tables(shape, T, N, k):
     }
 
 
+def measured_traffic(kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary, or None."""
+    path = os.path.join(ROOT, "profiles", "gemm_fc1_c3_siglip_t32_hbm_traffic.md")
+    if kernel != "gemm_fc1@all" or not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.strip().startswith("traffic_bytes_per_launch"):
+            return float(line.split("=")[1])
+    return None
+
+
 def cpu_baseline(rec, sample_frames):
     """The oracle, as it is, on the first `sample_frames` frames of the same clip."""
     import numpy as np
@@ -158,7 +169,8 @@ def main():
         # dominant kernel = largest share of device time
         dom = max((x for x in kernels.items() if "tflops" in x[1]), key=lambda x: x[1]["share"])
         roofline = {"kernel": dom[0], "bound": "mfma", "achieved": dom[1]["tflops"], "peak": PEAK_BF16_TFLOPS,
-                    "unit": "TFLOP/s", "frac": round(dom[1]["tflops"] / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                    "unit": "TFLOP/s", "frac": round(dom[1]["tflops"] / PEAK_BF16_TFLOPS, 4),
+                    "traffic": measured_traffic(dom[0]) if args.workload == "c3_siglip_t32" else None,
                     "avg_us": dom[1]["avg_us"]}
         # the compression stage as one bandwidth figure: 2 reads of X + merged write + gather
         stage_ms = sum(prof[(kk, 0)][0] for kk in ("similarity", "scan", "merge", "select", "compact"))
