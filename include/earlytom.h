@@ -150,8 +150,8 @@ typedef struct {
 
 /* Optional description of the output frames (device arrays of capacity T, or NULL). */
 typedef struct {
-  int32_t *frame_first_dev;   /* first input frame merged into output frame n                  */
-  int32_t *frame_count_dev;   /* number of consecutive input frames merged into it             */
+  int32_t *frame_first_dev;   /* first ORIGINAL input frame behind output frame n              */
+  int32_t *frame_count_dev;   /* number of consecutive original frames behind it               */
   int32_t *frame_dynamic_dev; /* 1 = head or tail frame of its segment ("dynamic"), 0 = static */
   int32_t n_segments;         /* HOST, valid on return                                         */
 } et_plan_out;
@@ -248,6 +248,20 @@ int et_attention_uniform(const uint16_t *qkv_dev, int32_t n_frames, int32_t len,
                          int32_t head_dim, void *scratch_dev, size_t scratch_bytes, uint16_t *out_dev,
                          void *hip_stream);
 size_t et_attention_uniform_scratch_bytes(int32_t n_frames, int32_t len, int32_t n_heads, int32_t head_dim);
+
+/* Stage I at several encoder layers, Stage II once (the paper merges at three layers, e.g. 6, 14,
+ * 20, and selects after the encoder; Table 8).  At every layer of merge_layers[0..n_merge_layers)
+ * (strictly ascending, each <= select_layer) the adjacent-frame similarity of the CURRENT frames
+ * drives Eq. 1 and the merge of policy->merge_mode; frames keep all L tokens.  At select_layer
+ * (after that layer's merge if they coincide) the selection of policy->select_mode runs once:
+ * dynamic flags come from the most recent merge (all frames dynamic if n_merge_layers = 0), the
+ * re-scaled count of Eq. 5 uses the original T.  seg_start_dev and the plan's frame ranges are in
+ * original frame indices.  Synchronises the stream once per merge / select layer and at the end;
+ * frame_sim_dev receives the similarities of the first merge layer only. */
+int et_encode_clip_multi(et_encoder *enc, const float *frames_dev, int32_t T, const int32_t *merge_layers,
+                         int32_t n_merge_layers, int32_t select_layer, const et_policy *policy,
+                         void *workspace_dev, size_t workspace_bytes, void *hip_stream, et_output *out,
+                         et_plan_out *plan);
 
 #ifdef __cplusplus
 }

@@ -439,3 +439,93 @@ def encode_clip(shape, w, frames, merge_layer, sim_threshold, keep_ratio,
                    seg_start=info["seg_start"], frame_sim=info["frame_sim"],
                    hidden_at_merge=info["hidden_at_merge"], score=info["score"])
     return out
+
+
+def encode_clip_multi(shape, w, frames, merge_layers, select_layer, policy, dtype=np.float64,
+                      x_at_layers=None, force_kept=None):
+    """Stage I at several encoder layers, Stage II once (the paper merges at three layers, e.g.
+    [6, 14, 20], and selects after the encoder).
+
+    At every layer in `merge_layers` (ascending) the adjacent-frame similarity of the CURRENT frames
+    drives Eq. 1 and the merge of `policy["merge_mode"]`; frames keep all L tokens.  At `select_layer`
+    (>= the last merge layer; after that layer's merge if they coincide) the selection of
+    `policy["select_mode"]` runs once: dynamic flags come from the most recent merge (every frame is
+    dynamic if there was none), the re-scaled count uses the ORIGINAL frame count.
+    `x_at_layers` (optional dict layer -> [frames, L, D]) replaces the hidden states seen at a merge /
+    select layer (stage-wise parity); a block whose output would be replaced that way is not evaluated.
+    Returns tokens, kept_idx, cu_tokens, frame_first / frame_count (ranges of original frames),
+    frame_dynamic, seg_start (original frame index of each segment start of the last merge),
+    n_frames_out, hidden (dict of the states seen at each layer), stages (per merge layer: frame_sim,
+    s_hat, n_frames) and score (the selection scores)."""
+    n_layers = len(w["layers"])
+    T0 = frames.shape[0]
+    L = shape.tokens_per_frame
+    x = patch_embed(frames, w, shape.patch, dtype)
+    first = np.arange(T0, dtype=np.int64)
+    count = np.ones(T0, dtype=np.int64)
+    dyn = np.ones(T0, dtype=np.int32)
+    seg_orig = np.arange(T0 + 1, dtype=np.int64)
+    hidden, rows, cu, kept = {}, None, None, None
+    merge_layers = list(merge_layers)
+    stage_layers = sorted(set(merge_layers) | {select_layer})
+    stages, score = {}, None
+
+    def replaced_later(i):
+        nxt = [j for j in stage_layers if j > i]
+        return bool(nxt) and x_at_layers is not None and nxt[0] in x_at_layers
+    for i in range(n_layers + 1):
+        if rows is None and (i in merge_layers or i == select_layer):
+            if x_at_layers is not None and i in x_at_layers:
+                x = np.asarray(x_at_layers[i], dtype=dtype)
+                if x.shape[0] != len(first):
+                    raise ValueError("x_at_layers[%d] holds %d frames, the plan so far gives %d"
+                                     % (i, x.shape[0], len(first)))
+            hidden[i] = x
+            z = None
+            if i in merge_layers:
+                Tc = x.shape[0]
+                s = frame_similarity(x)[1] if Tc > 1 else np.zeros((0,), dtype)
+                seg, s_hat = ema_segment_starts(s, policy["alpha"], policy["tau_seg"], Tc)
+                plan = merge_plan(s, seg, policy["tau_merge"], policy["merge_mode"])
+                x = apply_plan(x, plan)
+                z = token_score(x)
+                stages[i] = dict(frame_sim=s, s_hat=s_hat, n_frames=len(plan), merged=x)
+                ends = first + count
+                seg_orig = np.asarray([first[a] for a in seg[:-1]] + [T0], dtype=np.int64)
+                nf = np.asarray([first[p["first"]] for p in plan], dtype=np.int64)
+                ne = np.asarray([ends[p["first"] + p["count"] - 1] for p in plan], dtype=np.int64)
+                first, count = nf, ne - nf
+                dyn = np.asarray([p["dynamic"] for p in plan], dtype=np.int32)
+            if i == select_layer:
+                if z is None:
+                    z = token_score(x)
+                N = x.shape[0]
+                score = z
+                if force_kept is not None:
+                    per_frame = [np.asarray(p, dtype=np.int32) for p in force_kept]
+                elif policy["select_mode"] == "uniform":
+                    k = keep_count(L, policy["ratio"])
+                    per_frame = [topk_positions(z[n], k) for n in range(N)]
+                else:
+                    r_hat = rescaled_count(policy["ratio"], T0, L, N)
+                    per_frame = [topk_positions(z[n], r_hat) if dyn[n] else window_positions(z[n], r_hat)
+                                 for n in range(N)]
+                cu = np.concatenate([[0], np.cumsum([len(p) for p in per_frame])]).astype(np.int32)
+                kept = np.concatenate(per_frame).astype(np.int32)
+                rows = np.concatenate([x[n][per_frame[n]] for n in range(N)], axis=0)
+        if i < n_layers:
+            if rows is None:
+                if not replaced_later(i):
+                    x = encoder_block(x, w["layers"][i], shape.n_heads, shape.ln_eps)
+            else:
+                rows = np.concatenate([encoder_block(rows[cu[n]:cu[n + 1]][None], w["layers"][i],
+                                                     shape.n_heads, shape.ln_eps)[0]
+                                       for n in range(len(cu) - 1)], axis=0)
+    assert rows is not None, "select_layer must lie in [0, n_layers]"
+    if shape.has_final_ln:
+        rows = layer_norm(rows, np.asarray(w["final_ln_g"], dtype), np.asarray(w["final_ln_b"], dtype),
+                          shape.ln_eps)
+    return dict(tokens=rows, kept_idx=kept, cu_tokens=cu, frame_first=first.astype(np.int32),
+                frame_count=count.astype(np.int32), frame_dynamic=dyn, seg_start=seg_orig.astype(np.int32),
+                n_frames_out=len(cu) - 1, hidden=hidden, stages=stages, score=score)
+

@@ -81,6 +81,8 @@ def load_library():
                                             C.POINTER(_Output), C.POINTER(_PlanOut)]),
         "et_encode_clip_policy": (C.c_int, [vp, vp, i32, i32, C.POINTER(_Policy), vp, sz, vp,
                                            C.POINTER(_Output), C.POINTER(_PlanOut)]),
+        "et_encode_clip_multi": (C.c_int, [vp, vp, i32, C.POINTER(i32), i32, i32, C.POINTER(_Policy), vp, sz, vp,
+                                          C.POINTER(_Output), C.POINTER(_PlanOut)]),
         "et_frame_similarity": (C.c_int, [vp, i32, i32, i32, vp, vp, vp]),
         "et_segment_scan": (C.c_int, [vp, i32, f32, vp, vp, vp]),
         "et_segment_mean": (C.c_int, [vp, i32, i32, i32, vp, vp, vp, vp, vp]),
@@ -244,6 +246,24 @@ def et_encode_clip_policy(handle, frames, merge_layer, policy, L, D, workspace=N
     pol = _policy_struct(policy)
     _check(lib.et_encode_clip_policy(handle, _ptr(frames), T, int(merge_layer), C.byref(pol), _ptr(workspace),
                                      workspace.numel(), _stream(stream), C.byref(o), C.byref(po)))
+    return _trim_policy(bufs, o, plan_bufs, po, T)
+
+
+def et_encode_clip_multi(handle, frames, merge_layers, select_layer, policy, L, D, workspace=None, stream=None):
+    lib = load_library()
+    _dev(frames, torch.float32, "frames")
+    T = frames.shape[0]
+    if workspace is None:
+        workspace = torch.empty((max(et_workspace_bytes(handle, T), 1),), dtype=torch.uint8,
+                                device=frames.device)
+    bufs = _alloc_outputs(T, L, D, frames.device)
+    o = _out_struct(bufs)
+    plan_bufs, po = _plan_bufs(T, frames.device)
+    pol = _policy_struct(policy)
+    layers = (C.c_int32 * max(len(merge_layers), 1))(*[int(v) for v in merge_layers])
+    _check(lib.et_encode_clip_multi(handle, _ptr(frames), T, layers, len(merge_layers), int(select_layer),
+                                    C.byref(pol), _ptr(workspace), workspace.numel(), _stream(stream),
+                                    C.byref(o), C.byref(po)))
     return _trim_policy(bufs, o, plan_bufs, po, T)
 
 
@@ -469,6 +489,15 @@ class Encoder:
             self._ws = torch.empty((need,), dtype=torch.uint8, device=self.device)
         return et_encode_clip_policy(self.handle, frames, merge_layer, policy, self.shape.tokens_per_frame,
                                      self.shape.d_model, workspace=self._ws, stream=stream)
+
+    def encode_multi(self, frames, merge_layers, select_layer, policy, stream=None):
+        T = frames.shape[0]
+        need = et_workspace_bytes(self.handle, T)
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = torch.empty((need,), dtype=torch.uint8, device=self.device)
+        return et_encode_clip_multi(self.handle, frames, merge_layers, select_layer, policy,
+                                    self.shape.tokens_per_frame, self.shape.d_model, workspace=self._ws,
+                                    stream=stream)
 
     def close(self):
         if self.handle is not None:

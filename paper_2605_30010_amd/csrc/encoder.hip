@@ -233,8 +233,11 @@ size_t et_workspace_bytes(const et_encoder *e, int32_t T) {
 
 // Shared body of et_encode_clip (policy == nullptr: simple stage with sim_threshold / keep_ratio)
 // and et_encode_clip_policy.
+// With a policy, `merge_layers[0..n_merge)` (ascending) are the layers where Stage I runs and
+// `merge_layer` is the layer of Stage II (>= the last Stage I layer).
 static int encode_impl(et_encoder *e, const float *frames_dev, int32_t T, int32_t merge_layer,
-                       float sim_threshold, float keep_ratio, const et_policy *policy, void *workspace_dev,
+                       float sim_threshold, float keep_ratio, const et_policy *policy,
+                       const int32_t *merge_layers, int32_t n_merge, void *workspace_dev,
                        size_t workspace_bytes, void *hip_stream, et_output *out, et_plan_out *plan) {
   ET_REQUIRE(e != nullptr, "encoder is NULL");
   ET_REQUIRE(frames_dev != nullptr, "frames_dev is NULL");
@@ -283,47 +286,65 @@ static int encode_impl(et_encoder *e, const float *frames_dev, int32_t T, int32_
     ET_TIMED(ET_K_MISC, launch_cu_uniform(T, L, w.cu_full, s));
   }
 
-  bool ragged = false;
-  int n_segments = T;
+  bool ragged = false, selected = false, first_stage = true;
+  int n_segments = T, next_merge = 0;
   for (int i = 0; i <= c.n_layers; ++i) {
-    if (compress && i == merge_layer) {
+    const bool merge_here = compress && policy && !selected && next_merge < n_merge && merge_layers[next_merge] == i;
+    const bool select_here = compress && !selected && i == merge_layer;
+    if (policy && (merge_here || select_here)) {
       const MergeWs mw = carve_merge(w.merge, T, L, D);
-      if (policy) {
-        int32_t *info = mw.n_seg + 8;
-        int rc = enqueue_policy_stage(w.x, T, L, D, *policy, mw, out->frame_sim_dev, out->seg_start_dev,
-                                      out->kept_idx_dev, out->cu_tokens_dev, w.x, info, s, &e->prof);
-        if (rc) return rc;
-        int32_t hi[5] = {0, 0, 0, 0, 0};
-        ET_HIP(hipMemcpyAsync(hi, info, sizeof(hi), hipMemcpyDeviceToHost, s));
-        ET_HIP(hipStreamSynchronize(s));
-        if (hi[0] < 1 || hi[0] > T || hi[2] < hi[0] || hi[2] > T * L || hi[3] < 1 || hi[3] > L || hi[4] < 1 ||
-            hi[4] > L) {
-          set_error("plan read back from the device is inconsistent (N = %d, tokens = %d)", hi[0], hi[2]);
+      int32_t *info = mw.n_seg + 8;
+      const PlanStep step{merge_here ? 1 : 0, select_here ? 1 : 0, first_stage ? 1 : 0, T};
+      int rc = enqueue_policy_stage(w.x, n_frames, L, D, *policy, step, mw, first_stage ? out->frame_sim_dev : nullptr,
+                                    out->seg_start_dev, out->kept_idx_dev, out->cu_tokens_dev, w.x, info, s,
+                                    &e->prof);
+      if (rc) return rc;
+      if (!select_here)      // frames keep all L tokens: the merged frames become the residual stream
+        ET_HIP(hipMemcpyAsync(w.x, mw.merged, (size_t)n_frames * L * D * 2, hipMemcpyDeviceToDevice, s));
+      int32_t hi[5] = {0, 0, 0, 0, 0};
+      ET_HIP(hipMemcpyAsync(hi, info, sizeof(hi), hipMemcpyDeviceToHost, s));
+      ET_HIP(hipStreamSynchronize(s));
+      if (hi[0] < 1 || hi[0] > n_frames || hi[1] < 1 || hi[1] > T) {
+        set_error("plan read back from the device is inconsistent (N = %d, segments = %d)", hi[0], hi[1]);
+        return ET_ERR_HIP;
+      }
+      n_frames = hi[0];
+      n_segments = hi[1];
+      first_stage = false;
+      if (merge_here) ++next_merge;
+      if (select_here) {
+        if (hi[2] < hi[0] || hi[2] > T * L || hi[3] < 1 || hi[3] > L || hi[4] < 1 || hi[4] > L) {
+          set_error("token counts read back from the device are inconsistent (tokens = %d)", hi[2]);
           return ET_ERR_HIP;
         }
         if ((rc = copy_plan_out(mw, hi[0], plan, s))) return rc;
-        n_frames = hi[0];
-        n_segments = hi[1];
         rows = hi[2];
         max_len = hi[3] > hi[4] ? hi[3] : hi[4];
         ragged = policy->select_mode == ET_SELECT_DECOUPLED && hi[3] != hi[4];
+        cu = out->cu_tokens_dev;
+        selected = true;
+        e->prof.phase = 1;
       } else {
-        k = et_keep_count(L, keep_ratio);
-        int rc = enqueue_merge_stage(w.x, T, L, D, sim_threshold, k, mw, out->frame_sim_dev, out->seg_start_dev,
-                                     out->kept_idx_dev, out->cu_tokens_dev, w.x, s, &e->prof);
-        if (rc) return rc;
-        int32_t n_seg = 0;
-        ET_HIP(hipMemcpyAsync(&n_seg, mw.n_seg, sizeof(int32_t), hipMemcpyDeviceToHost, s));
-        ET_HIP(hipStreamSynchronize(s));
-        if (n_seg < 1 || n_seg > T) {
-          set_error("segment count %d read back from the device is outside [1, T = %d]", n_seg, T);
-          return ET_ERR_HIP;
-        }
-        n_frames = n_segments = n_seg;
-        rows = n_seg * k;
-        max_len = k;
+        rows = n_frames * L;     // still L tokens per frame: the uniform offsets stay valid
       }
+    } else if (select_here) {
+      const MergeWs mw = carve_merge(w.merge, T, L, D);
+      k = et_keep_count(L, keep_ratio);
+      int rc = enqueue_merge_stage(w.x, T, L, D, sim_threshold, k, mw, out->frame_sim_dev, out->seg_start_dev,
+                                   out->kept_idx_dev, out->cu_tokens_dev, w.x, s, &e->prof);
+      if (rc) return rc;
+      int32_t n_seg = 0;
+      ET_HIP(hipMemcpyAsync(&n_seg, mw.n_seg, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+      ET_HIP(hipStreamSynchronize(s));
+      if (n_seg < 1 || n_seg > T) {
+        set_error("segment count %d read back from the device is outside [1, T = %d]", n_seg, T);
+        return ET_ERR_HIP;
+      }
+      n_frames = n_segments = n_seg;
+      rows = n_seg * k;
+      max_len = k;
       cu = out->cu_tokens_dev;
+      selected = true;
       e->prof.phase = 1;
     }
     if (i < c.n_layers) {
@@ -351,16 +372,36 @@ extern "C" {
 int et_encode_clip(et_encoder *e, const float *frames_dev, int32_t T, int32_t merge_layer,
                    float sim_threshold, float keep_ratio, void *workspace_dev, size_t workspace_bytes,
                    void *hip_stream, et_output *out) {
-  return encode_impl(e, frames_dev, T, merge_layer, sim_threshold, keep_ratio, nullptr, workspace_dev,
-                     workspace_bytes, hip_stream, out, nullptr);
+  return encode_impl(e, frames_dev, T, merge_layer, sim_threshold, keep_ratio, nullptr, nullptr, 0,
+                     workspace_dev, workspace_bytes, hip_stream, out, nullptr);
 }
 
 int et_encode_clip_policy(et_encoder *e, const float *frames_dev, int32_t T, int32_t merge_layer,
                           const et_policy *policy, void *workspace_dev, size_t workspace_bytes,
                           void *hip_stream, et_output *out, et_plan_out *plan) {
   ET_REQUIRE(merge_layer < 0 || policy != nullptr, "policy is NULL");
-  return encode_impl(e, frames_dev, T, merge_layer, 0.f, 1.f, policy, workspace_dev, workspace_bytes,
-                     hip_stream, out, plan);
+  const int32_t layers[1] = {merge_layer};
+  return encode_impl(e, frames_dev, T, merge_layer, 0.f, 1.f, policy, layers, merge_layer >= 0 ? 1 : 0,
+                     workspace_dev, workspace_bytes, hip_stream, out, plan);
+}
+
+int et_encode_clip_multi(et_encoder *e, const float *frames_dev, int32_t T, const int32_t *merge_layers,
+                         int32_t n_merge_layers, int32_t select_layer, const et_policy *policy,
+                         void *workspace_dev, size_t workspace_bytes, void *hip_stream, et_output *out,
+                         et_plan_out *plan) {
+  ET_REQUIRE(e != nullptr, "encoder is NULL");
+  ET_REQUIRE(policy != nullptr, "policy is NULL");
+  ET_REQUIRE(n_merge_layers >= 0 && n_merge_layers <= 64, "n_merge_layers = %d outside [0, 64]", n_merge_layers);
+  ET_REQUIRE(n_merge_layers == 0 || merge_layers != nullptr, "merge_layers is NULL");
+  ET_REQUIRE(select_layer >= 0 && select_layer <= e->cfg.n_layers, "select_layer = %d outside [0, n_layers = %d]",
+             select_layer, e->cfg.n_layers);
+  for (int i = 0; i < n_merge_layers; ++i) {
+    ET_REQUIRE(merge_layers[i] >= 0 && merge_layers[i] <= select_layer,
+               "merge_layers[%d] = %d outside [0, select_layer = %d]", i, merge_layers[i], select_layer);
+    ET_REQUIRE(i == 0 || merge_layers[i] > merge_layers[i - 1], "merge_layers must be strictly ascending");
+  }
+  return encode_impl(e, frames_dev, T, select_layer, 0.f, 1.f, policy, merge_layers, n_merge_layers,
+                     workspace_dev, workspace_bytes, hip_stream, out, plan);
 }
 
 int et_profile_enable(et_encoder *e, int32_t on) {

@@ -50,6 +50,8 @@ MergeWs carve_merge(void *ws, int T, int L, int D) {
   m.frame_count = c.take<int32_t>((size_t)T);
   m.frame_dyn = c.take<int32_t>((size_t)T);
   m.frame_w = c.take<float>((size_t)2 * T);
+  m.orig_first = c.take<int32_t>((size_t)T);
+  m.orig_count = c.take<int32_t>((size_t)T);
   m.merged = c.take<uint16_t>((size_t)T * L * D);
   m.bytes = c.off;
   return m;
@@ -95,29 +97,34 @@ int check_policy(const et_policy *p) {
   return ET_OK;
 }
 
-int enqueue_policy_stage(const uint16_t *x, int T, int L, int D, const et_policy &pol, const MergeWs &w,
-                         float *sim_out, int32_t *seg_start, int32_t *kept, int32_t *cu_tokens,
-                         uint16_t *packed, int32_t *info, hipStream_t s, Profiler *prof) {
+int enqueue_policy_stage(const uint16_t *x, int T, int L, int D, const et_policy &pol, const PlanStep &step,
+                         const MergeWs &w, float *sim_out, int32_t *seg_start, int32_t *kept,
+                         int32_t *cu_tokens, uint16_t *packed, int32_t *info, hipStream_t s, Profiler *prof) {
   float *sim = sim_out ? sim_out : w.sim;
   const PolicyArgs pa{pol.merge_mode, pol.select_mode, pol.alpha, pol.tau_seg, pol.tau_merge, pol.ratio};
   const int k_uniform = et_keep_count(L, pol.ratio);
-  ET_TIMED_P(prof, ET_K_SIMILARITY, launch_similarity(x, T, L, D, w.cos, s));
-  ET_TIMED_P(prof, ET_K_SCAN, launch_sim_mean_scan(w.cos, T, L, 0.f, sim, nullptr, nullptr, true, false, s));
-  ET_TIMED_P(prof, ET_K_SCAN, launch_plan(sim, T, L, pa, k_uniform, seg_start, w.frame_first, w.frame_count,
-                                          w.frame_dyn, w.frame_w, cu_tokens, info, s));
+  if (step.do_plan) {
+    ET_TIMED_P(prof, ET_K_SIMILARITY, launch_similarity(x, T, L, D, w.cos, s));
+    ET_TIMED_P(prof, ET_K_SCAN, launch_sim_mean_scan(w.cos, T, L, 0.f, sim, nullptr, nullptr, true, false, s));
+  }
+  ET_TIMED_P(prof, ET_K_SCAN, launch_plan(sim, T, L, pa, k_uniform, step, seg_start, w.frame_first, w.frame_count,
+                                          w.frame_dyn, w.frame_w, w.orig_first, w.orig_count, cu_tokens, info, s));
   ET_TIMED_P(prof, ET_K_MERGE, launch_plan_merge(x, T, L, D, info, w.frame_first, w.frame_count, w.frame_w,
-                                                 pol.merge_mode == ET_MERGE_MEAN, w.merged, w.score, s));
-  ET_TIMED_P(prof, ET_K_SELECT, launch_select_policy(w.score, T, info, w.frame_dyn, cu_tokens, L,
-                                                     pol.select_mode == ET_SELECT_UNIFORM, kept, s));
-  ET_TIMED_P(prof, ET_K_COMPACT, launch_compact_ragged(w.merged, kept, T, info, cu_tokens, L, D, packed, s));
+                                                 step.do_plan && pol.merge_mode == ET_MERGE_MEAN, w.merged,
+                                                 w.score, s));
+  if (step.do_counts) {
+    ET_TIMED_P(prof, ET_K_SELECT, launch_select_policy(w.score, T, info, w.frame_dyn, cu_tokens, L,
+                                                       pol.select_mode == ET_SELECT_UNIFORM, kept, s));
+    ET_TIMED_P(prof, ET_K_COMPACT, launch_compact_ragged(w.merged, kept, T, info, cu_tokens, L, D, packed, s));
+  }
   return ET_OK;
 }
 
 int copy_plan_out(const MergeWs &w, int N, et_plan_out *plan, hipStream_t s) {
   if (!plan || N <= 0) return ET_OK;
   const size_t bytes = (size_t)N * sizeof(int32_t);
-  if (plan->frame_first_dev) ET_HIP(hipMemcpyAsync(plan->frame_first_dev, w.frame_first, bytes, hipMemcpyDeviceToDevice, s));
-  if (plan->frame_count_dev) ET_HIP(hipMemcpyAsync(plan->frame_count_dev, w.frame_count, bytes, hipMemcpyDeviceToDevice, s));
+  if (plan->frame_first_dev) ET_HIP(hipMemcpyAsync(plan->frame_first_dev, w.orig_first, bytes, hipMemcpyDeviceToDevice, s));
+  if (plan->frame_count_dev) ET_HIP(hipMemcpyAsync(plan->frame_count_dev, w.orig_count, bytes, hipMemcpyDeviceToDevice, s));
   if (plan->frame_dynamic_dev) ET_HIP(hipMemcpyAsync(plan->frame_dynamic_dev, w.frame_dyn, bytes, hipMemcpyDeviceToDevice, s));
   return ET_OK;
 }
@@ -227,7 +234,8 @@ int et_merge_select_policy(const uint16_t *x_dev, int32_t T, int32_t L, int32_t 
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   MergeWs w = carve_merge(workspace_dev, T, L, D);
   int32_t *info = w.n_seg + 8;
-  if ((rc = enqueue_policy_stage(x_dev, T, L, D, *policy, w, out->frame_sim_dev, out->seg_start_dev,
+  const PlanStep step{1, 1, 1, T};
+  if ((rc = enqueue_policy_stage(x_dev, T, L, D, *policy, step, w, out->frame_sim_dev, out->seg_start_dev,
                                  out->kept_idx_dev, out->cu_tokens_dev, out->tokens_dev, info, s, nullptr)))
     return rc;
   int32_t host_info[5] = {0, 0, 0, 0, 0};

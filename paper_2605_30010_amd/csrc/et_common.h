@@ -133,6 +133,7 @@ struct MergeWs {
   int32_t *n_seg;                 // 64 ints: [0] segment count of the simple path; [8..12] policy info
   int32_t *frame_first, *frame_count, *frame_dyn;   // [T] each: output-frame plan (policy path)
   float *frame_w;                 // [2T]
+  int32_t *orig_first, *orig_count;   // [T] each: range of original frames behind each current frame
   size_t bytes;
 };
 
@@ -141,12 +142,20 @@ struct PolicyArgs {
   int merge_mode, select_mode;
   float alpha, tau_seg, tau_merge, ratio;
 };
+// One application of the plan kernel: build a plan from similarities or take the identity plan;
+// compute the selection's token counts or not; first stage (frame ranges start as identity) or not.
+struct PlanStep {
+  int do_plan, do_counts, init_orig, t_orig;
+};
 int check_policy(const et_policy *p);
 // Enqueues similarity -> plan -> weighted merge -> selection -> ragged gather; no host sync.
 // info (device, >= 5 ints) receives N, segments, total tokens, tokens per dynamic / static frame.
-int enqueue_policy_stage(const uint16_t *x, int T, int L, int D, const et_policy &pol, const MergeWs &w,
-                         float *sim_out, int32_t *seg_start, int32_t *kept, int32_t *cu_tokens,
-                         uint16_t *packed, int32_t *info, hipStream_t s, struct Profiler *prof);
+// `step` says which parts run: with do_counts the selection and the gather into `packed` follow the
+// merge; without, only `w.merged` (all L tokens per frame) and `w.score` are produced.
+int enqueue_policy_stage(const uint16_t *x, int T, int L, int D, const et_policy &pol, const PlanStep &step,
+                         const MergeWs &w, float *sim_out, int32_t *seg_start, int32_t *kept,
+                         int32_t *cu_tokens, uint16_t *packed, int32_t *info, hipStream_t s,
+                         struct Profiler *prof);
 int copy_plan_out(const MergeWs &w, int N, et_plan_out *plan, hipStream_t s);
 MergeWs carve_merge(void *ws, int T, int L, int D);
 // Enqueues similarity -> scan -> segment mean (+score) -> top-k -> compaction; no host sync.
@@ -172,9 +181,10 @@ int launch_cu_uniform(int n, int step, int32_t *cu, hipStream_t s);
 int launch_fill_random_bf16(uint16_t *p, size_t n, uint32_t seed, hipStream_t s);
 
 // ---- launchers implemented in policy_kernels.hip ----
-int launch_plan(const float *sim, int T, int L, const PolicyArgs &p, int k_uniform, int32_t *seg_start,
-                int32_t *frame_first, int32_t *frame_count, int32_t *frame_dyn, float *frame_w,
-                int32_t *cu_tokens, int32_t *info, hipStream_t s);
+int launch_plan(const float *sim, int T, int L, const PolicyArgs &p, int k_uniform, const PlanStep &st,
+                int32_t *seg_start, int32_t *frame_first, int32_t *frame_count, int32_t *frame_dyn,
+                float *frame_w, int32_t *orig_first, int32_t *orig_count, int32_t *cu_tokens, int32_t *info,
+                hipStream_t s);
 int launch_plan_merge(const uint16_t *x, int T, int L, int D, const int32_t *info, const int32_t *frame_first,
                       const int32_t *frame_count, const float *frame_w, bool uniform_mean, uint16_t *merged,
                       float *score, hipStream_t s);

@@ -26,66 +26,102 @@ constexpr int kSelThreads = 256;
 //  - Eq. 6: w = L / r_hat (integer division), M = ceil(L / w) windows.
 // ---------------------------------------------------------------------------------------
 __global__ void plan_kernel(const float *__restrict__ sim, int T, int L, PolicyArgs p, int k_uniform,
-                            int32_t *__restrict__ seg_start, int32_t *__restrict__ frame_first,
+                            PlanStep st, int32_t *__restrict__ seg_start, int32_t *__restrict__ frame_first,
                             int32_t *__restrict__ frame_count, int32_t *__restrict__ frame_dyn,
-                            float *__restrict__ frame_w, int32_t *__restrict__ cu_tokens,
+                            float *__restrict__ frame_w, int32_t *__restrict__ orig_first,
+                            int32_t *__restrict__ orig_count, int32_t *__restrict__ cu_tokens,
                             int32_t *__restrict__ info) {
+  // T = current number of frames.  st.do_plan: build segments and output frames from sim (else the
+  // identity plan over the T current frames, dynamic flags left as they are).  st.do_counts: token
+  // counts and offsets of the selection.  orig_first / orig_count: range of ORIGINAL frames behind
+  // each current frame (st.init_orig: identity, first stage), updated in place; seg_start is
+  // written in original frame indices.
   if (threadIdx.x != 0 || blockIdx.x != 0) return;
-  // segmentation
-  int n_seg = 0;
-  seg_start[0] = 0;
-  float prev = 0.f;
-  bool fresh = true;
-  for (int t = 1; t < T; ++t) {
-    const float st = sim[t - 1];
-    const float cur = fresh ? st : p.alpha * st + (1.0f - p.alpha) * prev;
-    if (!(cur >= p.tau_seg)) {
-      seg_start[++n_seg] = t;
-      fresh = true;
-    } else {
-      prev = cur;
-      fresh = false;
-    }
-  }
-  seg_start[++n_seg] = T;
-  // output frames
   int N = 0;
-  auto emit = [&](int first, int count, float w0, float w1, int dyn) {
-    frame_first[N] = first;
-    frame_count[N] = count;
-    frame_dyn[N] = dyn;
-    frame_w[2 * N] = w0;
-    frame_w[2 * N + 1] = w1;
-    ++N;
-  };
-  for (int sgi = 0; sgi < n_seg; ++sgi) {
-    const int a = seg_start[sgi], b = seg_start[sgi + 1];
-    if (p.merge_mode == ET_MERGE_MEAN) {
-      emit(a, b - a, 0.f, 0.f, 1);                   // uniform weights: handled as sum / count
-      continue;
-    }
-    const int k = b - a - 1;
-    emit(a, 1, 1.f, 0.f, 1);
-    int i = 1;
-    while (i < k) {
-      const float si = sim[a + i];                   // Sim(F_i, F_{i+1})
-      if (i + 1 <= k - 1 && si > p.tau_merge && si > sim[a + i + 1]) {
-        const float sj = sim[a + i + 1];
-        emit(a + i, 2, si / (si + sj), sj / (si + sj), 0);
-        i += 2;
+  if (st.do_plan) {
+    int n_seg = 0;
+    seg_start[0] = 0;
+    float prev = 0.f;
+    bool fresh = true;
+    for (int t = 1; t < T; ++t) {
+      const float sv = sim[t - 1];
+      const float cur = fresh ? sv : p.alpha * sv + (1.0f - p.alpha) * prev;
+      if (!(cur >= p.tau_seg)) {
+        seg_start[++n_seg] = t;
+        fresh = true;
       } else {
-        emit(a + i, 1, 1.f, 0.f, 0);
-        i += 1;
+        prev = cur;
+        fresh = false;
       }
     }
-    if (k >= 1) emit(a + k, 1, 1.f, 0.f, 1);
+    seg_start[++n_seg] = T;
+    auto emit = [&](int first, int count, float w0, float w1, int dyn) {
+      frame_first[N] = first;
+      frame_count[N] = count;
+      frame_dyn[N] = dyn;
+      frame_w[2 * N] = w0;
+      frame_w[2 * N + 1] = w1;
+      ++N;
+    };
+    for (int sgi = 0; sgi < n_seg; ++sgi) {
+      const int a = seg_start[sgi], b = seg_start[sgi + 1];
+      if (p.merge_mode == ET_MERGE_MEAN) {
+        emit(a, b - a, 0.f, 0.f, 1);                 // uniform weights: handled as sum / count
+        continue;
+      }
+      const int k = b - a - 1;
+      emit(a, 1, 1.f, 0.f, 1);
+      int i = 1;
+      while (i < k) {
+        const float si = sim[a + i];                 // Sim(F_i, F_{i+1})
+        if (i + 1 <= k - 1 && si > p.tau_merge && si > sim[a + i + 1]) {
+          const float sj = sim[a + i + 1];
+          emit(a + i, 2, si / (si + sj), sj / (si + sj), 0);
+          i += 2;
+        } else {
+          emit(a + i, 1, 1.f, 0.f, 0);
+          i += 1;
+        }
+      }
+      if (k >= 1) emit(a + k, 1, 1.f, 0.f, 1);
+    }
+    // segment starts and frame ranges in original frame indices (ascending, in place: entry n only
+    // reads entries >= n)
+    for (int i = 0; i < n_seg; ++i) seg_start[i] = st.init_orig ? seg_start[i] : orig_first[seg_start[i]];
+    seg_start[n_seg] = st.t_orig;
+    for (int n = 0; n < N; ++n) {
+      const int f = frame_first[n], l = f + frame_count[n] - 1;
+      const int of = st.init_orig ? f : orig_first[f];
+      const int oe = st.init_orig ? l + 1 : orig_first[l] + orig_count[l];
+      orig_first[n] = of;
+      orig_count[n] = oe - of;
+    }
+    info[1] = n_seg;
+  } else {
+    N = T;
+    for (int n = 0; n < N; ++n) {
+      frame_first[n] = n;
+      frame_count[n] = 1;
+      frame_w[2 * n] = 1.f;
+      frame_w[2 * n + 1] = 0.f;
+      if (st.init_orig) {
+        frame_dyn[n] = 1;
+        orig_first[n] = n;
+        orig_count[n] = 1;
+      }
+    }
+    if (st.init_orig) {
+      for (int i = 0; i <= T; ++i) seg_start[i] = i;
+      info[1] = T;
+    }
   }
-  // token counts
+  info[0] = N;
+  if (!st.do_counts) return;
   int n_dyn_tok, n_sta_tok;
   if (p.select_mode == ET_SELECT_UNIFORM) {
     n_dyn_tok = n_sta_tok = k_uniform;
   } else {
-    double v = floor((double)p.ratio * (double)T * (double)L / (double)N + 0.5);
+    double v = floor((double)p.ratio * (double)st.t_orig * (double)L / (double)N + 0.5);
     int r_hat = v < 1.0 ? 1 : (v > (double)L ? L : (int)v);
     const int w = L / r_hat;
     n_dyn_tok = r_hat;
@@ -97,8 +133,6 @@ __global__ void plan_kernel(const float *__restrict__ sim, int T, int L, PolicyA
     total += (p.select_mode == ET_SELECT_UNIFORM || frame_dyn[n]) ? n_dyn_tok : n_sta_tok;
   }
   cu_tokens[N] = total;
-  info[0] = N;
-  info[1] = n_seg;
   info[2] = total;
   info[3] = n_dyn_tok;
   info[4] = n_sta_tok;
@@ -300,11 +334,12 @@ __global__ __launch_bounds__(kRowsPerBlock * kWave) void compact_ragged_kernel(
 
 }  // namespace
 
-int launch_plan(const float *sim, int T, int L, const PolicyArgs &p, int k_uniform, int32_t *seg_start,
-                int32_t *frame_first, int32_t *frame_count, int32_t *frame_dyn, float *frame_w,
-                int32_t *cu_tokens, int32_t *info, hipStream_t s) {
-  hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(64), 0, s, sim, T, L, p, k_uniform, seg_start, frame_first,
-                     frame_count, frame_dyn, frame_w, cu_tokens, info);
+int launch_plan(const float *sim, int T, int L, const PolicyArgs &p, int k_uniform, const PlanStep &st,
+                int32_t *seg_start, int32_t *frame_first, int32_t *frame_count, int32_t *frame_dyn,
+                float *frame_w, int32_t *orig_first, int32_t *orig_count, int32_t *cu_tokens, int32_t *info,
+                hipStream_t s) {
+  hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(64), 0, s, sim, T, L, p, k_uniform, st, seg_start, frame_first,
+                     frame_count, frame_dyn, frame_w, orig_first, orig_count, cu_tokens, info);
   ET_LAUNCH_CHECK();
   return ET_OK;
 }

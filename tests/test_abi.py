@@ -148,3 +148,7 @@ def test_policy_entry_points_reject_bad_arguments():
     assert lib.et_merge_select_policy(None, 4, 8, 64, C.byref(good), fake, 1 << 30, None, C.byref(out), None) == -1
     assert lib.et_merge_select_policy(fake, 4, 8, 64, C.byref(good), fake, 16, None, C.byref(out), None) == -2
     assert lib.et_encode_clip_policy(None, fake, 4, 2, C.byref(good), fake, 1 << 30, None, C.byref(out), None) == -1
+    layers = (C.c_int32 * 2)(1, 2)
+    assert lib.et_encode_clip_multi(None, fake, 4, layers, 2, 3, C.byref(good), fake, 1 << 30, None,
+                                    C.byref(out), None) == -1
+    assert "encoder" in et.et_last_error()

@@ -196,3 +196,184 @@ def test_siglip_32_frames_with_paper_policy():
     assert abs(got["n_tokens"] / total_in - 0.2) < 0.03
     print("paper policy, 32 frames: N=%d tokens=%d (%.1f%%) rel-L2 %.4g, indices identical: %s"
           % (got["n_frames_out"], got["n_tokens"], 100.0 * got["n_tokens"] / total_in, err, same))
+
+
+# ---- Stage I at several layers, Stage II once (Table 8) ---------------------------------------
+
+ALL_TOKENS = dict(merge_mode="mean", select_mode="uniform", alpha=1.0, tau_seg=0.9, tau_merge=0.9, ratio=1.0)
+
+
+def _gpu_hidden_at(shape, w, frames, merge_layers, layer, pol):
+    """bf16 hidden states the device path sees at `layer` (before its merge), given the merges at the
+    earlier `merge_layers`: an encoder cut after `layer` blocks that keeps every token."""
+    from dataclasses import replace
+    T = frames.shape[0]
+    L, D = shape.tokens_per_frame, shape.d_model
+    enc = et.Encoder(replace(shape, n_layers=layer, has_final_ln=0), dict(w, layers=w["layers"][:layer]), T)
+    fr = torch.from_numpy(frames).cuda()
+    if merge_layers:
+        keep_all = dict(pol, select_mode="uniform", ratio=1.0)
+        r = enc.encode_multi(fr, merge_layers, layer, keep_all)
+        assert r["n_tokens"] == r["n_frames_out"] * L
+        assert np.array_equal(r["kept_idx"].cpu().numpy(), np.tile(np.arange(L), r["n_frames_out"]))
+    else:
+        r = enc.encode(fr, -1, 0.0, 1.0)
+    x = bf16_bits_to_f32(dev_to_bits(r["tokens"])).astype(np.float64).reshape(-1, L, D)
+    enc.close()
+    return x
+
+
+def _stage_margins_ok(ref, pol):
+    for st in ref["stages"].values():
+        if len(st["s_hat"]) and np.min(np.abs(st["s_hat"] - pol["tau_seg"])) < 1e-2:
+            return False
+        s = st["frame_sim"]
+        if pol["merge_mode"] == "alg1" and len(s) > 1:
+            if np.min(np.abs(np.diff(s))) < 1e-6 or np.min(np.abs(s - pol["tau_merge"])) < 1e-5:
+                return False
+    return True
+
+
+def _selection_margins_ok(ref, pol, L, T):
+    cu = ref["cu_tokens"]
+    for n, z in enumerate(ref["score"]):
+        k = int(cu[n + 1] - cu[n])
+        if ref["frame_dynamic"][n] or pol["select_mode"] == "uniform":
+            zs = np.sort(z)[::-1]
+            if k < L and (zs[k - 1] - zs[k]) < 2e-6 * zs[k - 1]:
+                return False
+        else:
+            w = L // O.rescaled_count(pol["ratio"], T, L, len(ref["score"]))
+            for lo in range(0, L, w):
+                win = np.sort(z[lo:lo + w])[::-1]
+                if len(win) > 1 and (win[0] - win[1]) < 2e-6 * win[0]:
+                    return False
+    return True
+
+
+def _multi_check(shape, w, frames, merge_layers, select_layer, pol, tol=2e-2, strict_selection=True):
+    """Device path against the oracle fed the device's own bf16 hidden states at every stage layer, so
+    that each stage is compared on identical inputs; the tokens are compared end to end."""
+    T = frames.shape[0]
+    L = shape.tokens_per_frame
+    x_at = {}
+    for layer in sorted(set(merge_layers) | {select_layer}):
+        x_at[layer] = _gpu_hidden_at(shape, w, frames, [m for m in merge_layers if m < layer], layer, pol)
+    # decisions are promised away from ties only: look at every merge layer's similarities first (a
+    # tie there may already have given the next stage a different number of frames)
+    for layer in merge_layers:
+        s_l = O.frame_similarity(x_at[layer])[1]
+        _, s_hat = O.ema_segment_starts(s_l, pol["alpha"], pol["tau_seg"], x_at[layer].shape[0])
+        if not _stage_margins_ok(dict(stages={layer: dict(frame_sim=s_l, s_hat=s_hat)}), pol):
+            return None
+    enc = et.Encoder(shape, w, T)
+    got = enc.encode_multi(torch.from_numpy(frames).cuda(), merge_layers, select_layer, pol)
+    got = {k: (v.clone() if isinstance(v, torch.Tensor) else v) for k, v in got.items()}
+    enc.close()
+    ref = O.encode_clip_multi(shape, w, frames, merge_layers, select_layer, pol, x_at_layers=x_at)
+    if not _stage_margins_ok(ref, pol) or (strict_selection and not _selection_margins_ok(ref, pol, L, T)):
+        return None
+    for layer, st in ref["stages"].items():          # every stage saw the frame count the oracle derives
+        later = [j for j in x_at if j > layer]
+        if later:
+            assert x_at[min(later)].shape[0] == st["n_frames"]
+    assert got["n_frames_out"] == ref["n_frames_out"]
+    assert got["seg_start"].tolist() == ref["seg_start"].tolist()
+    assert got["frame_first"].tolist() == ref["frame_first"].tolist()
+    assert got["frame_count"].tolist() == ref["frame_count"].tolist()
+    assert got["frame_dynamic"].tolist() == ref["frame_dynamic"].tolist()
+    assert got["cu_tokens"].tolist() == ref["cu_tokens"].tolist()
+    kept = got["kept_idx"].cpu().numpy()
+    same = np.array_equal(kept, ref["kept_idx"])
+    if strict_selection:
+        assert same
+    elif not same:      # near-tied scores somewhere: few flips, and the tokens compared on the device's choice
+        assert (kept != ref["kept_idx"]).mean() < 2e-3
+        cu = ref["cu_tokens"]
+        ref = O.encode_clip_multi(shape, w, frames, merge_layers, select_layer, pol, x_at_layers=x_at,
+                                  force_kept=[kept[cu[n]:cu[n + 1]] for n in range(len(cu) - 1)])
+    err = rel_l2(dev_to_f64(got["tokens"]), ref["tokens"])
+    assert err <= tol, err
+    return got, ref, err
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("merge_layers,select_layer,pi", [([1, 2], 3, 0), ([0, 2, 3], 4, 2), ([], 2, 0),
+                                                          ([1, 3], 3, 4), ([2], 2, 1)])
+def test_tiny_encoder_multi_layer_merging(merge_layers, select_layer, pi):
+    rec = build_workload("c1_tiny")
+    w = rec["weights"]
+    pol = _f32_policy(dict(POLICIES[pi], tau_seg=0.9, tau_merge=0.9))
+    for seed in range(40):
+        frames = make_clip(TINY, [7, 2, 6, 1], 300 + seed, base="uniform", sigma=0.02)
+        res = _multi_check(TINY, w, frames, merge_layers, select_layer, pol)
+        if res is not None:
+            break
+    else:
+        pytest.fail("no clip with clear margins in 40 seeds")
+    got, ref, err = res
+    if merge_layers:
+        assert got["n_frames_out"] < 16
+    first, count = got["frame_first"].cpu().numpy(), got["frame_count"].cpu().numpy()
+    assert first[0] == 0 and np.array_equal(first[1:], (first + count)[:-1]) and first[-1] + count[-1] == 16
+
+
+@pytest.mark.gpu
+def test_multi_equals_single_layer_entry_point():
+    rec = build_workload("c1_tiny")
+    w = rec["weights"]
+    frames = torch.from_numpy(make_clip(TINY, [6, 1, 5], 21, base="uniform", sigma=0.02)).cuda()
+    enc = et.Encoder(TINY, w, 12)
+    for pol in POLICIES:
+        a = enc.encode_policy(frames, 2, pol)
+        a = {k: (v.clone() if isinstance(v, torch.Tensor) else v) for k, v in a.items()}
+        b = enc.encode_multi(frames, [2], 2, pol)
+        for key in ("tokens", "kept_idx", "cu_tokens", "seg_start", "frame_first", "frame_count", "frame_dynamic"):
+            assert torch.equal(a[key], b[key]), key
+    enc.close()
+
+
+@pytest.mark.gpu
+def test_siglip_multi_layer_merging_stagewise():
+    """SigLIP-sized layers (6 of them), merges after blocks 2 and 4, selection after block 5."""
+    from dataclasses import replace
+    shape = replace(SIGLIP, n_layers=6)
+    pol = _f32_policy(dict(merge_mode="alg1", select_mode="decoupled", alpha=0.9, tau_seg=0.8, tau_merge=0.8,
+                           ratio=0.25))
+    rec = build_workload("c2_siglip_t8", n_layers=6)
+    rec["lengths"] = [6, 1, 5]
+    for seed in range(10):
+        # frame noise 0.2: in-scene similarities near 0.96 whose differences (about 1e-4) decide Alg. 1
+        # well clear of float32 rounding
+        frames = make_clip(SIGLIP, rec["lengths"], 700 + seed, base=rec["base"], sigma=0.2)
+        res = _multi_check(shape, rec["weights"], frames, [2, 4], 5, pol, strict_selection=False)
+        if res is not None:
+            break
+    else:
+        pytest.fail("no clip with clear margins")
+    got, ref, err = res
+    print("multi-layer SigLIP-size: scenes %s, N = %d, tokens = %d, rel-L2 = %.4f"
+          % (rec["lengths"], got["n_frames_out"], got["n_tokens"], err))
+    assert got["n_frames_out"] < 12
+
+
+@pytest.mark.gpu
+def test_siglip_32_frames_three_merge_layers_selection_after_encoder():
+    """The paper's layer choice at full size: Stage I after blocks 6, 14 and 20, Stage II on the
+    encoder output (27 blocks), 32 frames, 20 % retention."""
+    rec = build_workload("c3_siglip_t32")
+    pol = _f32_policy(dict(merge_mode="alg1", select_mode="decoupled", alpha=0.9, tau_seg=0.8, tau_merge=0.8,
+                           ratio=0.2))
+    for seed in range(4):
+        frames = make_clip(SIGLIP, rec["lengths"], 900 + seed, base=rec["base"], sigma=0.2)
+        res = _multi_check(SIGLIP, rec["weights"], frames, [6, 14, 20], 27, pol, strict_selection=False)
+        if res is not None:
+            break
+    else:
+        pytest.fail("no clip with clear margins")
+    got, ref, err = res
+    counts = [st["n_frames"] for _, st in sorted(ref["stages"].items())]
+    print("layers 6/14/20 + selection at 27: scenes %s, frames 32 -> %s, tokens = %d (%.1f %%), rel-L2 = %.4f"
+          % (rec["lengths"], counts, got["n_tokens"], 100.0 * got["n_tokens"] / (32 * 729), err))
+    assert counts[0] <= 32 and counts[1] <= counts[0] and counts[2] <= counts[1]
+    assert abs(got["n_tokens"] / (32 * 729) - 0.2) < 0.03

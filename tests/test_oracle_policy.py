@@ -188,3 +188,39 @@ def test_paper_policy_end_to_end_bookkeeping(tiny):
     solo = O.encode_clip_policy(TINY, w, frames[6:7], 2, pol, force_kept=[kept_mid])
     np.testing.assert_allclose(solo["tokens"], r["tokens"][r["cu_tokens"][n_mid]:r["cu_tokens"][n_mid + 1]],
                                rtol=1e-10, atol=1e-10)
+
+
+def test_multi_layer_merging_reductions_and_bookkeeping(tiny):
+    w, _ = tiny
+    frames = make_clip(TINY, [6, 1, 5], 21, base="uniform", sigma=0.02)
+    pol = dict(alpha=0.9, tau_seg=0.9, tau_merge=0.9, merge_mode="alg1", select_mode="decoupled", ratio=0.25)
+    # one merge layer that is also the select layer == the single-layer policy path
+    a = O.encode_clip_policy(TINY, w, frames, 2, pol)
+    b = O.encode_clip_multi(TINY, w, frames, [2], 2, pol)
+    assert b["cu_tokens"].tolist() == a["cu_tokens"].tolist() and b["kept_idx"].tolist() == a["kept_idx"].tolist()
+    np.testing.assert_allclose(b["tokens"], a["tokens"], rtol=1e-12, atol=1e-12)
+    assert b["frame_first"].tolist() == a["frame_first"].tolist()
+    assert b["frame_count"].tolist() == a["frame_count"].tolist()
+    assert b["seg_start"].tolist() == a["seg_start"].tolist()
+    # no merge layer, selection after the last block == plain encoder, then selection on its output
+    c = O.encode_clip_multi(TINY, w, frames, [], 4, dict(pol, select_mode="uniform", ratio=0.5))
+    d = O.encode_clip_policy(TINY, w, frames, 4, dict(pol, tau_seg=math.inf, merge_mode="mean",
+                                                      select_mode="uniform", ratio=0.5))
+    assert c["kept_idx"].tolist() == d["kept_idx"].tolist()
+    np.testing.assert_allclose(c["tokens"], d["tokens"], rtol=1e-12, atol=1e-12)
+    assert c["frame_dynamic"].tolist() == [1] * 12
+    # three merge layers: output frames are contiguous, disjoint ranges of the original frames, and
+    # frame counts never grow from layer to layer
+    e = O.encode_clip_multi(TINY, w, frames, [1, 2, 3], 4, pol)
+    covered = [t for f, c_ in zip(e["frame_first"], e["frame_count"]) for t in range(f, f + c_)]
+    assert covered == list(range(12))
+    sizes = [e["hidden"][i].shape[0] for i in (1, 2, 3, 4)]
+    assert sizes[0] == 12 and all(x >= y for x, y in zip(sizes, sizes[1:])) and sizes[-1] == e["n_frames_out"]
+    assert e["n_frames_out"] < 12                         # the six-frame scene fuses at least one pair
+    # mean mode collapses each scene at the first layer; later layers find nothing more to merge
+    pm = dict(pol, merge_mode="mean", alpha=1.0)
+    f1 = O.encode_clip_multi(TINY, w, frames, [1], 3, pm)
+    f3 = O.encode_clip_multi(TINY, w, frames, [1, 2, 3], 3, pm)
+    assert f1["n_frames_out"] == f3["n_frames_out"] == 3
+    assert f3["frame_first"].tolist() == [0, 6, 7] and f3["frame_count"].tolist() == [6, 1, 5]
+    np.testing.assert_allclose(f3["tokens"], f1["tokens"], rtol=1e-12, atol=1e-12)
