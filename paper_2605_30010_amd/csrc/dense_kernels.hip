@@ -6,6 +6,8 @@
 //   operand "A" (32 x 16): lane holds row r,    k = 8g .. 8g+7   (8 bf16 = one 16-byte vector)
 //   operand "B" (16 x 32): lane holds column r, k = 8g .. 8g+7
 //   accumulator (32 x 32): lane holds column r, rows (i / 4) * 8 + 4g + (i % 4), i = 0..15
+#include <type_traits>
+
 #include "et_common.h"
 
 namespace et {
@@ -187,7 +189,7 @@ __device__ __forceinline__ void gemm_epilogue(f32x16 (&acc)[FN][FM], const GemmA
 // pieces to the slice; finally the slice is read row-wise and stored.  16-byte slots of a row are
 // XOR-swizzled by (row >> 1) & 7.  LDS operations of one wavefront execute in order, so the phases
 // need no barrier.
-template <int EPI, int FM, int FN>
+template <int EPI, int FM, int FN, int PIN = 0>
 __device__ __forceinline__ void gemm_epilogue_lds(f32x16 (&acc)[FN][FM], const GemmArgs &g, int m_base,
                                                   int n_base, int lane, uint16_t *slice) {
   static_assert(FN % 2 == 0, "the staged epilogue handles 64-column pieces of the wavefront tile");
@@ -199,6 +201,15 @@ __device__ __forceinline__ void gemm_epilogue_lds(f32x16 (&acc)[FN][FM], const G
   const int nb = n_base + half * 64;
   const int n_lane = nb + pch * 8;
   const bool n_ok = n_lane < g.n_store;                       // n_store is a multiple of 8 on this path
+  float4 bi[2][4];                                            // this lane's bias values for the 64 columns
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int n = nb + a * 32 + q * 8 + grp * 4;
+      bi[a][q] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (n < g.n_store) bi[a][q] = *reinterpret_cast<const float4 *>(g.bias + n);
+    }
 #pragma unroll
   for (int b = 0; b < FM; ++b) {
     const int mb = m_base + b * 32;
@@ -215,14 +226,15 @@ __device__ __forceinline__ void gemm_epilogue_lds(f32x16 (&acc)[FN][FM], const G
     }
 #pragma unroll
     for (int a = 0; a < 2; ++a) {
+      f32x16 av = acc[half * 2 + a][b];
+      if constexpr (PIN) {                      // one accumulator at a time leaves the accumulation registers
+        asm volatile("" : "+v"(av));
+        __builtin_amdgcn_sched_barrier(0);
+      }
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int n = nb + a * 32 + q * 8 + grp * 4;
-        float4 bi = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (n < g.n_store) bi = *reinterpret_cast<const float4 *>(g.bias + n);
-        const f32x16 &av = acc[half * 2 + a][b];
-        float v0 = av[q * 4 + 0] + bi.x, v1 = av[q * 4 + 1] + bi.y;
-        float v2 = av[q * 4 + 2] + bi.z, v3 = av[q * 4 + 3] + bi.w;
+        float v0 = av[q * 4 + 0] + bi[a][q].x, v1 = av[q * 4 + 1] + bi[a][q].y;
+        float v2 = av[q * 4 + 2] + bi[a][q].z, v3 = av[q * 4 + 3] + bi[a][q].w;
         if (EPI == EPI_BIAS_GELU) {
           v0 = gelu_tanh_f(v0); v1 = gelu_tanh_f(v1); v2 = gelu_tanh_f(v2); v3 = gelu_tanh_f(v3);
         }
@@ -507,7 +519,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_dma_kernel(G
 // registers) while the finished tile's epilogue runs.  That removes the per-tile prologue latency
 // and the workgroup relaunch between tiles.
 // ---------------------------------------------------------------------------------------
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, int MINB, int EPI>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, int MINB, int EPI, int ACCA = 0>
 __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kernel(GemmArgs g, int tiles_m, int tiles_n) {
   constexpr int NW = WAVES_M * WAVES_N;
   constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
@@ -569,14 +581,17 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
   };
   const int kt_n = g.K / BK;
   int load_tile = 0, load_kt = 0;                   // next k-tile of the stream to be fetched
-  auto issue_next = [&](int stage) {
+  auto issue_one = [&](int stage, int i) {          // i-th 1 KiB load of this wavefront for the next k-tile
     uint16_t *as = lds + stage * STAGE_ELEMS;
     uint16_t *ws = as + BM * BK;
     const int ko = load_kt * BK;
-#pragma unroll
-    for (int i = 0; i < A_BLK; ++i) ET_LDS_DMA16(a_src[i] + ko, as + (wave * A_BLK + i) * 512);
-#pragma unroll
-    for (int i = 0; i < W_BLK; ++i) ET_LDS_DMA16(w_src[i] + ko, ws + (wave * W_BLK + i) * 512);
+    if (i < A_BLK) {
+      ET_LDS_DMA16(a_src[i] + ko, as + (wave * A_BLK + i) * 512);
+    } else {
+      ET_LDS_DMA16(w_src[i - A_BLK] + ko, ws + (wave * W_BLK + (i - A_BLK)) * 512);
+    }
+  };
+  auto issue_advance = [&]() {
     if (++load_kt == kt_n) {                        // past the stream's end the last k-tile is re-read (unused)
       if (load_tile + 1 < n_my) {
         load_kt = 0;
@@ -586,6 +601,11 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
       }
     }
   };
+  auto issue_next = [&](int stage) {
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) issue_one(stage, i);
+    issue_advance();
+  };
 
   const int fx = (r32 >> SWZ) & (CPR - 1);
   int koff[KS];
@@ -594,12 +614,24 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
   const int a_row = (wm * WTM + r32) * BK, w_row = (wn * WTN + r32) * BK;
 
   f32x16 acc[FN][FM];
+  auto clear_acc = [&]() {        // in place: 0 * 0 + 0 through the matrix unit (no second copy of the accumulators)
+    const u32x4 z = u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
-  for (int a = 0; a < FN; ++a)
+    for (int a = 0; a < FN; ++a)
 #pragma unroll
-    for (int b = 0; b < FM; ++b)
+      for (int b = 0; b < FM; ++b)
+        asm volatile("s_nop 4\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %1, 0" : "+a"(acc[a][b]) : "v"(z));   // idle states: the zero operand may have just been written
+  };
+  if constexpr (!ACCA) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+    for (int a = 0; a < FN; ++a)
+#pragma unroll
+      for (int b = 0; b < FM; ++b)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+  } else {
+    clear_acc();
+  }
 
   set_load_tile(0);
 #pragma unroll
@@ -618,15 +650,58 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
 #pragma unroll
     for (int a = 0; a < FN; ++a)
 #pragma unroll
-      for (int b = 0; b < FM; ++b) acc[a][b] = mfma32(fw[buf][a], fa[buf][b], acc[a][b]);
+      for (int b = 0; b < FM; ++b) {
+        if constexpr (ACCA) {
+          asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc[a][b]) : "v"(fw[buf][a]), "v"(fa[buf][b]));
+        } else {
+          acc[a][b] = mfma32(fw[buf][a], fa[buf][b], acc[a][b]);
+        }
+      }
+  };
+  auto mfma_first = [&](int buf) {            // first MFMA of an output tile: C = 0 (defines the accumulators)
+#pragma unroll
+    for (int a = 0; a < FN; ++a)
+#pragma unroll
+      for (int b = 0; b < FM; ++b)
+        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=a"(acc[a][b]) : "v"(fw[buf][a]), "v"(fa[buf][b]));
+  };
+  // ACCA: MFMAs on fragment buffer `cur` with the reads of the next k-slice (stage nst, slice nks, into
+  // the other buffer) placed one after each of the first FM + FN MFMAs.  The asm statements are
+  // volatile, so this order is the issue order.
+  auto step_acca = [&](int cur, int nst, int nks, auto with_loads, int load_stage) {
+    const uint16_t *as = lds + nst * STAGE_ELEMS;
+    const uint16_t *ws = as + BM * BK;
+    const int nxt = cur ^ 1;
+    int idx = 0;
+#pragma unroll
+    for (int a = 0; a < FN; ++a)
+#pragma unroll
+      for (int b = 0; b < FM; ++b) {
+        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc[a][b]) : "v"(fw[cur][a]), "v"(fa[cur][b]));
+        if (idx < FM)
+          fa[nxt][idx] = *reinterpret_cast<const u32x4 *>(as + a_row + idx * 32 * BK + koff[nks]);
+        else if (idx < FM + FN)
+          fw[nxt][idx - FM] = *reinterpret_cast<const u32x4 *>(ws + w_row + (idx - FM) * 32 * BK + koff[nks]);
+        if constexpr (decltype(with_loads)::value) {   // the next k-tile's loads ride under this group's MFMAs
+#pragma unroll
+          for (int i = idx * LOADS / (FM * FN); i < (idx + 1) * LOADS / (FM * FN); ++i) issue_one(load_stage, i);
+        }
+        ++idx;
+      }
+    if constexpr (decltype(with_loads)::value) issue_advance();
+    __builtin_amdgcn_sched_barrier(0);
   };
   auto interleave = [&]() {
+    if constexpr (ACCA) {
+      __builtin_amdgcn_sched_barrier(0);
+    } else {
 #pragma unroll
-    for (int i = 0; i < FM + FN; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      for (int i = 0; i < FM + FN; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, FM * FN - (FM + FN), 0);
     }
-    __builtin_amdgcn_sched_group_barrier(0x008, FM * FN - (FM + FN), 0);
   };
 
   wait_vmcnt<(STAGES - 1) * LOADS>();
@@ -640,9 +715,13 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
   for (int u = 0; u < units; ++u) {
 #pragma unroll
     for (int ks = 0; ks < KS - 1; ++ks) {
-      read_frags((ks + 1) & 1, stage, ks + 1);
-      mfma_step(ks & 1);
-      interleave();
+      if constexpr (ACCA) {
+        step_acca(ks & 1, stage, ks + 1, std::false_type{}, 0);
+      } else {
+        read_frags((ks + 1) & 1, stage, ks + 1);
+        mfma_step(ks & 1);
+        interleave();
+      }
     }
     // Vector-memory operations retire in issue order.  For STAGES - 1 units after the epilogue of
     // an interior tile (every lane stored: exactly N_ST store instructions per wavefront) those
@@ -657,28 +736,37 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    issue_next(stage);
     const int next_stage = (stage + 1 == STAGES) ? 0 : stage + 1;
-    read_frags(KS & 1, next_stage, 0);
-    mfma_step((KS - 1) & 1);
-    interleave();
+    if constexpr (ACCA) {
+      step_acca((KS - 1) & 1, next_stage, 0, std::true_type{}, stage);
+    } else {
+      issue_next(stage);
+      read_frags(KS & 1, next_stage, 0);
+      mfma_step((KS - 1) & 1);
+      interleave();
+    }
     stage = next_stage;
     if (++kt == kt_n) {                             // an output tile is complete
       int m0, n0;
       tile_of(my_tile, m0, n0);
+      if constexpr (ACCA) asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
       if constexpr (WTN % 64 == 0) {
-        gemm_epilogue_lds<EPI, FM, FN>(acc, g, m0 + wm * WTM, n0 + wn * WTN, lane,
-                                       lds + STAGES * STAGE_ELEMS + wave * (32 * 64));
+        gemm_epilogue_lds<EPI, FM, FN, ACCA>(acc, g, m0 + wm * WTM, n0 + wn * WTN, lane,
+                                             lds + STAGES * STAGE_ELEMS + wave * (32 * 64));
         if (m0 + BM <= g.M && n0 + BN <= g.n_store) relax = STAGES - 1;
       } else {
         gemm_epilogue<EPI, FM, FN>(acc, g, m0 + wm * WTM, n0 + wn * WTN, r32, grp);
       }
+      if constexpr (!ACCA) {
 #pragma unroll
-      for (int a = 0; a < FN; ++a)
+        for (int a = 0; a < FN; ++a)
 #pragma unroll
-        for (int b = 0; b < FM; ++b)
+          for (int b = 0; b < FM; ++b)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+      } else {
+        clear_acc();
+      }
       kt = 0;
       ++my_tile;
     }
@@ -686,7 +774,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
   wait_vmcnt<0>();
 }
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, int MINB = 1>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, int MINB = 1, int ACCA = 0>
 int launch_gemm_stream_cfg(const GemmArgs &g, hipStream_t s) {
   constexpr int NT = WAVES_M * WAVES_N * 64;
   // k-tile stages plus, for 64-column wavefront tiles, one 4 KiB epilogue slice per wavefront
@@ -706,7 +794,7 @@ int launch_gemm_stream_cfg(const GemmArgs &g, hipStream_t s) {
   const dim3 grid(n_tiles < slots ? n_tiles : slots), block(NT);
 #define ET_GEMM_LAUNCH(E)                                                                        \
   {                                                                                              \
-    auto kern = gemm_stream_kernel<BM, BN, BK, WAVES_M, WAVES_N, STAGES, MINB, E>;               \
+    auto kern = gemm_stream_kernel<BM, BN, BK, WAVES_M, WAVES_N, STAGES, MINB, E, ACCA>;         \
     static bool attr_set = false;                                                                \
     if (!attr_set) {                                                                             \
       ET_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                           \
@@ -1226,7 +1314,7 @@ int launch_im2col(const float *frames, int T, int C, int H, int W, int P, int Kp
   return ET_OK;
 }
 
-int gemm_config_count() { return 33; }
+int gemm_config_count() { return 36; }
 
 static int launch_gemm_id(const GemmArgs &g, hipStream_t s, int cfg) {
   switch (cfg) {
@@ -1263,6 +1351,9 @@ static int launch_gemm_id(const GemmArgs &g, hipStream_t s, int cfg) {
     case 30: return launch_gemm_stream_cfg<256, 256, 32, 2, 4, 4, 1>(g, s);
     case 31: return launch_gemm_stream_cfg<256, 256, 32, 4, 2, 4, 1>(g, s);
     case 32: return launch_gemm_stream_cfg<256, 256, 32, 4, 2, 3, 1>(g, s);
+    case 33: return launch_gemm_stream_cfg<256, 256, 64, 2, 2, 2, 1, 1>(g, s);
+    case 34: return launch_gemm_stream_cfg<256, 256, 32, 2, 2, 4, 1, 1>(g, s);
+    case 35: return launch_gemm_stream_cfg<256, 256, 32, 2, 2, 3, 1, 1>(g, s);
     default: set_error("unknown gemm tile configuration %d", cfg); return ET_ERR_INVALID_ARG;
   }
 }

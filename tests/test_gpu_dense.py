@@ -61,7 +61,7 @@ def test_gemm_matches_oracle(M, N, K, epi):
     assert rel_l2(got, ref) < 4e-3
 
 
-@pytest.mark.parametrize("cfg", list(range(33)))
+@pytest.mark.parametrize("cfg", list(range(36)))
 def test_gemm_every_tile_configuration(cfg):
     """Each workgroup tiling, on a shape with ragged M, several k-tiles and a partial N tile."""
     rng = np.random.default_rng(cfg)
@@ -158,3 +158,23 @@ def test_attention_uniform_matches_oracle(n_heads, hd, n_frames, length):
     # the general (ragged) kernel agrees on the same input
     gen = et.et_attention(bits_to_dev(bits), torch.from_numpy(cu).cuda(), length, n_heads, hd)
     assert rel_l2(dev_to_f64(gen), got) < 6e-3
+
+
+@pytest.mark.parametrize("cfg", [20, 33, 34, 35])
+def test_gemm_persistent_configs_walk_several_tiles_per_workgroup(cfg):
+    """More output tiles than compute units, so each persistent workgroup finishes a tile, clears its
+    accumulators and goes on; ragged last tile row and column; all three epilogues."""
+    rng = np.random.default_rng(100 + cfg)
+    M, N, K = 4500, 4304, 320                       # 18 x 17 = 306 tiles of 256 x 256
+    a_bits, a = _bf(rng, (M, K))
+    w_bits, w = _bf(rng, (N, K), scale=0.05)
+    bias = (0.1 * rng.standard_normal(N)).astype(np.float32)
+    r_bits, r = _bf(rng, (M, N))
+    lin = a @ w.T + bias.astype(np.float64)
+    a_d, w_d, b_d = bits_to_dev(a_bits), bits_to_dev(w_bits), torch.from_numpy(bias).cuda()
+    for epi, ref in ((0, lin), (1, O.gelu_tanh(lin)), (2, lin + r)):
+        c = et.et_gemm_bf16(a_d, w_d, b_d, epi, residual=bits_to_dev(r_bits) if epi == 2 else None,
+                            tile_config=cfg)
+        got = dev_to_f64(c)
+        assert np.max(np.abs(got - ref) - 2 ** -8 * np.abs(ref)) < 5e-4, epi
+        assert rel_l2(got, ref) < 4e-3, epi
