@@ -210,6 +210,18 @@ __device__ __forceinline__ void gemm_epilogue_lds(f32x16 (&acc)[FN][FM], const G
       bi[a][q] = make_float4(0.f, 0.f, 0.f, 0.f);
       if (n < g.n_store) bi[a][q] = *reinterpret_cast<const float4 *>(g.bias + n);
     }
+  // residual rows of a 32-row block, fetched coalesced one block ahead of their use
+  u32x4 rv[4];
+  auto fetch_res = [&](int b) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int m = m_base + b * 32 + j * 8 + prow;
+      rv[j] = u32x4{0u, 0u, 0u, 0u};
+      if (m < g.M && n_ok)
+        rv[j] = *reinterpret_cast<const u32x4 *>(g.res + (size_t)(m % g.res_mod) * g.ldr + n_lane);
+    }
+  };
+  if (EPI == EPI_BIAS_RES) fetch_res(0);
 #pragma unroll
   for (int b = 0; b < FM; ++b) {
     const int mb = m_base + b * 32;
@@ -217,12 +229,10 @@ __device__ __forceinline__ void gemm_epilogue_lds(f32x16 (&acc)[FN][FM], const G
     if (EPI == EPI_BIAS_RES) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const int row = j * 8 + prow, m = mb + row;
-        u32x4 rv = u32x4{0u, 0u, 0u, 0u};
-        if (m < g.M && n_ok)
-          rv = *reinterpret_cast<const u32x4 *>(g.res + (size_t)(m % g.res_mod) * g.ldr + n_lane);
-        *reinterpret_cast<u32x4 *>(slice + row * 64 + ((pch ^ ((row >> 1) & 7)) * 8)) = rv;
+        const int row = j * 8 + prow;
+        *reinterpret_cast<u32x4 *>(slice + row * 64 + ((pch ^ ((row >> 1) & 7)) * 8)) = rv[j];
       }
+      if (b + 1 < FM) fetch_res(b + 1);
     }
 #pragma unroll
     for (int a = 0; a < 2; ++a) {
@@ -622,7 +632,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
       for (int b = 0; b < FM; ++b)
         asm volatile("s_nop 4\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %1, 0" : "+a"(acc[a][b]) : "v"(z));   // idle states: the zero operand may have just been written
   };
-  if constexpr (!ACCA) {
+  if constexpr (ACCA <= 0) {
 #pragma unroll
     for (int a = 0; a < FN; ++a)
 #pragma unroll
@@ -634,8 +644,15 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
   }
 
   set_load_tile(0);
+  if constexpr (ACCA == 3) {      // spread loads: the last stage gets its first part here, the rest in the first unit
 #pragma unroll
-  for (int st = 0; st < STAGES; ++st) issue_next(st);
+    for (int st = 0; st < STAGES - 1; ++st) issue_next(st);
+#pragma unroll
+    for (int i = 0; i < LOADS / KS; ++i) issue_one(STAGES - 1, i);
+  } else {
+#pragma unroll
+    for (int st = 0; st < STAGES; ++st) issue_next(st);
+  }
 
   u32x4 fa[2][FM], fw[2][FN];
   auto read_frags = [&](int buf, int stage, int ks) {
@@ -651,7 +668,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
     for (int a = 0; a < FN; ++a)
 #pragma unroll
       for (int b = 0; b < FM; ++b) {
-        if constexpr (ACCA) {
+        if constexpr (ACCA > 0) {
           asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc[a][b]) : "v"(fw[buf][a]), "v"(fa[buf][b]));
         } else {
           acc[a][b] = mfma32(fw[buf][a], fa[buf][b], acc[a][b]);
@@ -668,7 +685,8 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
   // ACCA: MFMAs on fragment buffer `cur` with the reads of the next k-slice (stage nst, slice nks, into
   // the other buffer) placed one after each of the first FM + FN MFMAs.  The asm statements are
   // volatile, so this order is the issue order.
-  auto step_acca = [&](int cur, int nst, int nks, auto with_loads, int load_stage) {
+  // Loads lo .. hi-1 of the k-tile bound for `load_stage` ride under this group's MFMAs (lo == hi: none).
+  auto step_acca = [&](int cur, int nst, int nks, int lo, int hi, int load_stage) {
     const uint16_t *as = lds + nst * STAGE_ELEMS;
     const uint16_t *ws = as + BM * BK;
     const int nxt = cur ^ 1;
@@ -682,17 +700,20 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
           fa[nxt][idx] = *reinterpret_cast<const u32x4 *>(as + a_row + idx * 32 * BK + koff[nks]);
         else if (idx < FM + FN)
           fw[nxt][idx - FM] = *reinterpret_cast<const u32x4 *>(ws + w_row + (idx - FM) * 32 * BK + koff[nks]);
-        if constexpr (decltype(with_loads)::value) {   // the next k-tile's loads ride under this group's MFMAs
 #pragma unroll
-          for (int i = idx * LOADS / (FM * FN); i < (idx + 1) * LOADS / (FM * FN); ++i) issue_one(load_stage, i);
-        }
+        for (int i = lo + idx * (hi - lo) / (FM * FN); i < lo + (idx + 1) * (hi - lo) / (FM * FN); ++i)
+          issue_one(load_stage, i);
         ++idx;
       }
-    if constexpr (decltype(with_loads)::value) issue_advance();
     __builtin_amdgcn_sched_barrier(0);
   };
+  // ACCA == 3 (needs STAGES >= 3): the loads of a k-tile are spread over all KS groups between two
+  // barriers instead of riding under one group, which keeps the address unit below its rate.
+  constexpr bool SPREAD = (ACCA == 3);
+  static_assert(!SPREAD || STAGES >= 3, "spread loads need a stage that stays free for a whole unit");
+  constexpr int PART = LOADS / KS;
   auto interleave = [&]() {
-    if constexpr (ACCA) {
+    if constexpr (ACCA > 0) {
       __builtin_amdgcn_sched_barrier(0);
     } else {
 #pragma unroll
@@ -704,19 +725,22 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
     }
   };
 
-  wait_vmcnt<(STAGES - 1) * LOADS>();
+  wait_vmcnt<SPREAD ? (STAGES - 2) * LOADS + PART : (STAGES - 1) * LOADS>();
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
   read_frags(0, 0, 0);
 
-  int stage = 0, kt = 0, my_tile = 0, relax = 0;
+  int stage = 0, kt = 0, my_tile = 0, relax = 0, free_stage = STAGES - 1;
   constexpr int N_ST = FM * (FN / 2) * 4;            // global stores per wavefront in the staged epilogue
   const int units = n_my * kt_n;
   for (int u = 0; u < units; ++u) {
 #pragma unroll
     for (int ks = 0; ks < KS - 1; ++ks) {
-      if constexpr (ACCA) {
-        step_acca(ks & 1, stage, ks + 1, std::false_type{}, 0);
+      if constexpr (SPREAD) {
+        step_acca(ks & 1, stage, ks + 1, (ks + 1) * PART, (ks + 2) * PART, free_stage);
+        if (ks == KS - 2) issue_advance();
+      } else if constexpr (ACCA > 0) {
+        step_acca(ks & 1, stage, ks + 1, 0, 0, 0);
       } else {
         read_frags((ks + 1) & 1, stage, ks + 1);
         mfma_step(ks & 1);
@@ -737,8 +761,12 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     const int next_stage = (stage + 1 == STAGES) ? 0 : stage + 1;
-    if constexpr (ACCA) {
-      step_acca((KS - 1) & 1, next_stage, 0, std::true_type{}, stage);
+    if constexpr (SPREAD) {
+      free_stage = stage;
+      step_acca((KS - 1) & 1, next_stage, 0, 0, PART, stage);
+    } else if constexpr (ACCA > 0) {
+      step_acca((KS - 1) & 1, next_stage, 0, 0, LOADS, stage);
+      issue_advance();
     } else {
       issue_next(stage);
       read_frags(KS & 1, next_stage, 0);
@@ -749,15 +777,16 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
     if (++kt == kt_n) {                             // an output tile is complete
       int m0, n0;
       tile_of(my_tile, m0, n0);
-      if constexpr (ACCA) asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+      if constexpr (ACCA > 0) asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
       if constexpr (WTN % 64 == 0) {
-        gemm_epilogue_lds<EPI, FM, FN, ACCA>(acc, g, m0 + wm * WTM, n0 + wn * WTN, lane,
+        gemm_epilogue_lds<EPI, FM, FN, (ACCA > 0)>(acc, g, m0 + wm * WTM, n0 + wn * WTN, lane,
                                              lds + STAGES * STAGE_ELEMS + wave * (32 * 64));
-        if (m0 + BM <= g.M && n0 + BN <= g.n_store) relax = STAGES - 1;
+        // (with spread loads the last k-tile issued before the stores is one unit older)
+        if (m0 + BM <= g.M && n0 + BN <= g.n_store) relax = SPREAD ? STAGES - 2 : STAGES - 1;
       } else {
         gemm_epilogue<EPI, FM, FN>(acc, g, m0 + wm * WTM, n0 + wn * WTN, r32, grp);
       }
-      if constexpr (!ACCA) {
+      if constexpr (ACCA <= 0) {
 #pragma unroll
         for (int a = 0; a < FN; ++a)
 #pragma unroll
@@ -1352,8 +1381,8 @@ static int launch_gemm_id(const GemmArgs &g, hipStream_t s, int cfg) {
     case 31: return launch_gemm_stream_cfg<256, 256, 32, 4, 2, 4, 1>(g, s);
     case 32: return launch_gemm_stream_cfg<256, 256, 32, 4, 2, 3, 1>(g, s);
     case 33: return launch_gemm_stream_cfg<256, 256, 64, 2, 2, 2, 1, 1>(g, s);
-    case 34: return launch_gemm_stream_cfg<256, 256, 32, 2, 2, 4, 1, 1>(g, s);
-    case 35: return launch_gemm_stream_cfg<256, 256, 32, 2, 2, 3, 1, 1>(g, s);
+    case 34: return launch_gemm_stream_cfg<256, 256, 32, 2, 2, 4, 1, 3>(g, s);
+    case 35: return launch_gemm_stream_cfg<256, 256, 32, 2, 2, 3, 1, 3>(g, s);
     default: set_error("unknown gemm tile configuration %d", cfg); return ET_ERR_INVALID_ARG;
   }
 }
