@@ -95,6 +95,38 @@ def attention(xn, lw, n_heads):
     return o @ np.asarray(lw["wo"], dtype=dt).T + np.asarray(lw["bo"], dtype=dt)
 
 
+def round_bf16(a):
+    """Round to bfloat16 (nearest, ties to even) and return the values as float64."""
+    f = np.ascontiguousarray(np.asarray(a, dtype=np.float32))
+    b = f.view(np.uint32).astype(np.uint64)
+    b = ((b + 0x7FFF + ((b >> 16) & 1)) >> 16) << 16
+    return b.astype(np.uint32).view(np.float32).reshape(f.shape).astype(np.float64)
+
+
+def attention_received(x, lw, n_heads, eps, storage_bf16=False):
+    """Per-token attention score of Sec. 3.3 / Alg. 2 ("attentions A from the vision encoder").
+
+    The paper does not say how a per-token score is taken from the attention maps; the reading
+    here: the attention a token RECEIVES in the block with weights `lw`, i.e. the column mean of the
+    softmax matrix over all queries of its frame, averaged over the heads.  x: [F, n, D] is the
+    input of that block.  Returns [F, n]; every row sums to 1.
+    storage_bf16: round the LayerNorm output and q, k to bfloat16 first, the points where the device
+    path stores bfloat16, so that a ranking is decided from the same numbers on both sides."""
+    F, n, D = x.shape
+    hd = D // n_heads
+    dt = x.dtype
+    xn = layer_norm(x, np.asarray(lw["ln1_g"], dt), np.asarray(lw["ln1_b"], dt), eps)
+    if storage_bf16:
+        xn = round_bf16(xn).astype(dt)
+    qk = xn @ np.asarray(lw["wqkv"], dtype=dt)[:2 * D].T + np.asarray(lw["bqkv"], dtype=dt)[:2 * D]
+    if storage_bf16:
+        qk = round_bf16(qk).astype(dt)
+    q = qk[..., :D].reshape(F, n, n_heads, hd).transpose(0, 2, 1, 3)
+    k = qk[..., D:].reshape(F, n, n_heads, hd).transpose(0, 2, 1, 3)
+    p = softmax_rows((q @ k.transpose(0, 1, 3, 2)) / math.sqrt(hd))        # F, H, query, key
+    return p.mean(axis=(1, 2))
+
+
 def mlp(xn, lw):
     dt = xn.dtype
     h = gelu_tanh(xn @ np.asarray(lw["w1"], dtype=dt).T + np.asarray(lw["b1"], dtype=dt))
@@ -469,11 +501,26 @@ def encode_clip_multi(shape, w, frames, merge_layers, select_layer, policy, dtyp
     merge_layers = list(merge_layers)
     stage_layers = sorted(set(merge_layers) | {select_layer})
     stages, score = {}, None
+    by_attention = policy.get("score_mode", "l2") == "attention"
+    z_att = None
+    if by_attention:
+        # the scores are the attention received in the block just before the selection, which has to
+        # see the frames the selection sees: no merge may sit between that block and the selection
+        assert select_layer >= 1 and select_layer not in merge_layers, \
+            "attention scores need a block between the last merge and the selection"
+        stage_layers = sorted(set(stage_layers) | {select_layer - 1})
 
     def replaced_later(i):
         nxt = [j for j in stage_layers if j > i]
         return bool(nxt) and x_at_layers is not None and nxt[0] in x_at_layers
     for i in range(n_layers + 1):
+        if by_attention and i == select_layer - 1 and i not in merge_layers:
+            if x_at_layers is not None and i in x_at_layers:
+                x = np.asarray(x_at_layers[i], dtype=dtype)
+                if x.shape[0] != len(first):
+                    raise ValueError("x_at_layers[%d] holds %d frames, the plan so far gives %d"
+                                     % (i, x.shape[0], len(first)))
+            hidden[i] = x
         if rows is None and (i in merge_layers or i == select_layer):
             if x_at_layers is not None and i in x_at_layers:
                 x = np.asarray(x_at_layers[i], dtype=dtype)
@@ -497,7 +544,9 @@ def encode_clip_multi(shape, w, frames, merge_layers, select_layer, policy, dtyp
                 first, count = nf, ne - nf
                 dyn = np.asarray([p["dynamic"] for p in plan], dtype=np.int32)
             if i == select_layer:
-                if z is None:
+                if by_attention:
+                    z = z_att
+                elif z is None:
                     z = token_score(x)
                 N = x.shape[0]
                 score = z
@@ -513,6 +562,10 @@ def encode_clip_multi(shape, w, frames, merge_layers, select_layer, policy, dtyp
                 cu = np.concatenate([[0], np.cumsum([len(p) for p in per_frame])]).astype(np.int32)
                 kept = np.concatenate(per_frame).astype(np.int32)
                 rows = np.concatenate([x[n][per_frame[n]] for n in range(N)], axis=0)
+        if by_attention and i == select_layer - 1:
+            # (after this layer's own merge, if it has one: the block runs on the merged frames)
+            z_att = attention_received(x, w["layers"][i], shape.n_heads, shape.ln_eps,
+                                       storage_bf16=policy.get("score_storage_bf16", False))
         if i < n_layers:
             if rows is None:
                 if not replaced_later(i):

@@ -224,3 +224,94 @@ def test_multi_layer_merging_reductions_and_bookkeeping(tiny):
     assert f1["n_frames_out"] == f3["n_frames_out"] == 3
     assert f3["frame_first"].tolist() == [0, 6, 7] and f3["frame_count"].tolist() == [6, 1, 5]
     np.testing.assert_allclose(f3["tokens"], f1["tokens"], rtol=1e-12, atol=1e-12)
+
+
+# ---- attention-received scores (Sec. 3.3 "per-token attention scores"; reading stated in the oracle) ----
+
+def _tiny_layer(rng, D, H):
+    return dict(ln1_g=1.0 + 0.1 * rng.standard_normal(D), ln1_b=0.1 * rng.standard_normal(D),
+                wqkv=0.4 * rng.standard_normal((3 * D, D)), bqkv=0.1 * rng.standard_normal(3 * D))
+
+
+def test_attention_received_matches_explicit_loops():
+    """Written out with scalar loops: softmax row by row, then the column mean over queries and heads."""
+    rng = np.random.default_rng(0)
+    F, n, D, H, eps = 2, 7, 8, 2, 1e-6
+    lw = _tiny_layer(rng, D, H)
+    x = rng.standard_normal((F, n, D))
+    got = O.attention_received(x, lw, H, eps)
+    hd = D // H
+    want = np.zeros((F, n))
+    for f in range(F):
+        xn = np.zeros((n, D))
+        for i in range(n):
+            mu = sum(x[f, i]) / D
+            var = sum((v - mu) ** 2 for v in x[f, i]) / D
+            xn[i] = [(v - mu) / math.sqrt(var + eps) * g + b for v, g, b in zip(x[f, i], lw["ln1_g"], lw["ln1_b"])]
+        q = [[sum(lw["wqkv"][c, d] * xn[i, d] for d in range(D)) + lw["bqkv"][c] for c in range(D)] for i in range(n)]
+        k = [[sum(lw["wqkv"][D + c, d] * xn[i, d] for d in range(D)) + lw["bqkv"][D + c] for c in range(D)]
+             for i in range(n)]
+        for h in range(H):
+            for i in range(n):
+                logit = [sum(q[i][h * hd + c] * k[j][h * hd + c] for c in range(hd)) / math.sqrt(hd) for j in range(n)]
+                mx = max(logit)
+                e = [math.exp(v - mx) for v in logit]
+                tot = sum(e)
+                for j in range(n):
+                    want[f, j] += e[j] / tot / (n * H)
+    assert np.allclose(got, want, rtol=1e-12, atol=1e-15)
+    assert np.allclose(got.sum(axis=1), 1.0)
+
+
+def test_attention_received_closed_form_two_token_types():
+    """One head, identity LayerNorm (rows already have mean 0, variance 1), q = k = c x: the logits take
+    two values +-t, so every softmax row is known in closed form.  m tokens of type (1,-1), n-m of type
+    (-1,1): a column of the larger group receives more than 1/n - a row mean would give exactly 1/n."""
+    n, m, c = 7, 5, 0.8
+    D = 2
+    x = np.array([[1.0, -1.0]] * m + [[-1.0, 1.0]] * (n - m))[None]
+    lw = dict(ln1_g=np.ones(D), ln1_b=np.zeros(D), wqkv=np.concatenate([c * np.eye(D), c * np.eye(D), np.eye(D)]),
+              bqkv=np.zeros(3 * D))
+    got = O.attention_received(x, lw, 1, 0.0)[0]
+    t = 2 * c * c / math.sqrt(2.0)
+    row_a = m * math.exp(t) + (n - m) * math.exp(-t)         # normaliser of a type-A query
+    row_b = (n - m) * math.exp(t) + m * math.exp(-t)
+    col_a = (m * math.exp(t) / row_a + (n - m) * math.exp(-t) / row_b) / n
+    col_b = (m * math.exp(-t) / row_a + (n - m) * math.exp(t) / row_b) / n
+    assert np.allclose(got[:m], col_a, rtol=1e-13) and np.allclose(got[m:], col_b, rtol=1e-13)
+    assert col_a > 1.0 / n > col_b
+
+
+def test_attention_received_special_cases():
+    rng = np.random.default_rng(3)
+    D, H = 8, 2
+    lw = _tiny_layer(rng, D, H)
+    same = np.tile(rng.standard_normal((1, 1, D)), (1, 9, 1))
+    assert np.allclose(O.attention_received(same, lw, H, 1e-6), 1.0 / 9)       # identical tokens: uniform
+    x = rng.standard_normal((3, 6, D))
+    perm = rng.permutation(6)
+    a = O.attention_received(x, lw, H, 1e-6)
+    assert np.allclose(O.attention_received(x[:, perm], lw, H, 1e-6), a[:, perm])   # equivariant to token order
+    # values exactly representable in bfloat16 and untouched by the rounding points give the same scores
+    assert np.array_equal(O.round_bf16(np.array([0.5, -3.0, 1.0 + 2.0 ** -7])), np.array([0.5, -3.0, 1.0 + 2.0 ** -7]))
+    assert np.array_equal(O.round_bf16(np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8])),
+                          np.array([1.0, 1.0 + 2.0 ** -6]))                     # ties go to the even mantissa
+
+
+def test_multi_layer_selection_by_attention_scores(tiny):
+    w, frames = tiny
+    pol = dict(merge_mode="alg1", select_mode="decoupled", alpha=0.9, tau_seg=0.9, tau_merge=0.9, ratio=0.25,
+               score_mode="attention")
+    r = O.encode_clip_multi(TINY, w, frames, [1], 3, pol)
+    # the scores are those of block 2 on the frames it sees, and the kept tokens are their top-k / window maxima
+    z = O.attention_received(r["hidden"][2], w["layers"][2], TINY.n_heads, TINY.ln_eps)
+    assert np.array_equal(r["score"], z)
+    L = TINY.tokens_per_frame
+    r_hat = O.rescaled_count(pol["ratio"], frames.shape[0], L, r["n_frames_out"])
+    cu = r["cu_tokens"]
+    for n in range(r["n_frames_out"]):
+        kept = r["kept_idx"][cu[n]:cu[n + 1]]
+        want = O.topk_positions(z[n], r_hat) if r["frame_dynamic"][n] else O.window_positions(z[n], r_hat)
+        assert np.array_equal(kept, want)
+    with pytest.raises(AssertionError):
+        O.encode_clip_multi(TINY, w, frames, [1, 3], 3, pol)       # a merge between the scoring block and the selection
