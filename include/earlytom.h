@@ -138,14 +138,23 @@ const char *et_last_error(void); /* thread-local, never NULL */
  *                w = floor(L / r_hat) consecutive positions (Eq. 6).
  *   alpha        smoothing factor of Eq. 1 in (0, 1]; the smoothed similarity restarts at every
  *                segment start.  tau_seg: segment threshold.  tau_merge: Eq. 2 threshold.
- * Scores, tie-breaks and ordering are those of the simple path.  With these forms output frames
+ *   score_mode   ET_SCORE_L2NORM: a token's score is its squared L2 norm (as on the simple path).
+ *                ET_SCORE_ATTENTION: the attention the token receives in the encoder block just
+ *                before the selection (Sec. 3.3 ranks by "per-token attention scores" without
+ *                defining them; this library's reading): the mean over heads and over the queries
+ *                of its frame of softmax(Q K^T / sqrt(hd))[query][token].  Needs a block before
+ *                the selection (select layer >= 1) whose input is what the selection sees, so no
+ *                merge may run at the select layer itself; only et_encode_clip_multi accepts it.
+ * Tie-breaks and ordering are those of the simple path.  With these forms output frames
  * keep different token counts: cu_tokens_dev is ragged, seg_start_dev has n_segments + 1 entries
  * and n_frames_out counts output frames (>= segments). */
 enum { ET_MERGE_MEAN = 0, ET_MERGE_ALG1 = 1 };
 enum { ET_SELECT_UNIFORM = 0, ET_SELECT_DECOUPLED = 1 };
+enum { ET_SCORE_L2NORM = 0, ET_SCORE_ATTENTION = 1 };
 typedef struct {
   int32_t merge_mode, select_mode;
   float alpha, tau_seg, tau_merge, ratio;
+  int32_t score_mode;
 } et_policy;
 
 /* Optional description of the output frames (device arrays of capacity T, or NULL). */
@@ -173,7 +182,7 @@ int et_encode_clip_policy(et_encoder *enc, const float *frames_dev, int32_t T, i
 enum {
   ET_K_IM2COL = 0, ET_K_GEMM_PATCH, ET_K_LAYERNORM, ET_K_GEMM_QKV, ET_K_ATTENTION,
   ET_K_GEMM_OUT, ET_K_GEMM_FC1, ET_K_GEMM_FC2, ET_K_SIMILARITY, ET_K_SCAN, ET_K_MERGE,
-  ET_K_SELECT, ET_K_COMPACT, ET_K_MISC, ET_K_COUNT
+  ET_K_SELECT, ET_K_COMPACT, ET_K_MISC, ET_K_SCORE, ET_K_COUNT
 };
 int et_profile_enable(et_encoder *enc, int32_t on);
 /* Reads the accumulators into ms[2 * ET_K_COUNT] and launches[2 * ET_K_COUNT]: entry
@@ -262,6 +271,14 @@ int et_encode_clip_multi(et_encoder *enc, const float *frames_dev, int32_t T, co
                          int32_t n_merge_layers, int32_t select_layer, const et_policy *policy,
                          void *workspace_dev, size_t workspace_bytes, void *hip_stream, et_output *out,
                          et_plan_out *plan);
+
+/* Attention-received scores (ET_SCORE_ATTENTION) of equal-length frames: score_dev float32
+ * [n_frames, L], each row summing to 1, from the q and k thirds of qkv_dev bf16 [n_frames * L,
+ * 3 * n_heads * head_dim] (the layout et_attention reads).  scratch_dev: at least
+ * et_attention_scores_scratch_bytes(n_frames, L, n_heads) bytes.  head_dim a multiple of 8, <= 128. */
+size_t et_attention_scores_scratch_bytes(int32_t n_frames, int32_t L, int32_t n_heads);
+int et_attention_scores(const uint16_t *qkv_dev, int32_t n_frames, int32_t L, int32_t n_heads,
+                        int32_t head_dim, void *scratch_dev, float *score_dev, void *hip_stream);
 
 #ifdef __cplusplus
 }

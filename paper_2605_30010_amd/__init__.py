@@ -7,7 +7,7 @@ the binding's functions without a built library raises.
 from .binding import (  # noqa: F401
     EtError, load_library, library_path,
     et_keep_count, et_last_error, et_merge_workspace_bytes, et_merge_select,
-    et_merge_select_policy, et_encode_clip_policy, et_encode_clip_multi,
+    et_merge_select_policy, et_encode_clip_policy, et_encode_clip_multi, et_attention_scores,
     et_frame_similarity, et_segment_scan, et_segment_mean, et_topk_select, et_compact_tokens,
     et_layernorm, et_gemm_bf16, et_gemm_tune, et_attention,
     et_attention_uniform, et_attention_uniform_scratch_bytes,

@@ -11,9 +11,9 @@ _LIB_PATH = os.path.join(_PKG, "libearlytom.so")
 _lib = None
 
 ET_OK = 0
-ET_K_COUNT = 14
+ET_K_COUNT = 15
 KERNEL_KINDS = ["im2col", "gemm_patch", "layernorm", "gemm_qkv", "attention", "gemm_out",
-                "gemm_fc1", "gemm_fc2", "similarity", "scan", "merge", "select", "compact", "misc"]
+                "gemm_fc1", "gemm_fc2", "similarity", "scan", "merge", "select", "compact", "misc", "score"]
 
 
 class EtError(RuntimeError):
@@ -46,7 +46,8 @@ class _Output(C.Structure):
 
 class _Policy(C.Structure):
     _fields_ = [("merge_mode", C.c_int32), ("select_mode", C.c_int32), ("alpha", C.c_float),
-                ("tau_seg", C.c_float), ("tau_merge", C.c_float), ("ratio", C.c_float)]
+                ("tau_seg", C.c_float), ("tau_merge", C.c_float), ("ratio", C.c_float),
+                ("score_mode", C.c_int32)]
 
 
 class _PlanOut(C.Structure):
@@ -56,6 +57,7 @@ class _PlanOut(C.Structure):
 
 ET_MERGE_MEAN, ET_MERGE_ALG1 = 0, 1
 ET_SELECT_UNIFORM, ET_SELECT_DECOUPLED = 0, 1
+ET_SCORE_L2NORM, ET_SCORE_ATTENTION = 0, 1
 
 
 def library_path():
@@ -83,6 +85,8 @@ def load_library():
                                            C.POINTER(_Output), C.POINTER(_PlanOut)]),
         "et_encode_clip_multi": (C.c_int, [vp, vp, i32, C.POINTER(i32), i32, i32, C.POINTER(_Policy), vp, sz, vp,
                                           C.POINTER(_Output), C.POINTER(_PlanOut)]),
+        "et_attention_scores_scratch_bytes": (C.c_size_t, [i32, i32, i32]),
+        "et_attention_scores": (C.c_int, [vp, i32, i32, i32, i32, vp, vp, vp]),
         "et_frame_similarity": (C.c_int, [vp, i32, i32, i32, vp, vp, vp]),
         "et_segment_scan": (C.c_int, [vp, i32, f32, vp, vp, vp]),
         "et_segment_mean": (C.c_int, [vp, i32, i32, i32, vp, vp, vp, vp, vp]),
@@ -194,6 +198,7 @@ def _policy_struct(policy):
     p.select_mode = {"uniform": ET_SELECT_UNIFORM, "decoupled": ET_SELECT_DECOUPLED}[policy["select_mode"]]
     p.alpha, p.tau_seg = float(policy["alpha"]), float(policy["tau_seg"])
     p.tau_merge, p.ratio = float(policy["tau_merge"]), float(policy["ratio"])
+    p.score_mode = {"l2": ET_SCORE_L2NORM, "attention": ET_SCORE_ATTENTION}[policy.get("score_mode", "l2")]
     return p
 
 
@@ -265,6 +270,18 @@ def et_encode_clip_multi(handle, frames, merge_layers, select_layer, policy, L, 
                                     C.byref(pol), _ptr(workspace), workspace.numel(), _stream(stream),
                                     C.byref(o), C.byref(po)))
     return _trim_policy(bufs, o, plan_bufs, po, T)
+
+
+def et_attention_scores(qkv, n_frames, L, n_heads, head_dim, stream=None):
+    """Attention received per token: float32 [n_frames, L] from qkv bf16 [n_frames * L, 3 * n_heads * head_dim]."""
+    lib = load_library()
+    _dev(qkv, torch.bfloat16, "qkv")
+    scratch = torch.empty((max(lib.et_attention_scores_scratch_bytes(n_frames, L, n_heads), 1),), dtype=torch.uint8,
+                          device=qkv.device)
+    score = torch.empty((n_frames, L), dtype=torch.float32, device=qkv.device)
+    _check(lib.et_attention_scores(_ptr(qkv), n_frames, L, n_heads, head_dim, _ptr(scratch), _ptr(score),
+                                   _stream(stream)))
+    return score
 
 
 def et_frame_similarity(x, stream=None):

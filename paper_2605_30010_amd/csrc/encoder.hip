@@ -77,6 +77,8 @@ struct EncWs {
   uint16_t *x, *xn, *qkv, *att, *hid, *vt;
   int32_t *cu_full;
   void *merge;
+  void *score_ws;      // row statistics and per-head column sums of the attention-received scores
+  float *att_score;    // [T, L]
   size_t bytes;
 };
 
@@ -99,20 +101,26 @@ static EncWs carve_encoder(const et_encoder *e, void *ws, int T) {
   w.vt = static_cast<uint16_t *>(take(attention_uniform_workspace_bytes(T, e->L, e->cfg.n_heads, e->hd)));
   w.cu_full = static_cast<int32_t *>(take((size_t)(T + 1) * 4));
   w.merge = take(carve_merge(nullptr, T, e->L, e->D).bytes);
+  w.score_ws = take(attention_scores_workspace_bytes(T, e->L, e->cfg.n_heads));
+  w.att_score = static_cast<float *>(take(R * sizeof(float)));
   w.bytes = off;
   return w;
 }
 
 #define ET_TIMED(kind, call) ET_TIMED_P(&e->prof, kind, call)
 
+// with_scores: also leave the attention each token receives in this block in w.att_score (frames of
+// equal length only).
 static int run_block(et_encoder *e, const LayerDev &lw, const EncWs &w, int rows, const int32_t *cu,
-                     int n_frames, int max_len, bool ragged, hipStream_t s) {
+                     int n_frames, int max_len, bool ragged, hipStream_t s, bool with_scores = false) {
   const et_config &c = e->cfg;
   const int D = e->D;
   ET_TIMED(ET_K_LAYERNORM, launch_layernorm(w.x, lw.ln1_g, lw.ln1_b, c.ln_eps, rows, D, w.xn, s));
   GemmArgs g;
   g = GemmArgs{w.xn, D, lw.wqkv, lw.bqkv, nullptr, 0, 1, w.qkv, 3 * D, rows, 3 * D, D, EPI_BIAS};
   ET_TIMED(ET_K_GEMM_QKV, launch_gemm(g, s));
+  if (with_scores)
+    ET_TIMED(ET_K_SCORE, launch_attention_scores(w.qkv, n_frames, max_len, c.n_heads, e->hd, w.score_ws, w.att_score, s));
   if (ragged) {   // frames of different lengths (decoupled selection): the general kernel
     ET_TIMED(ET_K_ATTENTION, launch_attention(w.qkv, cu, n_frames, max_len, c.n_heads, e->hd, w.att, s));
   } else {        // every frame has max_len tokens
@@ -248,9 +256,18 @@ static int encode_impl(et_encoder *e, const float *frames_dev, int32_t T, int32_
   ET_REQUIRE(out->tokens_dev && out->kept_idx_dev && out->cu_tokens_dev && out->seg_start_dev,
              "an output buffer is NULL (tokens_dev, kept_idx_dev, cu_tokens_dev, seg_start_dev are required)");
   const bool compress = merge_layer >= 0;
+  bool by_attention = false;
   if (compress && policy) {
     int prc = check_policy(policy);
     if (prc) return prc;
+    by_attention = policy->score_mode == ET_SCORE_ATTENTION;
+    if (by_attention) {
+      ET_REQUIRE(merge_layer >= 1, "attention scores need an encoder block before the selection (select layer >= 1)");
+      for (int i = 0; i < n_merge; ++i)
+        ET_REQUIRE(merge_layers[i] != merge_layer,
+                   "attention scores need a block between the last merge and the selection (both at layer %d)",
+                   merge_layer);
+    }
   } else if (compress) {
     ET_REQUIRE(!isnan(sim_threshold), "sim_threshold is NaN");
     ET_REQUIRE(keep_ratio > 0.f && keep_ratio <= 1.f, "keep_ratio = %g outside (0, 1]", (double)keep_ratio);
@@ -297,7 +314,7 @@ static int encode_impl(et_encoder *e, const float *frames_dev, int32_t T, int32_
       const PlanStep step{merge_here ? 1 : 0, select_here ? 1 : 0, first_stage ? 1 : 0, T};
       int rc = enqueue_policy_stage(w.x, n_frames, L, D, *policy, step, mw, first_stage ? out->frame_sim_dev : nullptr,
                                     out->seg_start_dev, out->kept_idx_dev, out->cu_tokens_dev, w.x, info, s,
-                                    &e->prof);
+                                    &e->prof, (select_here && by_attention) ? w.att_score : nullptr);
       if (rc) return rc;
       if (!select_here)      // frames keep all L tokens: the merged frames become the residual stream
         ET_HIP(hipMemcpyAsync(w.x, mw.merged, (size_t)n_frames * L * D * 2, hipMemcpyDeviceToDevice, s));
@@ -348,7 +365,8 @@ static int encode_impl(et_encoder *e, const float *frames_dev, int32_t T, int32_
       e->prof.phase = 1;
     }
     if (i < c.n_layers) {
-      int rc = run_block(e, e->layers[i], w, rows, cu, n_frames, max_len, ragged, s);
+      int rc = run_block(e, e->layers[i], w, rows, cu, n_frames, max_len, ragged, s,
+                         by_attention && !selected && i == merge_layer - 1);
       if (rc) return rc;
     }
   }
@@ -423,8 +441,22 @@ int et_profile_read(et_encoder *e, double *ms, int64_t *launches, int32_t reset)
 const char *et_kernel_name(int32_t kind) {
   static const char *names[ET_K_COUNT] = {"im2col", "gemm_patch", "layernorm", "gemm_qkv", "attention",
                                           "gemm_out", "gemm_fc1", "gemm_fc2", "similarity", "scan",
-                                          "merge", "select", "compact", "misc"};
+                                          "merge", "select", "compact", "misc", "score"};
   return (kind >= 0 && kind < ET_K_COUNT) ? names[kind] : "?";
+}
+
+size_t et_attention_scores_scratch_bytes(int32_t n_frames, int32_t L, int32_t n_heads) {
+  if (n_frames < 0 || L < 0 || n_heads < 1) return 0;
+  return attention_scores_workspace_bytes(n_frames, L, n_heads);
+}
+
+int et_attention_scores(const uint16_t *qkv_dev, int32_t n_frames, int32_t L, int32_t n_heads, int32_t head_dim,
+                        void *scratch_dev, float *score_dev, void *hip_stream) {
+  ET_REQUIRE(qkv_dev && scratch_dev && score_dev, "a pointer argument is NULL");
+  ET_REQUIRE(n_frames >= 0 && L >= 1 && n_heads >= 1 && (int64_t)n_frames * L <= (1 << 24),
+             "n_frames = %d, L = %d, n_heads = %d out of range", n_frames, L, n_heads);
+  return launch_attention_scores(qkv_dev, n_frames, L, n_heads, head_dim, scratch_dev, score_dev,
+                                 static_cast<hipStream_t>(hip_stream));
 }
 
 int et_layernorm(const uint16_t *x_dev, const float *gamma_dev, const float *beta_dev, float eps,

@@ -91,6 +91,8 @@ int check_policy(const et_policy *p) {
   ET_REQUIRE(p->merge_mode == ET_MERGE_MEAN || p->merge_mode == ET_MERGE_ALG1, "merge_mode = %d unknown", p->merge_mode);
   ET_REQUIRE(p->select_mode == ET_SELECT_UNIFORM || p->select_mode == ET_SELECT_DECOUPLED,
              "select_mode = %d unknown", p->select_mode);
+  ET_REQUIRE(p->score_mode == ET_SCORE_L2NORM || p->score_mode == ET_SCORE_ATTENTION,
+             "score_mode = %d unknown", p->score_mode);
   ET_REQUIRE(p->alpha > 0.f && p->alpha <= 1.f, "alpha = %g outside (0, 1]", (double)p->alpha);
   ET_REQUIRE(!isnan(p->tau_seg) && !isnan(p->tau_merge), "a threshold is NaN");
   ET_REQUIRE(p->ratio > 0.f && p->ratio <= 1.f, "ratio = %g outside (0, 1]", (double)p->ratio);
@@ -99,7 +101,8 @@ int check_policy(const et_policy *p) {
 
 int enqueue_policy_stage(const uint16_t *x, int T, int L, int D, const et_policy &pol, const PlanStep &step,
                          const MergeWs &w, float *sim_out, int32_t *seg_start, int32_t *kept,
-                         int32_t *cu_tokens, uint16_t *packed, int32_t *info, hipStream_t s, Profiler *prof) {
+                         int32_t *cu_tokens, uint16_t *packed, int32_t *info, hipStream_t s, Profiler *prof,
+                         const float *score_override) {
   float *sim = sim_out ? sim_out : w.sim;
   const PolicyArgs pa{pol.merge_mode, pol.select_mode, pol.alpha, pol.tau_seg, pol.tau_merge, pol.ratio};
   const int k_uniform = et_keep_count(L, pol.ratio);
@@ -113,7 +116,8 @@ int enqueue_policy_stage(const uint16_t *x, int T, int L, int D, const et_policy
                                                  step.do_plan && pol.merge_mode == ET_MERGE_MEAN, w.merged,
                                                  w.score, s));
   if (step.do_counts) {
-    ET_TIMED_P(prof, ET_K_SELECT, launch_select_policy(w.score, T, info, w.frame_dyn, cu_tokens, L,
+    // (score_override: scores computed elsewhere, e.g. the attention received, instead of the L2 norms)
+    ET_TIMED_P(prof, ET_K_SELECT, launch_select_policy(score_override ? score_override : w.score, T, info, w.frame_dyn, cu_tokens, L,
                                                        pol.select_mode == ET_SELECT_UNIFORM, kept, s));
     ET_TIMED_P(prof, ET_K_COMPACT, launch_compact_ragged(w.merged, kept, T, info, cu_tokens, L, D, packed, s));
   }
@@ -225,6 +229,8 @@ int et_merge_select_policy(const uint16_t *x_dev, int32_t T, int32_t L, int32_t 
   if ((rc = check_merge_shape(T, L, D))) return rc;
   if ((rc = check_outputs(out))) return rc;
   if ((rc = check_policy(policy))) return rc;
+  ET_REQUIRE(policy->score_mode == ET_SCORE_L2NORM,
+             "score_mode = ET_SCORE_ATTENTION needs the encoder (et_encode_clip_multi): there is no attention here");
   ET_REQUIRE(workspace_dev != nullptr, "workspace_dev is NULL");
   size_t need = et_merge_workspace_bytes(T, L, D);
   if (workspace_bytes < need) {

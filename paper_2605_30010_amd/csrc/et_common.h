@@ -155,7 +155,7 @@ int check_policy(const et_policy *p);
 int enqueue_policy_stage(const uint16_t *x, int T, int L, int D, const et_policy &pol, const PlanStep &step,
                          const MergeWs &w, float *sim_out, int32_t *seg_start, int32_t *kept,
                          int32_t *cu_tokens, uint16_t *packed, int32_t *info, hipStream_t s,
-                         struct Profiler *prof);
+                         struct Profiler *prof, const float *score_override = nullptr);
 int copy_plan_out(const MergeWs &w, int N, et_plan_out *plan, hipStream_t s);
 MergeWs carve_merge(void *ws, int T, int L, int D);
 // Enqueues similarity -> scan -> segment mean (+score) -> top-k -> compaction; no host sync.
@@ -218,5 +218,10 @@ bool head_dim_supported(int hd);
 size_t attention_uniform_workspace_bytes(int n_frames, int len, int n_heads, int head_dim);
 int launch_attention_uniform(const uint16_t *qkv, int n_frames, int len, int n_heads, int head_dim,
                              uint16_t *vt_ws, uint16_t *out, hipStream_t s);
+
+// score_kernels.hip: attention received per token, equal-length frames
+size_t attention_scores_workspace_bytes(int n_frames, int L, int n_heads);
+int launch_attention_scores(const uint16_t *qkv, int n_frames, int L, int n_heads, int head_dim, void *stats_ws,
+                            float *score, hipStream_t s);
 
 }  // namespace et

@@ -212,7 +212,7 @@ def _gpu_hidden_at(shape, w, frames, merge_layers, layer, pol):
     enc = et.Encoder(replace(shape, n_layers=layer, has_final_ln=0), dict(w, layers=w["layers"][:layer]), T)
     fr = torch.from_numpy(frames).cuda()
     if merge_layers:
-        keep_all = dict(pol, select_mode="uniform", ratio=1.0)
+        keep_all = dict(pol, select_mode="uniform", ratio=1.0, score_mode="l2")
         r = enc.encode_multi(fr, merge_layers, layer, keep_all)
         assert r["n_tokens"] == r["n_frames_out"] * L
         assert np.array_equal(r["kept_idx"].cpu().numpy(), np.tile(np.arange(L), r["n_frames_out"]))
@@ -257,7 +257,8 @@ def _multi_check(shape, w, frames, merge_layers, select_layer, pol, tol=2e-2, st
     T = frames.shape[0]
     L = shape.tokens_per_frame
     x_at = {}
-    for layer in sorted(set(merge_layers) | {select_layer}):
+    by_attention = pol.get("score_mode", "l2") == "attention"
+    for layer in sorted(set(merge_layers) | {select_layer} | ({select_layer - 1} if by_attention else set())):
         x_at[layer] = _gpu_hidden_at(shape, w, frames, [m for m in merge_layers if m < layer], layer, pol)
     # decisions are promised away from ties only: look at every merge layer's similarities first (a
     # tie there may already have given the next stage a different number of frames)
@@ -285,10 +286,21 @@ def _multi_check(shape, w, frames, merge_layers, select_layer, pol, tol=2e-2, st
     assert got["cu_tokens"].tolist() == ref["cu_tokens"].tolist()
     kept = got["kept_idx"].cpu().numpy()
     same = np.array_equal(kept, ref["kept_idx"])
+    if by_attention:
+        # q and k pass through bfloat16 on the device; the oracle rounds at the same points, which leaves
+        # rare one-step differences that move a score by ~1e-5 relative: the device's choice must be a
+        # correct selection for the oracle's scores within that band
+        r_hat = O.rescaled_count(pol["ratio"], T, L, ref["n_frames_out"])
+        assert _selection_valid(kept, ref["cu_tokens"], ref["score"], ref["frame_dynamic"],
+                                pol["select_mode"] == "uniform", r_hat, L, 1e-4)
+        cu = ref["cu_tokens"]
+        swapped = sum(len(np.setdiff1d(kept[cu[n]:cu[n + 1]], ref["kept_idx"][cu[n]:cu[n + 1]])) for n in range(len(cu) - 1))
+        assert swapped <= 0.02 * len(kept) + 1            # and those band cases are few
     if strict_selection:
         assert same
-    elif not same:      # near-tied scores somewhere: few flips, and the tokens compared on the device's choice
+    elif not same and not by_attention:      # near-tied scores somewhere: few flips, and the tokens compared on the device's choice
         assert (kept != ref["kept_idx"]).mean() < 2e-3
+    if not same:
         cu = ref["cu_tokens"]
         ref = O.encode_clip_multi(shape, w, frames, merge_layers, select_layer, pol, x_at_layers=x_at,
                                   force_kept=[kept[cu[n]:cu[n + 1]] for n in range(len(cu) - 1)])
@@ -377,3 +389,108 @@ def test_siglip_32_frames_three_merge_layers_selection_after_encoder():
           % (rec["lengths"], counts, got["n_tokens"], 100.0 * got["n_tokens"] / (32 * 729), err))
     assert counts[0] <= 32 and counts[1] <= counts[0] and counts[2] <= counts[1]
     assert abs(got["n_tokens"] / (32 * 729) - 0.2) < 0.03
+
+
+# ---- attention-received scores (Sec. 3.3; reading stated in the header and the oracle) ---------------
+
+def _selection_valid(kept, cu, z, dyn, uniform, r_hat, L, delta):
+    """The kept set of every frame is a correct answer for the oracle's scores z up to a relative band
+    delta: top-k frames keep nothing below the k-th largest score and drop nothing above it; window frames
+    keep, per window, a token within delta of the window maximum."""
+    for n in range(len(cu) - 1):
+        K = kept[cu[n]:cu[n + 1]]
+        if uniform or dyn[n]:
+            k = len(K)
+            thr = np.sort(z[n])[::-1][k - 1]
+            rest = np.setdiff1d(np.arange(L), K)
+            if z[n][K].min() < thr * (1 - delta) or (len(rest) and z[n][rest].max() > thr * (1 + delta)):
+                return False
+        else:
+            w = L // r_hat
+            if len(K) != -(-L // w):
+                return False
+            for i, lo in enumerate(range(0, L, w)):
+                if not (lo <= K[i] < lo + w) or z[n][K[i]] < z[n][lo:lo + w].max() * (1 - delta):
+                    return False
+    return True
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("F,n,H,hd", [(3, 100, 4, 16), (2, 729, 16, 72), (1, 33, 2, 72), (2, 64, 1, 128)])
+def test_attention_scores_match_oracle(F, n, H, hd):
+    """LayerNorm -> q, k projection -> attention received, each step through its own entry point, against
+    the oracle rounding to bfloat16 at the same two points."""
+    rng = np.random.default_rng(F * 1000 + n)
+    D = H * hd
+    x_bits = f64_to_bits(rng.standard_normal((F * n, D)))
+    x = bf16_bits_to_f32(x_bits).astype(np.float64)
+    lw = dict(ln1_g=(1.0 + 0.1 * rng.standard_normal(D)).astype(np.float32),
+              ln1_b=(0.1 * rng.standard_normal(D)).astype(np.float32),
+              bqkv=(0.1 * rng.standard_normal(3 * D)).astype(np.float32))
+    w_bits = f64_to_bits(rng.standard_normal((3 * D, D)) * (2.0 / math.sqrt(D)))
+    lw["wqkv"] = bf16_bits_to_f32(w_bits)
+    xn = et.et_layernorm(bits_to_dev(x_bits), torch.from_numpy(lw["ln1_g"]).cuda(), torch.from_numpy(lw["ln1_b"]).cuda(),
+                         1e-6)
+    qkv = et.et_gemm_bf16(xn, bits_to_dev(w_bits), torch.from_numpy(lw["bqkv"]).cuda(), 0)
+    got = et.et_attention_scores(qkv, F, n, H, hd).cpu().numpy().astype(np.float64)
+    ref = O.attention_received(x.reshape(F, n, D), lw, H, 1e-6, storage_bf16=True)
+    assert np.allclose(got.sum(axis=1), 1.0, atol=1e-5)
+    assert np.max(np.abs(got - ref) / ref) < 2e-3          # a q or k element one bfloat16 step off moves a score by ~1e-4
+    assert rel_l2(got, ref) < 1e-4
+    # and the device's own q, k taken as given: agreement to float32 rounding
+    qk = bf16_bits_to_f32(dev_to_bits(qkv)).astype(np.float64).reshape(F, n, 3, H, hd)
+    s = np.einsum("fihd,fjhd->fhij", qk[:, :, 0], qk[:, :, 1]) / math.sqrt(hd)
+    want = O.softmax_rows(s).mean(axis=(1, 2))
+    assert np.max(np.abs(got - want) / want) < 2e-5
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("merge_layers,select_layer,pi", [([1], 3, 0), ([0, 1], 2, 2), ([], 4, 1), ([1, 2], 4, 4)])
+def test_tiny_encoder_selection_by_attention_scores(merge_layers, select_layer, pi):
+    rec = build_workload("c1_tiny")
+    w = rec["weights"]
+    pol = _f32_policy(dict(POLICIES[pi], tau_seg=0.9, tau_merge=0.9, score_mode="attention", score_storage_bf16=True))
+    for seed in range(40):
+        frames = make_clip(TINY, [7, 2, 6, 1], 400 + seed, base="uniform", sigma=0.02)
+        res = _multi_check(TINY, w, frames, merge_layers, select_layer, pol, strict_selection=False)
+        if res is not None:
+            break
+    else:
+        pytest.fail("no clip with clear margins in 40 seeds")
+    got, ref, err = res
+    assert np.allclose(ref["score"].sum(axis=1), 1.0)
+
+
+@pytest.mark.gpu
+def test_attention_score_mode_argument_errors():
+    rec = build_workload("c1_tiny")
+    frames = torch.from_numpy(rec["frames"]).cuda()
+    enc = et.Encoder(TINY, rec["weights"], frames.shape[0])
+    pol = dict(POLICIES[0], score_mode="attention")
+    with pytest.raises(et.EtError, match="block before"):
+        enc.encode_multi(frames, [], 0, pol)
+    with pytest.raises(et.EtError, match="between the last merge"):
+        enc.encode_multi(frames, [1, 2], 2, pol)
+    with pytest.raises(et.EtError, match="needs the encoder"):
+        et.et_merge_select_policy(torch.zeros((4, 16, 64), dtype=torch.bfloat16, device="cuda"), pol)
+    enc.close()
+
+
+@pytest.mark.gpu
+def test_siglip_32_frames_attention_scores_after_encoder():
+    """The paper's placement with attention scores: Stage I after blocks 6, 14, 20; Stage II on the encoder
+    output ranked by the attention received in the last block."""
+    rec = build_workload("c3_siglip_t32")
+    pol = _f32_policy(dict(merge_mode="alg1", select_mode="decoupled", alpha=0.9, tau_seg=0.8, tau_merge=0.8,
+                           ratio=0.2, score_mode="attention", score_storage_bf16=True))
+    for seed in range(4):
+        frames = make_clip(SIGLIP, rec["lengths"], 900 + seed, base=rec["base"], sigma=0.2)
+        res = _multi_check(SIGLIP, rec["weights"], frames, [6, 14, 20], 27, pol, strict_selection=False)
+        if res is not None:
+            break
+    else:
+        pytest.fail("no clip with clear margins")
+    got, ref, err = res
+    z = ref["score"]
+    print("attention scores, layers 6/14/20 + selection at 27: N = %d, tokens = %d, rel-L2 = %.4f, largest score x L = %.1f"
+          % (got["n_frames_out"], got["n_tokens"], err, z.max() * 729))
