@@ -1405,9 +1405,57 @@ int launch_gemm(const GemmArgs &g, hipStream_t s, int force_cfg) {
   const long t128 = (long)((g.M + 127) / 128) * ((g.n_store + 127) / 128);
   if (g.n_store % 8 != 0) return launch_gemm_id(g, s, t128 <= 256 ? 9 : 8);
   if (t256 > 256) {
-    const double cost256 = (double)((t256 + 255) / 256);
+    // The makespan of the big-tile kernel is whole rounds of 256 tiles, and a partly filled last
+    // tile row or column costs whole tiles.  Splitting that last tile row (a strip of < 256 rows)
+    // and / or tile column off into launches of their own, with small tiles, pays when it saves a
+    // round: costs below are in big-tile times (a round of 512 tiles of 128 x 128 about 0.6, of
+    // 64 x 128 about 0.35, plus 0.08 for the extra launch).
+    const int tm = (g.M + 255) / 256, tn = (g.n_store + 255) / 256;
+    auto strip_cost = [](long rows, long cols) {
+      const long s128 = ((rows + 127) / 128) * ((cols + 127) / 128), s64 = ((rows + 63) / 64) * ((cols + 127) / 128);
+      return 0.08 + (s128 >= 300 ? 0.6 * (double)((s128 + 511) / 512) : 0.35 * (double)((s64 + 511) / 512));
+    };
+    const bool rows_splittable = (g.epilogue != EPI_BIAS_RES || g.res_mod >= g.M) && g.M % 256 != 0 && tm > 1;
+    const bool cols_splittable = g.n_store % 256 != 0 && tn > 1;
+    int best_dr = 0, best_dc = 0;
+    double best = (double)((t256 + 255) / 256);
+    for (int dr = 0; dr <= (rows_splittable ? 1 : 0); ++dr)
+      for (int dc = 0; dc <= (cols_splittable ? 1 : 0); ++dc) {
+        if (!dr && !dc) continue;
+        const long rm = (long)(tm - dr) * 256 < g.M ? (long)(tm - dr) * 256 : g.M;
+        const long cm = (long)(tn - dc) * 256 < g.n_store ? (long)(tn - dc) * 256 : g.n_store;
+        double c = (double)(((long)(tm - dr) * (tn - dc) + 255) / 256);
+        if (dc) c += strip_cost(rm, g.n_store - cm);             // right strip next to the main block
+        if (dr) c += strip_cost(g.M - rm, g.n_store);            // bottom strip over the full width
+        if (c < best - 1e-9) { best = c; best_dr = dr; best_dc = dc; }
+      }
     const double cost128 = 0.6 * (double)((t128 + 511) / 512);
-    return launch_gemm_id(g, s, cost256 <= cost128 ? 20 : 22);
+    if (cost128 < best) return launch_gemm_id(g, s, 22);
+    if (!best_dr && !best_dc) return launch_gemm_id(g, s, 20);
+    const int rm = best_dr ? (tm - 1) * 256 : g.M, cm = best_dc ? (tn - 1) * 256 : g.n_store;
+    GemmArgs part = g;
+    part.M = rm;
+    part.n_store = cm;
+    int rc = launch_gemm_id(part, s, 20);
+    if (rc == ET_OK && best_dc) {
+      part = g;
+      part.M = rm;
+      part.W = g.W + (size_t)cm * g.K;
+      part.bias = g.bias + cm;
+      part.C = g.C + cm;
+      if (g.res) part.res = g.res + cm;
+      part.n_store = g.n_store - cm;
+      rc = launch_gemm(part, s);
+    }
+    if (rc == ET_OK && best_dr) {
+      part = g;
+      part.A = g.A + (size_t)rm * g.lda;
+      part.C = g.C + (size_t)rm * g.ldc;
+      if (g.res) part.res = g.res + (size_t)rm * g.ldr;
+      part.M = g.M - rm;
+      rc = launch_gemm(part, s);
+    }
+    return rc;
   }
   if (t256 >= 150) return launch_gemm_id(g, s, 20);
   if (t128 >= 300) return launch_gemm_id(g, s, 22);

@@ -14,7 +14,7 @@ import torch
 import paper_2605_30010_amd as et
 from et_inputs import bf16_bits_to_f32, f32_to_bf16_bits
 from oracle import earlytom_oracle as O
-from tests._util import bits_to_dev, dev_to_f64, rel_l2
+from tests._util import bits_to_dev, dev_to_bits, dev_to_f64, rel_l2
 
 pytestmark = pytest.mark.gpu
 
@@ -178,3 +178,26 @@ def test_gemm_persistent_configs_walk_several_tiles_per_workgroup(cfg):
         got = dev_to_f64(c)
         assert np.max(np.abs(got - ref) - 2 ** -8 * np.abs(ref)) < 5e-4, epi
         assert rel_l2(got, ref) < 4e-3, epi
+
+
+@pytest.mark.parametrize("N,epi", [(3456, 0), (4304, 1), (4304, 2), (1152, 2)])
+def test_gemm_library_choice_at_encoder_row_count(N, epi):
+    """32 x 729 rows with the library's own tiling, which splits a nearly empty last tile row or a partly
+    filled last tile column off into launches of their own: every output element against the oracle."""
+    rng = np.random.default_rng(N + epi)
+    M, K = 23328, 128
+    a_bits, a = _bf(rng, (M, K))
+    w_bits, w = _bf(rng, (N, K), scale=0.1)
+    bias = (0.1 * rng.standard_normal(N)).astype(np.float32)
+    ref = a.astype(np.float32) @ w.astype(np.float32).T + bias            # exact products, float32 sums of 128 terms
+    res = None
+    if epi == 1:
+        ref = O.gelu_tanh(ref.astype(np.float64))
+    if epi == 2:
+        r_bits, r = _bf(rng, (M, N))
+        ref = ref + r.astype(np.float32)
+        res = bits_to_dev(r_bits)
+    c = et.et_gemm_bf16(bits_to_dev(a_bits), bits_to_dev(w_bits), torch.from_numpy(bias).cuda(), epi, residual=res)
+    got = bf16_bits_to_f32(dev_to_bits(c))
+    assert np.max(np.abs(got - ref) - 2 ** -8 * np.abs(ref)) < 5e-4
+    assert rel_l2(got.astype(np.float64), ref.astype(np.float64)) < 4e-3
