@@ -97,6 +97,8 @@ def main():
     ap.add_argument("--cpu-frames", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile-pass", action="store_true")
+    ap.add_argument("--no-paper-policy", action="store_true",
+                    help="skip the extra timing of the paper's own configuration (reported beside the headline)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 256 MiB device copy first (reference for scaling "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -181,6 +183,26 @@ def main():
                                   "gbs": round(stage_bytes / (stage_ms / stage_cnt * 1e-3) / 1e9, 1)}
         kernels["merge_stage"]["hbm_frac"] = round(kernels["merge_stage"]["gbs"] / PEAK_HBM_GBS, 4)
 
+    # Extra, not the headline: the paper's own layout (Table 8 / Alg. 1-2) on the same clip - Stage I after
+    # blocks 6, 14, 20 with EMA segmentation and the weighted middle-pair merge, Stage II once on the encoder
+    # output (decoupled top-k / local windows, overall retention 20 %, attention-received scores).
+    paper = None
+    if not args.no_paper_policy and shape.n_layers >= 21:
+        pol = dict(merge_mode="alg1", select_mode="decoupled", alpha=0.9, tau_seg=0.8, tau_merge=0.8, ratio=0.2,
+                   score_mode="attention")
+        layers, sel = [6, 14, 20], shape.n_layers
+        for _ in range(max(args.warmup, 1)):
+            po = enc.encode_multi(frames, layers, sel, pol, stream=stream)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            po = enc.encode_multi(frames, layers, sel, pol, stream=stream)
+        torch.cuda.synchronize()
+        pt = time.perf_counter() - t1
+        paper = {"merge_layers": layers, "select_layer": sel, "policy": pol, "ms_per_step": round(1e3 * pt / args.steps, 3),
+                 "frames_per_s": round(T * args.steps / pt, 2), "n_frames_out": po["n_frames_out"],
+                 "n_tokens_out": po["n_tokens"], "retention": round(po["n_tokens"] / (T * shape.tokens_per_frame), 4)}
+
     fl = flops_tables(shape, T, N, k, m)
     total_flops = fl[("gemm_patch", 0)]
     for kind in ("gemm_qkv", "gemm_out", "gemm_fc1", "gemm_fc2", "attention"):
@@ -201,6 +223,7 @@ def main():
         "effective_tflops": round(total_flops / (ms_per_step * 1e-3) / 1e12, 1),
         "roofline": roofline,
         "kernels": kernels,
+        "paper_policy": paper,
     }
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(rec, min(args.cpu_frames, T))

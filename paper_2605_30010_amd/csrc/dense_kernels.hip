@@ -1418,7 +1418,8 @@ int launch_gemm(const GemmArgs &g, hipStream_t s, int force_cfg) {
     const bool rows_splittable = (g.epilogue != EPI_BIAS_RES || g.res_mod >= g.M) && g.M % 256 != 0 && tm > 1;
     const bool cols_splittable = g.n_store % 256 != 0 && tn > 1;
     int best_dr = 0, best_dc = 0;
-    double best = (double)((t256 + 255) / 256);
+    const double whole = (double)((t256 + 255) / 256);
+    double best = whole - 0.5;                                   // a split has to save at least half a round
     for (int dr = 0; dr <= (rows_splittable ? 1 : 0); ++dr)
       for (int dc = 0; dc <= (cols_splittable ? 1 : 0); ++dc) {
         if (!dr && !dc) continue;
@@ -1430,7 +1431,7 @@ int launch_gemm(const GemmArgs &g, hipStream_t s, int force_cfg) {
         if (c < best - 1e-9) { best = c; best_dr = dr; best_dc = dc; }
       }
     const double cost128 = 0.6 * (double)((t128 + 511) / 512);
-    if (cost128 < best) return launch_gemm_id(g, s, 22);
+    if (cost128 < ((best_dr || best_dc) ? best : whole)) return launch_gemm_id(g, s, 22);
     if (!best_dr && !best_dc) return launch_gemm_id(g, s, 20);
     const int rm = best_dr ? (tm - 1) * 256 : g.M, cm = best_dc ? (tn - 1) * 256 : g.n_store;
     GemmArgs part = g;
