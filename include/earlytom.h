@@ -236,9 +236,11 @@ int et_gemm_bf16(const uint16_t *a_dev, const uint16_t *w_dev, const float *bias
 /* Times `iters` back-to-back launches of the GEMM above on library-allocated operands of the
  * given logical shape with HIP events; *avg_ms (HOST) receives the mean milliseconds per
  * launch.  tile_config selects one of the library's workgroup tilings: 0-5 register-staged
- * kernels, 6-19 direct-to-LDS kernels (one tile per workgroup), 20-32 persistent k-tile stream
- * kernels (20: 256x256x64 with 8 wavefronts, 22: 128x128x64, 26: 64x128x64; the full table is in
- * launch_gemm_id); -1: the library's own choice.  For tuning sweeps; allocates, frees, synchronises. */
+ * kernels, 6-19 direct-to-LDS kernels (one tile per workgroup), 20-35 persistent k-tile stream
+ * kernels (20: 256x256x64 with 8 wavefronts, 22: 128x128x64, 26: 64x128x64; 33-35: 256x256 with 4
+ * wavefronts of 128x128 whose accumulators sit in the accumulation registers; the full table is in
+ * launch_gemm_id); -1: the library's own choice, which may also split a thin last tile row or
+ * column off into a launch of its own.  For tuning sweeps; allocates, frees, synchronises. */
 int et_gemm_tune(int32_t M, int32_t N, int32_t K, int32_t epilogue, int32_t tile_config, int32_t iters,
                  float *avg_ms, void *hip_stream);
 

@@ -1409,11 +1409,12 @@ int launch_gemm(const GemmArgs &g, hipStream_t s, int force_cfg) {
     // tile row or column costs whole tiles.  Splitting that last tile row (a strip of < 256 rows)
     // and / or tile column off into launches of their own, with small tiles, pays when it saves a
     // round: costs below are in big-tile times (a round of 512 tiles of 128 x 128 about 0.6, of
-    // 64 x 128 about 0.35, plus 0.08 for the extra launch).
+    // 64 x 128 about 0.55, up to 256 of them 0.3, plus 0.08 for the extra launch).
     const int tm = (g.M + 255) / 256, tn = (g.n_store + 255) / 256;
     auto strip_cost = [](long rows, long cols) {
       const long s128 = ((rows + 127) / 128) * ((cols + 127) / 128), s64 = ((rows + 63) / 64) * ((cols + 127) / 128);
-      return 0.08 + (s128 >= 300 ? 0.6 * (double)((s128 + 511) / 512) : 0.35 * (double)((s64 + 511) / 512));
+      if (s128 >= 300) return 0.08 + 0.6 * (double)((s128 + 511) / 512);
+      return 0.08 + (s64 <= 256 ? 0.3 : 0.55 * (double)((s64 + 511) / 512));   // alone on a compute unit, or two sharing it
     };
     const bool rows_splittable = (g.epilogue != EPI_BIAS_RES || g.res_mod >= g.M) && g.M % 256 != 0 && tm > 1;
     const bool cols_splittable = g.n_store % 256 != 0 && tn > 1;
