@@ -494,3 +494,30 @@ def test_siglip_32_frames_attention_scores_after_encoder():
     z = ref["score"]
     print("attention scores, layers 6/14/20 + selection at 27: N = %d, tokens = %d, rel-L2 = %.4f, largest score x L = %.1f"
           % (got["n_frames_out"], got["n_tokens"], err, z.max() * 729))
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("score_mode", ["l2", "attention"])
+def test_multi_layer_degenerate_clips(score_mode):
+    """One frame; identical frames that collapse to a single frame at the first merge layer and stay one
+    frame at the later ones; every frame its own scene (nothing merges at any layer)."""
+    rec = build_workload("c1_tiny")
+    w = rec["weights"]
+    L = TINY.tokens_per_frame
+    base = dict(alpha=0.9, tau_seg=0.9, tau_merge=0.9, ratio=0.25, score_mode=score_mode, score_storage_bf16=True)
+    one = make_clip(TINY, [1], 5, base="uniform", sigma=0.02)
+    same = np.repeat(one, 6, axis=0)
+    scenes = make_clip(TINY, [1] * 5, 6, base="smooth", sigma=0.02)
+    enc = et.Encoder(TINY, w, 6)
+    for frames, merge_mode, want_n in ((one, "alg1", 1), (same, "mean", 1), (same, "alg1", 6), (scenes, "alg1", 5)):
+        pol = _f32_policy(dict(base, merge_mode=merge_mode, select_mode="decoupled"))
+        got = enc.encode_multi(torch.from_numpy(frames).cuda(), [1, 2], 3, pol)
+        got = {k: (v.clone() if isinstance(v, torch.Tensor) else v) for k, v in got.items()}
+        T = frames.shape[0]
+        assert got["n_frames_out"] == want_n
+        first, count = got["frame_first"].cpu().numpy(), got["frame_count"].cpu().numpy()
+        assert first[0] == 0 and first[-1] + count[-1] == T and np.array_equal(first[1:], (first + count)[:-1])
+        res = _multi_check(TINY, w, frames, [1, 2], 3, pol, strict_selection=False)
+        if res is not None:                         # (identical frames sit exactly on Alg. 1's ties: plan checked above)
+            assert res[0]["n_frames_out"] == want_n
+    enc.close()
