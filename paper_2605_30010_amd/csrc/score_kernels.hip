@@ -100,17 +100,24 @@ __global__ __launch_bounds__(kScoreWaves * 64) void attn_colsum_kernel(
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r32 = lane & 31, grp = lane >> 5;
   const int h = blockIdx.y, f = blockIdx.z;
-  const int k0 = (blockIdx.x * kScoreWaves + wave) * 32;
-  if (k0 >= L) return;                                         // wave-uniform
+  const int k0 = (blockIdx.x * kScoreWaves + wave) * 32;       // (a wavefront past the last key computes on clamped rows and stores nothing)
   const size_t row_stride = (size_t)3 * D;
   const uint16_t *head = qkv + (size_t)f * L * row_stride + (size_t)h * head_dim;
   const float2 *st = stats + ((size_t)f * n_heads + h) * L;
+  // the four wavefronts see the same 32 queries: their (m, 1/l) pairs go through LDS once per tile
+  // instead of 16 scattered loads per lane; two buffers, so one barrier per tile is enough
+  __shared__ float2 qstat[2][32];
   const int kj = k0 + r32 < L ? k0 + r32 : L - 1;
   u32x4 kf[KSTEPS];
 #pragma unroll
   for (int ks = 0; ks < KSTEPS; ++ks) kf[ks] = load_piece(head + (size_t)kj * row_stride + D, 2 * ks + grp, head_dim);
   float col = 0.f;
-  for (int q0 = 0; q0 < L; q0 += 32) {
+  int buf = 0;
+  for (int q0 = 0; q0 < L; q0 += 32, buf ^= 1) {
+    if (threadIdx.x < 32) {
+      const int q = q0 + (int)threadIdx.x;
+      qstat[buf][threadIdx.x] = q < L ? st[q] : make_float2(INFINITY, 0.f);  // rows past L: exp2(-inf) * 0 = 0
+    }
     const int qi = q0 + r32 < L ? q0 + r32 : L - 1;
     const uint16_t *qrow = head + (size_t)qi * row_stride;
     f32x16 acc;
@@ -118,13 +125,11 @@ __global__ __launch_bounds__(kScoreWaves * 64) void attn_colsum_kernel(
     for (int i = 0; i < 16; ++i) acc[i] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks) acc = mfma_bf16(load_piece(qrow, 2 * ks + grp, head_dim), kf[ks], acc);
+    __syncthreads();
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      const int q = q0 + (i / 4) * 8 + 4 * grp + (i % 4);
-      if (q < L) {
-        const float2 ml = st[q];
-        col += __builtin_amdgcn_exp2f(acc[i] * scale_log2 - ml.x) * ml.y;
-      }
+      const float2 ml = qstat[buf][(i / 4) * 8 + 4 * grp + (i % 4)];
+      col += __builtin_amdgcn_exp2f(acc[i] * scale_log2 - ml.x) * ml.y;
     }
   }
   col += __shfl_xor(col, 32);
