@@ -1394,74 +1394,74 @@ int launch_gemm(const GemmArgs &g, hipStream_t s, int force_cfg) {
     return ET_ERR_INVALID_ARG;
   }
   if (force_cfg >= 0) return launch_gemm_id(g, s, force_cfg);
-  // Tile choice (persistent stream kernels; measured on MI355X at the encoder's shapes).
+  // Tile choice among the persistent stream kernels, by a cost model in units of one round of
+  // 256 x 256 tiles (one per compute unit; all costs scale with K alike).  Measured on MI355X at
+  // the encoder's shapes: a round of 128 x 128 tiles (two workgroups per compute unit, 512 slots)
+  // costs 0.6 of it, 0.52 when at most 256 tiles leave every workgroup alone on its unit, 0.57 per
+  // round when there are several; 64 x 128 tiles 0.5 / 0.3 / 0.4.  The makespan is whole rounds:
+  // a workgroup with one tile more than the others finishes a tile time later.
   //  - n_store not a multiple of 8: the 4-column epilogue of the non-persistent kernels.
-  //  - at least ~150 tiles of 256 x 256: one workgroup of 8 wavefronts per compute unit.  Above 256
-  //    tiles the makespan is whole rounds of tiles; 128 x 128 tiles (two workgroups per compute
-  //    unit, each at about 0.6 of a big tile's time) win only when they save a round.
-  //  - fewer: 128 x 128 tiles if that gives ~300 workgroups, else 64 x 128 (k-tile 64, so the
-  //    latency-bound barrier-per-k-tile loop has few trips) to cover the compute units.
+  //  - big tiles: a partly filled last tile row or column costs whole tiles, so it may be split
+  //    off into a launch of its own with small tiles (only if that saves at least half a round).
   const long t256 = (long)((g.M + 255) / 256) * ((g.n_store + 255) / 256);
   const long t128 = (long)((g.M + 127) / 128) * ((g.n_store + 127) / 128);
   if (g.n_store % 8 != 0) return launch_gemm_id(g, s, t128 <= 256 ? 9 : 8);
+  auto cost_small = [](long rows, long cols, int *cfg) {
+    const long s128 = ((rows + 127) / 128) * ((cols + 127) / 128), s64 = ((rows + 63) / 64) * ((cols + 127) / 128);
+    const long r128 = (s128 + 511) / 512, r64 = (s64 + 511) / 512;
+    const double c128 = r128 > 1 ? 0.57 * (double)r128 : (s128 <= 256 ? 0.52 : 0.6);
+    const double c64 = r64 > 1 ? 0.4 * (double)r64 : (s64 <= 256 ? 0.3 : 0.5);
+    if (cfg) *cfg = c128 <= c64 ? 22 : 26;
+    return c128 <= c64 ? c128 : c64;
+  };
+  const int tm = (g.M + 255) / 256, tn = (g.n_store + 255) / 256;
+  const double whole = (double)((t256 + 255) / 256);
+  int best_dr = 0, best_dc = 0;
+  double best = whole;
   if (t256 > 256) {
-    // The makespan of the big-tile kernel is whole rounds of 256 tiles, and a partly filled last
-    // tile row or column costs whole tiles.  Splitting that last tile row (a strip of < 256 rows)
-    // and / or tile column off into launches of their own, with small tiles, pays when it saves a
-    // round: costs below are in big-tile times (a round of 512 tiles of 128 x 128 about 0.6, of
-    // 64 x 128 about 0.55, up to 256 of them 0.3, plus 0.08 for the extra launch).
-    const int tm = (g.M + 255) / 256, tn = (g.n_store + 255) / 256;
-    auto strip_cost = [](long rows, long cols) {
-      const long s128 = ((rows + 127) / 128) * ((cols + 127) / 128), s64 = ((rows + 63) / 64) * ((cols + 127) / 128);
-      if (s128 >= 300) return 0.08 + 0.6 * (double)((s128 + 511) / 512);
-      return 0.08 + (s64 <= 256 ? 0.3 : 0.55 * (double)((s64 + 511) / 512));   // alone on a compute unit, or two sharing it
-    };
     const bool rows_splittable = (g.epilogue != EPI_BIAS_RES || g.res_mod >= g.M) && g.M % 256 != 0 && tm > 1;
     const bool cols_splittable = g.n_store % 256 != 0 && tn > 1;
-    int best_dr = 0, best_dc = 0;
-    const double whole = (double)((t256 + 255) / 256);
-    double best = whole - 0.5;                                   // a split has to save at least half a round
+    double split_best = whole - 0.5;
     for (int dr = 0; dr <= (rows_splittable ? 1 : 0); ++dr)
       for (int dc = 0; dc <= (cols_splittable ? 1 : 0); ++dc) {
         if (!dr && !dc) continue;
         const long rm = (long)(tm - dr) * 256 < g.M ? (long)(tm - dr) * 256 : g.M;
         const long cm = (long)(tn - dc) * 256 < g.n_store ? (long)(tn - dc) * 256 : g.n_store;
         double c = (double)(((long)(tm - dr) * (tn - dc) + 255) / 256);
-        if (dc) c += strip_cost(rm, g.n_store - cm);             // right strip next to the main block
-        if (dr) c += strip_cost(g.M - rm, g.n_store);            // bottom strip over the full width
-        if (c < best - 1e-9) { best = c; best_dr = dr; best_dc = dc; }
+        if (dc) c += 0.08 + cost_small(rm, g.n_store - cm, nullptr);     // right strip next to the main block
+        if (dr) c += 0.08 + cost_small(g.M - rm, g.n_store, nullptr);    // bottom strip over the full width
+        if (c < split_best - 1e-9) { split_best = c; best_dr = dr; best_dc = dc; }
       }
-    const double cost128 = 0.6 * (double)((t128 + 511) / 512);
-    if (cost128 < ((best_dr || best_dc) ? best : whole)) return launch_gemm_id(g, s, 22);
-    if (!best_dr && !best_dc) return launch_gemm_id(g, s, 20);
-    const int rm = best_dr ? (tm - 1) * 256 : g.M, cm = best_dc ? (tn - 1) * 256 : g.n_store;
-    GemmArgs part = g;
-    part.M = rm;
-    part.n_store = cm;
-    int rc = launch_gemm_id(part, s, 20);
-    if (rc == ET_OK && best_dc) {
-      part = g;
-      part.M = rm;
-      part.W = g.W + (size_t)cm * g.K;
-      part.bias = g.bias + cm;
-      part.C = g.C + cm;
-      if (g.res) part.res = g.res + cm;
-      part.n_store = g.n_store - cm;
-      rc = launch_gemm(part, s);
-    }
-    if (rc == ET_OK && best_dr) {
-      part = g;
-      part.A = g.A + (size_t)rm * g.lda;
-      part.C = g.C + (size_t)rm * g.ldc;
-      if (g.res) part.res = g.res + (size_t)rm * g.ldr;
-      part.M = g.M - rm;
-      rc = launch_gemm(part, s);
-    }
-    return rc;
+    if (best_dr || best_dc) best = split_best;
   }
-  if (t256 >= 150) return launch_gemm_id(g, s, 20);
-  if (t128 >= 300) return launch_gemm_id(g, s, 22);
-  return launch_gemm_id(g, s, 26);
+  int small_cfg = 26;
+  const double small = cost_small(g.M, g.n_store, &small_cfg);
+  if (small < best) return launch_gemm_id(g, s, small_cfg);
+  if (!best_dr && !best_dc) return launch_gemm_id(g, s, 20);
+  const int rm = best_dr ? (tm - 1) * 256 : g.M, cm = best_dc ? (tn - 1) * 256 : g.n_store;
+  GemmArgs part = g;
+  part.M = rm;
+  part.n_store = cm;
+  int rc = launch_gemm_id(part, s, 20);
+  if (rc == ET_OK && best_dc) {
+    part = g;
+    part.M = rm;
+    part.W = g.W + (size_t)cm * g.K;
+    part.bias = g.bias + cm;
+    part.C = g.C + cm;
+    if (g.res) part.res = g.res + cm;
+    part.n_store = g.n_store - cm;
+    rc = launch_gemm(part, s);
+  }
+  if (rc == ET_OK && best_dr) {
+    part = g;
+    part.A = g.A + (size_t)rm * g.lda;
+    part.C = g.C + (size_t)rm * g.ldc;
+    if (g.res) part.res = g.res + (size_t)rm * g.ldr;
+    part.M = g.M - rm;
+    rc = launch_gemm(part, s);
+  }
+  return rc;
 }
 
 bool head_dim_supported(int hd) {
