@@ -414,7 +414,8 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_dma_kernel(G
   }
   const int tile_m = bid / tiles_n, tile_n = bid % tiles_n;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS destinations of the loads stay scalar
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
   const int r32 = lane & 31, grp = lane >> 5;
 
@@ -548,7 +549,8 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
   const int n_tiles = tiles_m * tiles_n;
   const int G = gridDim.x;
   const int n_my = (n_tiles - (int)blockIdx.x + G - 1) / G;       // >= 1: the grid never exceeds n_tiles
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS destinations of the loads stay scalar
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
   const int r32 = lane & 31, grp = lane >> 5;
   const int lrow = lane / CPR, lslot = lane % CPR;
