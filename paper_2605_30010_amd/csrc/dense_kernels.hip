@@ -573,22 +573,27 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
     n0 = (cb * 4 + r2 % wcb) * BN;
   };
 
-  const uint16_t *a_src[A_BLK];
-  const uint16_t *w_src[W_BLK];
+  // Source of this lane for each of the wavefront's loads: a wave-uniform tile origin (scalar
+  // registers) plus a 32-bit per-lane byte offset, so that each load is issued with a scalar base
+  // and needs no vector address arithmetic.  Only the activation offsets depend on the tile (rows
+  // past M are clamped to the last row).
+  const char *a_base = nullptr, *w_base = nullptr;
+  uint32_t a_off[A_BLK], w_off[W_BLK];
+#pragma unroll
+  for (int i = 0; i < W_BLK; ++i) {
+    const int row = (wave * W_BLK + i) * RPB + lrow;
+    w_off[i] = (uint32_t)(((size_t)row * g.K + ((lslot ^ ((row >> SWZ) & (CPR - 1))) * 8)) * 2);
+  }
   auto set_load_tile = [&](int j) {
     int m0, n0;
     tile_of(j, m0, n0);
+    a_base = reinterpret_cast<const char *>(g.A + (size_t)m0 * g.lda);
+    w_base = reinterpret_cast<const char *>(g.W + (size_t)n0 * g.K);
 #pragma unroll
     for (int i = 0; i < A_BLK; ++i) {
       const int row = (wave * A_BLK + i) * RPB + lrow;
-      int m = m0 + row;
-      if (m >= g.M) m = g.M - 1;
-      a_src[i] = g.A + (size_t)m * g.lda + ((lslot ^ ((row >> SWZ) & (CPR - 1))) * 8);
-    }
-#pragma unroll
-    for (int i = 0; i < W_BLK; ++i) {
-      const int row = (wave * W_BLK + i) * RPB + lrow;
-      w_src[i] = g.W + (size_t)(n0 + row) * g.K + ((lslot ^ ((row >> SWZ) & (CPR - 1))) * 8);
+      const int rc = (m0 + row < g.M) ? row : g.M - 1 - m0;       // m0 < M always
+      a_off[i] = (uint32_t)(((size_t)rc * g.lda + ((lslot ^ ((row >> SWZ) & (CPR - 1))) * 8)) * 2);
     }
   };
   const int kt_n = g.K / BK;
@@ -596,11 +601,15 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
   auto issue_one = [&](int stage, int i) {          // i-th 1 KiB load of this wavefront for the next k-tile
     uint16_t *as = lds + stage * STAGE_ELEMS;
     uint16_t *ws = as + BM * BK;
-    const int ko = load_kt * BK;
+    const size_t ko = (size_t)load_kt * (BK * 2);
+    // (the empty asm keeps the offset a 32-bit register at this point, so that the load is selected
+    // with the scalar base + 32-bit offset form instead of a widened 64-bit vector address)
     if (i < A_BLK) {
-      ET_LDS_DMA16(a_src[i] + ko, as + (wave * A_BLK + i) * 512);
+      asm volatile("" : "+v"(a_off[i]));
+      ET_LDS_DMA16(a_base + ko + a_off[i], as + (wave * A_BLK + i) * 512);
     } else {
-      ET_LDS_DMA16(w_src[i - A_BLK] + ko, ws + (wave * W_BLK + (i - A_BLK)) * 512);
+      asm volatile("" : "+v"(w_off[i - A_BLK]));
+      ET_LDS_DMA16(w_base + ko + w_off[i - A_BLK], ws + (wave * W_BLK + (i - A_BLK)) * 512);
     }
   };
   auto issue_advance = [&]() {
