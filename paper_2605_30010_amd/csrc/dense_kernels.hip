@@ -383,6 +383,10 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(GemmArgs g,
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gptr),   \
                                    (__attribute__((address_space(3))) void *)(lptr), 16, 0, 0)
 
+#define ET_LDS_DMA16_OFF(gptr, lptr, imm)                                                    \
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gptr),   \
+                                   (__attribute__((address_space(3))) void *)(lptr), 16, (imm), 0)
+
 // Waits until at most N of this wavefront's vector-memory operations are outstanding.
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
@@ -577,23 +581,30 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
   // registers) plus a 32-bit per-lane byte offset, so that each load is issued with a scalar base
   // and needs no vector address arithmetic.  Only the activation offsets depend on the tile (rows
   // past M are clamped to the last row).
+  // The instruction's immediate offset moves the global AND the LDS address, and the LDS base sits
+  // in M0, which cannot be rewritten before the previous load has read it: loads are therefore
+  // issued in groups of four that share one M0 value and step through LDS by immediates of 1 KiB,
+  // with the lane offsets lowered by the same amount (kOffBias keeps them non-negative; the tile
+  // origins are lowered by it).
+  constexpr uint32_t kOffBias = 4096;
   const char *a_base = nullptr, *w_base = nullptr;
   uint32_t a_off[A_BLK], w_off[W_BLK];
 #pragma unroll
   for (int i = 0; i < W_BLK; ++i) {
     const int row = (wave * W_BLK + i) * RPB + lrow;
-    w_off[i] = (uint32_t)(((size_t)row * g.K + ((lslot ^ ((row >> SWZ) & (CPR - 1))) * 8)) * 2);
+    w_off[i] = (uint32_t)(((size_t)row * g.K + ((lslot ^ ((row >> SWZ) & (CPR - 1))) * 8)) * 2) + kOffBias - (i % 4) * 1024;
   }
   auto set_load_tile = [&](int j) {
     int m0, n0;
     tile_of(j, m0, n0);
-    a_base = reinterpret_cast<const char *>(g.A + (size_t)m0 * g.lda);
-    w_base = reinterpret_cast<const char *>(g.W + (size_t)n0 * g.K);
+    a_base = reinterpret_cast<const char *>(g.A + (size_t)m0 * g.lda) - kOffBias;
+    w_base = reinterpret_cast<const char *>(g.W + (size_t)n0 * g.K) - kOffBias;
+    asm volatile("" : "+s"(a_base), "+s"(w_base));      // (keeps the bias out of the loads' address expressions)
 #pragma unroll
     for (int i = 0; i < A_BLK; ++i) {
       const int row = (wave * A_BLK + i) * RPB + lrow;
       const int rc = (m0 + row < g.M) ? row : g.M - 1 - m0;       // m0 < M always
-      a_off[i] = (uint32_t)(((size_t)rc * g.lda + ((lslot ^ ((row >> SWZ) & (CPR - 1))) * 8)) * 2);
+      a_off[i] = (uint32_t)(((size_t)rc * g.lda + ((lslot ^ ((row >> SWZ) & (CPR - 1))) * 8)) * 2) + kOffBias - (i % 4) * 1024;
     }
   };
   const int kt_n = g.K / BK;
@@ -604,12 +615,23 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
     const size_t ko = (size_t)load_kt * (BK * 2);
     // (the empty asm keeps the offset a 32-bit register at this point, so that the load is selected
     // with the scalar base + 32-bit offset form instead of a widened 64-bit vector address)
+    const char *src;
+    uint16_t *dst;
     if (i < A_BLK) {
       asm volatile("" : "+v"(a_off[i]));
-      ET_LDS_DMA16(a_base + ko + a_off[i], as + (wave * A_BLK + i) * 512);
+      src = a_base + ko + a_off[i];
+      dst = as + (wave * A_BLK + (i & ~3)) * 512;
     } else {
-      asm volatile("" : "+v"(w_off[i - A_BLK]));
-      ET_LDS_DMA16(w_base + ko + w_off[i - A_BLK], ws + (wave * W_BLK + (i - A_BLK)) * 512);
+      const int j = i - A_BLK;
+      asm volatile("" : "+v"(w_off[j]));
+      src = w_base + ko + w_off[j];
+      dst = ws + (wave * W_BLK + (j & ~3)) * 512;
+    }
+    switch ((i < A_BLK ? i : i - A_BLK) & 3) {       // the immediate has to be a literal
+      case 0: ET_LDS_DMA16_OFF(src, dst, 0); break;
+      case 1: ET_LDS_DMA16_OFF(src, dst, 1024); break;
+      case 2: ET_LDS_DMA16_OFF(src, dst, 2048); break;
+      default: ET_LDS_DMA16_OFF(src, dst, 3072); break;
     }
   };
   auto issue_advance = [&]() {
