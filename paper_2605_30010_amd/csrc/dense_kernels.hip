@@ -542,12 +542,20 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
   constexpr int CPR = BK / 8;
   constexpr int RPB = 64 / CPR;
   constexpr int SWZ = (BK == 64) ? 1 : 2;
-  constexpr int A_BLK = BM / RPB / NW, W_BLK = BN / RPB / NW;
+  // With two wavefronts per SIMD (8 wavefronts, one workgroup per compute unit) only the upper half
+  // of the wavefronts issues the direct loads.  The address unit takes 64 bytes per clock, so the
+  // 64 KiB of a k-tile keep it busy for ~1000 cycles and block whoever issues them; the wavefront
+  // that shares the SIMD and issues none goes straight on with its MFMAs, and the loader does its
+  // own while the other one waits at the next barrier.
+  constexpr bool SPLIT_LOADERS = (NW == 8 && MINB == 1 && ACCA <= 0);
+  constexpr int LW = SPLIT_LOADERS ? NW / 2 : NW;                    // wavefronts that load
+  constexpr int A_BLK = BM / RPB / LW, W_BLK = BN / RPB / LW;
   constexpr int LOADS = A_BLK + W_BLK;
   constexpr int STAGE_ELEMS = (BM + BN) * BK;
   constexpr int KS = BK / 16;
   static_assert(BK == 64 || BK == 32, "k-tile is 64 or 32");
-  static_assert(BM % (RPB * NW) == 0 && BN % (RPB * NW) == 0, "tile rows must split evenly over the wavefronts");
+  static_assert(BM % (RPB * LW) == 0 && BN % (RPB * LW) == 0, "tile rows must split evenly over the loading wavefronts");
+  static_assert(A_BLK % 4 == 0 || A_BLK < 4, "loads are issued in groups of four sharing one M0 value");
   extern __shared__ __align__(16) uint16_t lds[];
 
   const int n_tiles = tiles_m * tiles_n;
@@ -558,6 +566,8 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
   const int r32 = lane & 31, grp = lane >> 5;
   const int lrow = lane / CPR, lslot = lane % CPR;
+  const bool is_loader = !SPLIT_LOADERS || wave >= NW / 2;
+  const int lwave = SPLIT_LOADERS ? (wave >= NW / 2 ? wave - NW / 2 : 0) : wave;   // index among the loading wavefronts
 
   // j-th tile of this workgroup.  Tiles are ordered in bands of 8 tile rows, inside a band in
   // column blocks of 4 tile columns, inside a block row-major; within a round of G tiles each XCD
@@ -591,7 +601,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
   uint32_t a_off[A_BLK], w_off[W_BLK];
 #pragma unroll
   for (int i = 0; i < W_BLK; ++i) {
-    const int row = (wave * W_BLK + i) * RPB + lrow;
+    const int row = (lwave * W_BLK + i) * RPB + lrow;
     w_off[i] = (uint32_t)(((size_t)row * g.K + ((lslot ^ ((row >> SWZ) & (CPR - 1))) * 8)) * 2) + kOffBias - (i % 4) * 1024;
   }
   auto set_load_tile = [&](int j) {
@@ -602,7 +612,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
     asm volatile("" : "+s"(a_base), "+s"(w_base));      // (keeps the bias out of the loads' address expressions)
 #pragma unroll
     for (int i = 0; i < A_BLK; ++i) {
-      const int row = (wave * A_BLK + i) * RPB + lrow;
+      const int row = (lwave * A_BLK + i) * RPB + lrow;
       const int rc = (m0 + row < g.M) ? row : g.M - 1 - m0;       // m0 < M always
       a_off[i] = (uint32_t)(((size_t)rc * g.lda + ((lslot ^ ((row >> SWZ) & (CPR - 1))) * 8)) * 2) + kOffBias - (i % 4) * 1024;
     }
@@ -620,12 +630,12 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
     if (i < A_BLK) {
       asm volatile("" : "+v"(a_off[i]));
       src = a_base + ko + a_off[i];
-      dst = as + (wave * A_BLK + (i & ~3)) * 512;
+      dst = as + (lwave * A_BLK + (i & ~3)) * 512;
     } else {
       const int j = i - A_BLK;
       asm volatile("" : "+v"(w_off[j]));
       src = w_base + ko + w_off[j];
-      dst = ws + (wave * W_BLK + (j & ~3)) * 512;
+      dst = ws + (lwave * W_BLK + (j & ~3)) * 512;
     }
     switch ((i < A_BLK ? i : i - A_BLK) & 3) {       // the immediate has to be a literal
       case 0: ET_LDS_DMA16_OFF(src, dst, 0); break;
@@ -645,6 +655,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
     }
   };
   auto issue_next = [&](int stage) {
+    if (!is_loader) return;
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) issue_one(stage, i);
     issue_advance();
@@ -676,7 +687,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
     clear_acc();
   }
 
-  set_load_tile(0);
+  if (is_loader) set_load_tile(0);
   if constexpr (ACCA == 3) {      // spread loads: the last stage gets its first part here, the rest in the first unit
 #pragma unroll
     for (int st = 0; st < STAGES - 1; ++st) issue_next(st);
