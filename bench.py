@@ -95,6 +95,8 @@ def main():
     ap.add_argument("--keep-ratio", type=float, default=None)
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--cpu-frames", type=int, default=8)
+    ap.add_argument("--groups", type=int, default=1,
+                    help="frame groups run on streams of their own (et_encoder_set_frame_groups)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile-pass", action="store_true")
     ap.add_argument("--no-paper-policy", action="store_true",
@@ -122,6 +124,7 @@ def main():
     m, tau, keep = rec["merge_layer"], rec["sim_threshold"], rec["keep_ratio"]
 
     enc = et.Encoder(shape, rec["weights"], T, device=dev)
+    enc.set_frame_groups(args.groups)
     frames = torch.from_numpy(rec["frames"]).to(dev)
     stream = torch.cuda.current_stream()
 

@@ -88,6 +88,18 @@ int et_encoder_create(const et_config *config, const et_weights *weights, int32_
                       et_encoder **out);
 void et_encoder_destroy(et_encoder *enc); /* NULL is allowed */
 
+/* Frame groups.  Inside the encoder blocks the frames of a clip do not interact (attention is per
+ * frame, Sec. 3.1; everything else is per token), so the encode calls may split the current frames
+ * into n_groups contiguous groups and run each group's kernel sequence on a stream of its own:
+ * group 0 on the caller's stream, the others on streams the encoder owns (default priority), forked
+ * from and joined to the caller's stream with events around every stretch of blocks; the compression
+ * stages (Sec. 3.2, 3.3), which look across frames, run on the caller's stream alone.  The kernels of
+ * different groups fill each other's partly filled last rounds.  Results are bit-identical for every
+ * n_groups.  n_groups in [1, 8]; 1 (the default) keeps everything on the caller's stream.  Frames of
+ * unequal length (decoupled selection) and calls with per-kernel timing on run ungrouped.  Must not be
+ * called while an encode call of this encoder is running.  Errors: INVALID_ARG, HIP. */
+int et_encoder_set_frame_groups(et_encoder *enc, int32_t n_groups);
+
 /* Bytes of device workspace et_encode_clip needs for a clip of T frames (0 on bad arguments). */
 size_t et_workspace_bytes(const et_encoder *enc, int32_t T);
 

@@ -12,5 +12,5 @@ from .binding import (  # noqa: F401
     et_layernorm, et_gemm_bf16, et_gemm_tune, et_attention,
     et_attention_uniform, et_attention_uniform_scratch_bytes,
     et_encoder_create, et_encoder_destroy, et_workspace_bytes, et_encode_clip,
-    et_profile_enable, et_profile_read, et_kernel_name, Encoder, KERNEL_KINDS,
+    et_profile_enable, et_profile_read, et_encoder_set_frame_groups, et_kernel_name, Encoder, KERNEL_KINDS,
 )

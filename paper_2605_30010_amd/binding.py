@@ -103,6 +103,7 @@ def load_library():
         "et_workspace_bytes": (sz, [vp, i32]),
         "et_encode_clip": (C.c_int, [vp, vp, i32, i32, f32, f32, vp, sz, vp, C.POINTER(_Output)]),
         "et_profile_enable": (C.c_int, [vp, i32]),
+        "et_encoder_set_frame_groups": (C.c_int, [vp, i32]),
         "et_profile_read": (C.c_int, [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), i32]),
         "et_kernel_name": (C.c_char_p, [i32]),
     }
@@ -459,6 +460,10 @@ def et_encode_clip(handle, frames, merge_layer, sim_threshold, keep_ratio, L, D,
     return _trim(bufs, o, T)
 
 
+def et_encoder_set_frame_groups(handle, n_groups):
+    _check(load_library().et_encoder_set_frame_groups(handle, int(n_groups)))
+
+
 def et_profile_enable(handle, on):
     _check(load_library().et_profile_enable(handle, int(bool(on))))
 
@@ -487,6 +492,10 @@ class Encoder:
         self.max_frames = max_frames
         self._ws = None
         self._bufs = {}
+
+    def set_frame_groups(self, n_groups):
+        with torch.cuda.device(self.device):
+            et_encoder_set_frame_groups(self.handle, n_groups)
 
     def encode(self, frames, merge_layer, sim_threshold, keep_ratio, stream=None):
         T = frames.shape[0]

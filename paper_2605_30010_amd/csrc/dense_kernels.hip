@@ -1156,8 +1156,8 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const uint16_t *__rest
   }
 }
 
-template <int HD, int STAGES>
-__global__ __launch_bounds__(kAttWaves * 64, (HD <= 96 ? 2 : 1)) void attention_dma_kernel(
+template <int HD, int STAGES, int MINB = (HD <= 96 ? 2 : 1)>
+__global__ __launch_bounds__(kAttWaves * 64, MINB) void attention_dma_kernel(
     const uint16_t *__restrict__ qkv, const uint16_t *__restrict__ vt, int n, int n_heads, int Lpad,
     float scale_log2, uint16_t *__restrict__ out) {
   constexpr int NC = (HD + 15) / 16;
@@ -1165,8 +1165,14 @@ __global__ __launch_bounds__(kAttWaves * 64, (HD <= 96 ? 2 : 1)) void attention_
   constexpr int K_LOADS = HD / 8;            // 1 KiB loads per K tile  (64 keys * HD * 2 bytes)
   constexpr int V_LOADS = HD / 8;            // 1 KiB loads per V^T tile (HD rows * 128 bytes)
   constexpr int LOADS = (K_LOADS + V_LOADS + kAttWaves - 1) / kAttWaves;   // per wavefront per tile
+  // When head_dim is not a multiple of 32 the last O^T row block has spare rows: V^T row head_dim
+  // is then a row of ones kept behind each stage's V^T tile, and accumulator row head_dim of O^T
+  // is the softmax denominator (the sum of the bf16-rounded probabilities, exactly what the
+  // numerator used), for free.
+  constexpr bool SUM_BY_MFMA = (HD % 32) != 0;
+  constexpr int ONES = SUM_BY_MFMA ? kAttBKV : 0;
   constexpr int K_ELEMS = kAttBKV * HD, V_ELEMS = HD * kAttBKV;
-  constexpr int STAGE = K_ELEMS + V_ELEMS;
+  constexpr int STAGE = K_ELEMS + V_ELEMS + ONES;
   // tail pad: O^T row blocks past head_dim read rows behind the V^T tile; whatever they hold only
   // reaches accumulator rows >= head_dim, which are never stored (MFMA output rows are independent).
   // The last 512 elements absorb the filler loads that keep every wavefront at LOADS loads per tile.
@@ -1227,14 +1233,23 @@ __global__ __launch_bounds__(kAttWaves * 64, (HD <= 96 ? 2 : 1)) void attention_
 #pragma unroll
   for (int st = 0; st < STAGES - 1; ++st) issue(st, st);
 
+  if (SUM_BY_MFMA && tid < STAGES * (kAttBKV / 2)) {   // the rows of ones (the loop's first barrier orders them)
+    const int st = tid / (kAttBKV / 2), j = tid % (kAttBKV / 2);
+    reinterpret_cast<uint32_t *>(lds + st * STAGE + K_ELEMS + V_ELEMS)[j] = 0x3F803F80u;
+  }
+  // Q is scaled by log2(e) / sqrt(head_dim) once, here, and rounded back to bf16: the logits leave
+  // the MFMA already in the exponent's units.
   u32x4 qf[NC];
   {
     const int q = q0 + wave * 32 + r32;
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
       const int d = c * 16 + grp * 8;
-      if (q < n && d < HD) qf[c] = *reinterpret_cast<const u32x4 *>(qbase + (size_t)q * ld + d);
-      else qf[c] = u32x4{0u, 0u, 0u, 0u};
+      u32x4 raw = u32x4{0u, 0u, 0u, 0u};
+      if (q < n && d < HD) raw = *reinterpret_cast<const u32x4 *>(qbase + (size_t)q * ld + d);
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        qf[c][j] = cvt_pk_bf16(bf16lo_to_f32(raw[j]) * scale_log2, bf16hi_to_f32(raw[j]) * scale_log2);
     }
   }
   f32x16 o_acc[NDB];
@@ -1242,7 +1257,15 @@ __global__ __launch_bounds__(kAttWaves * 64, (HD <= 96 ? 2 : 1)) void attention_
   for (int b = 0; b < NDB; ++b)
 #pragma unroll
     for (int i = 0; i < 16; ++i) o_acc[b][i] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;        // m_run in raw logit units
+  // Reference maximum of the online softmax, per query, in exponent units.  It is moved only when a
+  // tile's maximum exceeds it by more than kLazy (probabilities then stay below 2^kLazy, harmless in
+  // fp32 / bf16), so the rescaling of O^T is rare after the first tile; its negative is the initial
+  // accumulator of S^T, so that the MFMA delivers s - m_ref and the exponent needs no subtraction.
+  constexpr float kLazy = 8.0f;
+  float m_ref = 0.f, l_run = 0.f;
+  f32x16 neg_m;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) neg_m[i] = 0.f;
   const int vfx = (r32 >> 1) & 7;              // swizzle of this lane's V^T rows (32 b + r32: same low bits)
 
   int stage = 0;
@@ -1260,7 +1283,6 @@ __global__ __launch_bounds__(kAttWaves * 64, (HD <= 96 ? 2 : 1)) void attention_
     // reads of contraction chunk c+1 are issued before the MFMAs of chunk c (scheduling barriers
     // keep that order), and the two key blocks alternate as independent MFMA chains.
     f32x16 s_acc[2];
-    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     u32x4 kf[2][2];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) kf[0][kb] = *reinterpret_cast<const u32x4 *>(ks + (kb * 32 + r32) * HD + grp * 8);
@@ -1273,7 +1295,7 @@ __global__ __launch_bounds__(kAttWaves * 64, (HD <= 96 ? 2 : 1)) void attention_
       }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) s_acc[kb] = mfma32(kf[c & 1][kb], qf[c], c == 0 ? zero16 : s_acc[kb]);
+      for (int kb = 0; kb < 2; ++kb) s_acc[kb] = mfma32(kf[c & 1][kb], qf[c], c == 0 ? neg_m : s_acc[kb]);
       __builtin_amdgcn_sched_barrier(0);
     }
     // first V^T fragments: fetched now, consumed after the softmax arithmetic below
@@ -1296,18 +1318,29 @@ __global__ __launch_bounds__(kAttWaves * 64, (HD <= 96 ? 2 : 1)) void attention_
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) m_tile = fmaxf(m_tile, s_acc[kb][i]);
-    m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32, 64));
-    const float m_new = fmaxf(m_run, m_tile);
-    if (__any(m_new > m_run)) {                // rescale only when some query's maximum moved
-      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2);
-      l_run *= alpha;
-#pragma unroll
-      for (int b = 0; b < NDB; ++b)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) o_acc[b][i] *= alpha;
-      m_run = m_new;
+    {   // maximum over the two lane halves (the other 32 keys of the same query), without an LDS round trip
+      const uint32_t mb = __float_as_uint(m_tile);
+      const auto r = __builtin_amdgcn_permlane32_swap(mb, mb, false, false);
+      m_tile = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));   // relative to m_ref; finite: the tile has a valid key
     }
-    const float mc = m_run * scale_log2;
+    if (t == 0 || __any(m_tile > kLazy)) {      // wave-uniform: move the reference (always after the first tile)
+      const float delta = t == 0 ? m_tile : fmaxf(m_tile, 0.f);
+      if (t > 0) {                              // (nothing accumulated yet in the first tile; later delta >= 0)
+        const float alpha = __builtin_amdgcn_exp2f(-delta);
+        l_run *= alpha;
+#pragma unroll
+        for (int b = 0; b < NDB; ++b)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) o_acc[b][i] *= alpha;
+      }
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s_acc[kb][i] -= delta;
+      m_ref += delta;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) neg_m[i] = -m_ref;
+    }
     float l_tile = 0.f;
     u32x4 pf[4];
 #pragma unroll
@@ -1315,8 +1348,8 @@ __global__ __launch_bounds__(kAttWaves * 64, (HD <= 96 ? 2 : 1)) void attention_
       float p[16];
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        p[i] = __builtin_amdgcn_exp2f(fmaf(s_acc[kb][i], scale_log2, -mc));
-        l_tile += p[i];
+        p[i] = __builtin_amdgcn_exp2f(s_acc[kb][i]);
+        if (!SUM_BY_MFMA) l_tile += p[i];
       }
 #pragma unroll
       for (int hh = 0; hh < 2; ++hh) {
@@ -1346,7 +1379,13 @@ __global__ __launch_bounds__(kAttWaves * 64, (HD <= 96 ? 2 : 1)) void attention_
   }
 
   wait_vmcnt<0>();                            // drain filler / past-the-end loads before LDS is released
-  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  float l_tot;
+  if (SUM_BY_MFMA) {                          // accumulator row head_dim of O^T: lane group (row % 8) / 4, register (row / 8) * 4 + row % 4
+    constexpr int ROW = HD % 32;
+    l_tot = __shfl(o_acc[NDB - 1][(ROW / 8) * 4 + (ROW % 4)], r32 + 32 * ((ROW % 8) / 4), 64);
+  } else {
+    l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  }
   const float inv = 1.0f / l_tot;
   const int q = q0 + wave * 32 + r32;
   if (q < n) {
@@ -1544,6 +1583,10 @@ int launch_attention_uniform(const uint16_t *qkv, int n_frames, int len, int n_h
 #define ET_ATT(HD)                                                                                        \
   case HD:                                                                                                \
     hipLaunchKernelGGL(transpose_v_kernel<HD>, tgrid, dim3(256), 0, s, qkv, len, n_heads, Lpad, vt_ws);   \
+    if (HD == 72 && getenv("ET_ATT_VARIANT"))                                                               \
+      hipLaunchKernelGGL((attention_dma_kernel<72, 2, 3>), agrid, dim3(kAttWaves * 64), 0, s, qkv, vt_ws, len, \
+                         n_heads, Lpad, scale_log2, out);                                                 \
+    else                                                                                                  \
     hipLaunchKernelGGL((attention_dma_kernel<HD, 3>), agrid, dim3(kAttWaves * 64), 0, s, qkv, vt_ws, len,      \
                        n_heads, Lpad, scale_log2, out);                                                   \
     break;

@@ -20,6 +20,8 @@ static uint16_t host_f32_to_bf16(float f) {
   return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
 }
 
+constexpr int kMaxGroups = 8;
+
 struct LayerDev {
   float *ln1_g, *ln1_b, *ln2_g, *ln2_b;
   uint16_t *wqkv, *wo, *w1, *w2;
@@ -36,6 +38,11 @@ struct et_encoder {
   float *patch_b = nullptr, *final_g = nullptr, *final_b = nullptr;
   std::vector<et::LayerDev> layers;
   et::Profiler prof;
+  // frame groups: frames are independent inside the encoder blocks, so their rows can be split into
+  // groups whose kernel sequences run on streams of their own (group 0 on the caller's stream)
+  int n_groups = 1;
+  hipStream_t side[et::kMaxGroups - 1] = {};
+  hipEvent_t fork_ev = nullptr, join_ev[et::kMaxGroups - 1] = {};
 };
 
 namespace et {
@@ -111,6 +118,20 @@ static EncWs carve_encoder(const et_encoder *e, void *ws, int T) {
 
 // with_scores: also leave the attention each token receives in this block in w.att_score (frames of
 // equal length only).
+// The buffers of frames f0.. when every frame has `len` rows (the layouts are all frame-major).
+static EncWs frames_from(const et_encoder *e, const EncWs &w, int f0, int len) {
+  EncWs v = w;
+  const size_t r0 = (size_t)f0 * len;
+  const size_t hid_cols = (size_t)(e->Mhp > e->Kp_pad ? e->Mhp : e->Kp_pad);
+  v.x += r0 * e->D;
+  v.xn += r0 * e->D;
+  v.qkv += r0 * 3 * e->D;
+  v.att += r0 * e->D;
+  v.hid += r0 * hid_cols;
+  v.vt += attention_uniform_workspace_bytes(f0, len, e->cfg.n_heads, e->hd) / sizeof(uint16_t);
+  return v;
+}
+
 static int run_block(et_encoder *e, const LayerDev &lw, const EncWs &w, int rows, const int32_t *cu,
                      int n_frames, int max_len, bool ragged, hipStream_t s, bool with_scores = false) {
   const et_config &c = e->cfg;
@@ -133,6 +154,53 @@ static int run_block(et_encoder *e, const LayerDev &lw, const EncWs &w, int rows
   ET_TIMED(ET_K_GEMM_FC1, launch_gemm(g, s));
   g = GemmArgs{w.hid, e->Mhp, lw.w2, lw.b2, w.x, D, rows, w.x, D, rows, D, e->Mhp, EPI_BIAS_RES};
   ET_TIMED(ET_K_GEMM_FC2, launch_gemm(g, s));
+  return ET_OK;
+}
+
+// Side streams start after everything enqueued on `s` so far ...
+static int fork_groups(et_encoder *e, int n, hipStream_t s) {
+  ET_HIP(hipEventRecord(e->fork_ev, s));
+  for (int g = 0; g + 1 < n; ++g) ET_HIP(hipStreamWaitEvent(e->side[g], e->fork_ev, 0));
+  return ET_OK;
+}
+// ... and `s` continues after everything enqueued on them.
+static int join_groups(et_encoder *e, int n, hipStream_t s) {
+  for (int g = 0; g + 1 < n; ++g) {
+    ET_HIP(hipEventRecord(e->join_ev[g], e->side[g]));
+    ET_HIP(hipStreamWaitEvent(s, e->join_ev[g], 0));
+  }
+  return ET_OK;
+}
+// Joins on every way out of the encode, so that the caller's stream never runs ahead of a side stream.
+struct GroupScope {
+  et_encoder *e;
+  int n;
+  hipStream_t s;
+  bool forked = false;
+  int fork() {
+    if (forked || n <= 1) return ET_OK;
+    forked = true;
+    return fork_groups(e, n, s);
+  }
+  int join() {
+    if (!forked) return ET_OK;
+    forked = false;
+    return join_groups(e, n, s);
+  }
+  ~GroupScope() { (void)join(); }
+};
+
+// One encoder block over n_frames frames of `len` rows each, the frames split into n groups (group 0
+// on `s`, the others on the side streams; the scope must be forked).
+static int run_block_groups(et_encoder *e, const LayerDev &lw, const EncWs &w, int n_frames, int len, int n,
+                            hipStream_t s) {
+  for (int g = 0; g < n; ++g) {
+    const int f0 = (int)((int64_t)g * n_frames / n), f1 = (int)((int64_t)(g + 1) * n_frames / n);
+    if (f1 == f0) continue;
+    int rc = run_block(e, lw, frames_from(e, w, f0, len), (f1 - f0) * len, nullptr, f1 - f0, len, false,
+                       g == 0 ? s : e->side[g - 1]);
+    if (rc) return rc;
+  }
   return ET_OK;
 }
 
@@ -225,11 +293,38 @@ int et_encoder_create(const et_config *config, const et_weights *weights, int32_
   return ET_OK;
 }
 
+static void destroy_groups(et_encoder *e) {
+  for (int g = 0; g < kMaxGroups - 1; ++g) {
+    if (e->side[g]) (void)hipStreamDestroy(e->side[g]);
+    if (e->join_ev[g]) (void)hipEventDestroy(e->join_ev[g]);
+    e->side[g] = nullptr;
+    e->join_ev[g] = nullptr;
+  }
+  if (e->fork_ev) (void)hipEventDestroy(e->fork_ev);
+  e->fork_ev = nullptr;
+  e->n_groups = 1;
+}
+
 void et_encoder_destroy(et_encoder *e) {
   if (!e) return;
+  destroy_groups(e);
   for (void *p : e->allocs) (void)hipFree(p);
   e->prof.destroy();
   delete e;
+}
+
+int et_encoder_set_frame_groups(et_encoder *e, int32_t n_groups) {
+  ET_REQUIRE(e != nullptr, "encoder is NULL");
+  ET_REQUIRE(n_groups >= 1 && n_groups <= kMaxGroups, "n_groups = %d outside [1, %d]", n_groups, kMaxGroups);
+  destroy_groups(e);
+  if (n_groups == 1) return ET_OK;
+  ET_HIP(hipEventCreateWithFlags(&e->fork_ev, hipEventDisableTiming));
+  for (int g = 0; g + 1 < n_groups; ++g) {
+    ET_HIP(hipStreamCreateWithFlags(&e->side[g], hipStreamNonBlocking));   // (default priority)
+    ET_HIP(hipEventCreateWithFlags(&e->join_ev[g], hipEventDisableTiming));
+  }
+  e->n_groups = n_groups;
+  return ET_OK;
 }
 
 size_t et_workspace_bytes(const et_encoder *e, int32_t T) {
@@ -285,13 +380,6 @@ static int encode_impl(et_encoder *e, const float *frames_dev, int32_t T, int32_
   e->prof.kinds.clear();
   e->prof.phase = 0;
 
-  // patch embedding: x = patches * Wp^T + bp + pos_emb[l]
-  ET_TIMED(ET_K_IM2COL, launch_im2col(frames_dev, T, c.channels, c.image_h, c.image_w, c.patch, e->Kp_pad,
-                                      w.hid, s));
-  GemmArgs g{w.hid, e->Kp_pad, e->patch_w, e->patch_b, e->pos_emb, D, L, w.x, D, T * L, D, e->Kp_pad,
-             EPI_BIAS_RES};
-  ET_TIMED(ET_K_GEMM_PATCH, launch_gemm(g, s));
-
   int rows = T * L, n_frames = T, max_len = L, k = L;
   (void)k;
   const int32_t *cu = w.cu_full;
@@ -303,11 +391,44 @@ static int encode_impl(et_encoder *e, const float *frames_dev, int32_t T, int32_
     ET_TIMED(ET_K_MISC, launch_cu_uniform(T, L, w.cu_full, s));
   }
 
+  // Frame groups (per-kernel timing wants one kernel at a time on the device, so it runs ungrouped).
+  const int G = e->prof.on ? 1 : e->n_groups;
+  GroupScope groups{e, G, s};
+
+  // patch embedding: x = patches * Wp^T + bp + pos_emb[l]
+  if (G > 1 && T >= 2) {
+    int rc = groups.fork();
+    if (rc) return rc;
+    const size_t frame_elems = (size_t)c.channels * c.image_h * c.image_w;
+    for (int gi = 0; gi < G; ++gi) {
+      const int f0 = (int)((int64_t)gi * T / G), f1 = (int)((int64_t)(gi + 1) * T / G);
+      if (f1 == f0) continue;
+      hipStream_t st = gi == 0 ? s : e->side[gi - 1];
+      const EncWs v = frames_from(e, w, f0, L);
+      if ((rc = launch_im2col(frames_dev + f0 * frame_elems, f1 - f0, c.channels, c.image_h, c.image_w, c.patch,
+                              e->Kp_pad, v.hid, st)))
+        return rc;
+      GemmArgs g{v.hid, e->Kp_pad, e->patch_w, e->patch_b, e->pos_emb, D, L, v.x, D, (f1 - f0) * L, D, e->Kp_pad,
+                 EPI_BIAS_RES};
+      if ((rc = launch_gemm(g, st))) return rc;
+    }
+  } else {
+    ET_TIMED(ET_K_IM2COL, launch_im2col(frames_dev, T, c.channels, c.image_h, c.image_w, c.patch, e->Kp_pad,
+                                        w.hid, s));
+    GemmArgs g{w.hid, e->Kp_pad, e->patch_w, e->patch_b, e->pos_emb, D, L, w.x, D, T * L, D, e->Kp_pad,
+               EPI_BIAS_RES};
+    ET_TIMED(ET_K_GEMM_PATCH, launch_gemm(g, s));
+  }
+
   bool ragged = false, selected = false, first_stage = true;
   int n_segments = T, next_merge = 0;
   for (int i = 0; i <= c.n_layers; ++i) {
     const bool merge_here = compress && policy && !selected && next_merge < n_merge && merge_layers[next_merge] == i;
     const bool select_here = compress && !selected && i == merge_layer;
+    if (merge_here || select_here) {       // the stage looks across frames
+      int rc = groups.join();
+      if (rc) return rc;
+    }
     if (policy && (merge_here || select_here)) {
       const MergeWs mw = carve_merge(w.merge, T, L, D);
       int32_t *info = mw.n_seg + 8;
@@ -365,10 +486,25 @@ static int encode_impl(et_encoder *e, const float *frames_dev, int32_t T, int32_
       e->prof.phase = 1;
     }
     if (i < c.n_layers) {
-      int rc = run_block(e, e->layers[i], w, rows, cu, n_frames, max_len, ragged, s,
-                         by_attention && !selected && i == merge_layer - 1);
-      if (rc) return rc;
+      const bool with_scores = by_attention && !selected && i == merge_layer - 1;
+      int rc;
+      if (G > 1 && !ragged && n_frames >= 2) {
+        if ((rc = groups.fork())) return rc;
+        if ((rc = run_block_groups(e, e->layers[i], w, n_frames, max_len, G, s))) return rc;
+        if (with_scores) {   // the block's q and k stay in w.qkv until the next block: scores of all frames at once
+          if ((rc = groups.join())) return rc;
+          if ((rc = launch_attention_scores(w.qkv, n_frames, max_len, c.n_heads, e->hd, w.score_ws, w.att_score, s)))
+            return rc;
+        }
+      } else {
+        if ((rc = groups.join())) return rc;
+        if ((rc = run_block(e, e->layers[i], w, rows, cu, n_frames, max_len, ragged, s, with_scores))) return rc;
+      }
     }
+  }
+  {
+    int rc = groups.join();
+    if (rc) return rc;
   }
   if (plan) plan->n_segments = n_segments;
   if (c.has_final_ln) {

@@ -160,6 +160,34 @@ def test_attention_uniform_matches_oracle(n_heads, hd, n_frames, length):
     assert rel_l2(dev_to_f64(gen), got) < 6e-3
 
 
+@pytest.mark.parametrize("order", ["rising", "falling", "negative_first", "spike_last"])
+def test_attention_uniform_moving_maxima(order):
+    """The online softmax keeps a reference maximum that it moves only when a 64-key tile exceeds it by
+    2^8; these inputs make the row maxima climb by far more than that from tile to tile (rising), never
+    move after the first tile (falling), start far below zero (negative_first), or jump in the last,
+    partly filled tile (spike_last)."""
+    n_heads, hd, n_frames, length = 16, 72, 2, 729
+    rng = np.random.default_rng({"rising": 1, "falling": 2, "negative_first": 3, "spike_last": 4}[order])
+    D, rows = n_heads * hd, n_frames * length
+    _, qkv = _bf(rng, (rows, 3 * D))
+    pos = np.tile(np.arange(length), n_frames).astype(np.float64)
+    # logits = q . k / sqrt(72): a shared direction u with |u| = 1 gives q.k ~ a_q * a_k
+    u = np.zeros(D)
+    u.reshape(n_heads, hd)[:, 0] = 1.0
+    ramp = {"rising": pos / 64.0 * 3.0, "falling": (length - pos) / 64.0 * 3.0,
+            "negative_first": np.where(pos < 64, -40.0, 0.0), "spike_last": np.where(pos >= 720, 30.0, 0.0)}[order]
+    qkv[:, :D] = qkv[:, :D] * 0.5 + 8.0 * u                      # q . u = 8 per head
+    qkv[:, D:2 * D] = qkv[:, D:2 * D] * 0.5 + ramp[:, None] * u  # k . u = ramp -> logit shift 8 ramp / sqrt(72)
+    bits = f32_to_bf16_bits(qkv.astype(np.float32))
+    qkv = bf16_bits_to_f32(bits).astype(np.float64)
+    cu = (np.arange(n_frames + 1) * length).astype(np.int32)
+    ref = _attention_ref(qkv, cu, n_heads, hd)
+    got = dev_to_f64(et.et_attention_uniform(bits_to_dev(bits), n_frames, length, n_heads, hd))
+    assert np.all(np.isfinite(got))
+    assert rel_l2(got, ref) < 1e-2
+    assert np.max(np.abs(got - ref)) < 0.05
+
+
 @pytest.mark.parametrize("cfg", [20, 33, 34, 35])
 def test_gemm_persistent_configs_walk_several_tiles_per_workgroup(cfg):
     """More output tiles than compute units, so each persistent workgroup finishes a tile, clears its

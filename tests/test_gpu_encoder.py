@@ -237,3 +237,75 @@ def test_full_size_32_frame_clip_other_settings(siglip_weights):
 def test_full_size_64_frame_clip(siglip_weights):
     """Config 4: 64 frames, noisier scenes with abrupt cuts, merge after 4 blocks, keep 0.25."""
     _full_size_check("c4_siglip_t64", siglip_weights, range(0, 6), sample_segments=1)
+
+
+# ------------------------------------------------------------------ frame groups on side streams
+
+def _same_outputs(a, b):
+    for key in ("seg_start", "cu_tokens", "kept_idx"):
+        assert a[key].tolist() == b[key].tolist(), key
+    assert a["n_frames_out"] == b["n_frames_out"] and a["n_tokens"] == b["n_tokens"]
+    assert torch.equal(dev_to_bits_t(a["tokens"]), dev_to_bits_t(b["tokens"]))
+
+
+def dev_to_bits_t(t):
+    return t.view(torch.int16) if t.dtype == torch.bfloat16 else t
+
+
+@pytest.mark.parametrize("n_groups", [2, 3, 8])
+def test_frame_groups_give_bit_identical_results_tiny(tiny, n_groups):
+    """Splitting the frames over streams changes neither decisions nor a single output bit: the
+    blocks are per-frame computations (Sec. 3.1) and the stages run after the groups have joined."""
+    w, frames = tiny
+    T = frames.shape[0]
+    enc = et.Encoder(TINY, w, T)
+    cases = [(2, 0.9, 0.5), (-1, 0.0, 1.0), (0, 0.5, 0.25), (TINY.n_layers, 0.9, 0.5)]
+    base = [_encode(enc, frames, *c) for c in cases]
+    enc.set_frame_groups(n_groups)
+    for _ in range(2):       # twice: the fork / join events are reused from call to call
+        for c, ref in zip(cases, base):
+            _same_outputs(_encode(enc, frames, *c), ref)
+    # a single frame, fewer frames than groups
+    one = _encode(enc, frames[:1], 2, 0.9, 0.5)
+    enc.set_frame_groups(1)
+    _same_outputs(one, _encode(enc, frames[:1], 2, 0.9, 0.5))
+    enc.close()
+
+
+def test_frame_groups_policy_paths_bit_identical(tiny):
+    w, frames = tiny
+    T = frames.shape[0]
+    enc = et.Encoder(TINY, w, T)
+    pols = [dict(merge_mode="alg1", select_mode="decoupled", alpha=1.0, tau_seg=0.9, tau_merge=0.8, ratio=0.5,
+                 score_mode="attention"),
+            dict(merge_mode="alg1", select_mode="uniform", alpha=1.0, tau_seg=0.9, tau_merge=0.8, ratio=0.5,
+                 score_mode="l2")]
+    for pol in pols:
+        enc.set_frame_groups(1)
+        ref = enc.encode_multi(torch.from_numpy(frames).cuda(), [1, 2], TINY.n_layers, pol)
+        ref = {k: (v.clone() if isinstance(v, torch.Tensor) else v) for k, v in ref.items()}
+        enc.set_frame_groups(2)
+        got = enc.encode_multi(torch.from_numpy(frames).cuda(), [1, 2], TINY.n_layers, pol)
+        _same_outputs(got, ref)
+    enc.close()
+
+
+def test_frame_groups_siglip_shape_bit_identical(siglip8):
+    rec = siglip8
+    enc = et.Encoder(SIGLIP, rec["weights"], 8)
+    args = (rec["frames"], rec["merge_layer"], rec["sim_threshold"], rec["keep_ratio"])
+    ref = _encode(enc, *args)
+    enc.set_frame_groups(2)
+    _same_outputs(_encode(enc, *args), ref)
+    enc.set_frame_groups(4)
+    _same_outputs(_encode(enc, *args), ref)
+    enc.close()
+
+
+def test_frame_groups_argument_errors(tiny):
+    w, frames = tiny
+    enc = et.Encoder(TINY, w, frames.shape[0])
+    for bad in (0, -1, 9):
+        with pytest.raises(et.EtError):
+            enc.set_frame_groups(bad)
+    enc.close()
