@@ -1156,7 +1156,7 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const uint16_t *__rest
   }
 }
 
-template <int HD, int STAGES, int MINB = (HD <= 96 ? 2 : 1)>
+template <int HD, int STAGES, int QB, int MINB>
 __global__ __launch_bounds__(kAttWaves * 64, MINB) void attention_dma_kernel(
     const uint16_t *__restrict__ qkv, const uint16_t *__restrict__ vt, int n, int n_heads, int Lpad,
     float scale_log2, uint16_t *__restrict__ out) {
@@ -1170,6 +1170,10 @@ __global__ __launch_bounds__(kAttWaves * 64, MINB) void attention_dma_kernel(
   // is the softmax denominator (the sum of the bf16-rounded probabilities, exactly what the
   // numerator used), for free.
   constexpr bool SUM_BY_MFMA = (HD % 32) != 0;
+  // When head_dim is not a multiple of 16 the Q K^T contraction has spare slots: slot head_dim of
+  // every K row is read as 1 and slot head_dim of a query holds minus its reference maximum, so
+  // the MFMA delivers s - m_ref.  Otherwise the subtraction is a vector instruction per logit.
+  constexpr bool REF_IN_PAD = (HD % 16) != 0;
   constexpr int ONES = SUM_BY_MFMA ? kAttBKV : 0;
   constexpr int K_ELEMS = kAttBKV * HD, V_ELEMS = HD * kAttBKV;
   constexpr int STAGE = K_ELEMS + V_ELEMS + ONES;
@@ -1179,7 +1183,7 @@ __global__ __launch_bounds__(kAttWaves * 64, MINB) void attention_dma_kernel(
   constexpr int PAD = (NDB * 32 - HD) * kAttBKV + 512;
   __shared__ __align__(16) uint16_t lds[STAGES * STAGE + PAD];
 
-  const int f = blockIdx.z, h = blockIdx.y, q0 = blockIdx.x * kAttBQ;
+  const int f = blockIdx.z, h = blockIdx.y, q0 = blockIdx.x * (kAttBQ * QB);
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps load dispatch scalar
   const int r32 = lane & 31, grp = lane >> 5;
@@ -1191,81 +1195,95 @@ __global__ __launch_bounds__(kAttWaves * 64, MINB) void attention_dma_kernel(
 
   // loads j = wave, wave + 4, ... of a tile belong to this wavefront; ids past the tile's 2*HD/8
   // loads are fillers (same count for every wavefront, so one vmcnt immediate serves all).
-  // Per-lane source offsets are computed once: tiles advance by a constant stride, and only the
-  // last tile needs its key rows clamped to the frame (its offsets are kept separately).
-  int off_first[LOADS], off_last[LOADS];
+  // Everything a load needs is prepared here, so that issuing a tile is straight-line code: a
+  // per-lane source pointer that advances by a constant per tile (the last tile has pointers of its
+  // own, with the key rows clamped to the frame; tiles past the end re-read it, unused) and a
+  // wave-uniform destination offset inside the stage.
+  const uint16_t *cur[LOADS], *src_last[LOADS];
+  int dst_off[LOADS], step[LOADS];           // elements into the stage (fillers: into the array); elements per tile
+  bool filler[LOADS];
 #pragma unroll
   for (int j = 0; j < LOADS; ++j) {
     const int ld_id = j * kAttWaves + wave;
+    filler[j] = false;
     if (ld_id < K_LOADS) {
       const int q = ld_id * 64 + lane, key = q / (HD / 8), ch = q % (HD / 8);
       int kl = (n_tiles - 1) * kAttBKV + key;
       if (kl >= n) kl = n - 1;                         // clamp: masked later, stays in bounds
-      off_first[j] = key * ld + ch * 8;
-      off_last[j] = kl * ld + ch * 8;
+      cur[j] = kbase + (size_t)key * ld + ch * 8;
+      src_last[j] = kbase + (size_t)kl * ld + ch * 8;
+      dst_off[j] = ld_id * 512;
+      step[j] = kAttBKV * ld;
     } else if (ld_id < K_LOADS + V_LOADS) {
       const int q = (ld_id - K_LOADS) * 64 + lane, d = q >> 3, slot = q & 7;
-      off_first[j] = d * Lpad + ((slot ^ ((d >> 1) & 7)) * 8);
-      off_last[j] = off_first[j] + (n_tiles - 1) * kAttBKV;
+      cur[j] = vtb + (size_t)d * Lpad + ((slot ^ ((d >> 1) & 7)) * 8);
+      src_last[j] = cur[j] + (n_tiles - 1) * kAttBKV;
+      dst_off[j] = K_ELEMS + (ld_id - K_LOADS) * 512;
+      step[j] = kAttBKV;
     } else {
-      off_first[j] = off_last[j] = lane * 8;
+      cur[j] = src_last[j] = vtb + lane * 8;
+      dst_off[j] = STAGES * STAGE + PAD - 512;
+      step[j] = 0;
+      filler[j] = true;
     }
+    if (n_tiles == 1) cur[j] = src_last[j];
   }
-  auto issue = [&](int stage, int tile) {
-    const bool last = tile >= n_tiles - 1;             // past the end: re-read the last tile, unused
-    uint16_t *ks = lds + stage * STAGE;
-    uint16_t *vs = ks + K_ELEMS;
+  int next_tile = 0;
+  auto issue = [&](int stage) {                        // the loads of tile `next_tile` into `stage`
+    const int sb = stage * STAGE;
 #pragma unroll
-    for (int j = 0; j < LOADS; ++j) {
-      const int ld_id = j * kAttWaves + wave;
-      if (ld_id < K_LOADS) {
-        const int off = last ? off_last[j] : off_first[j] + tile * (kAttBKV * ld);
-        ET_LDS_DMA16(kbase + off, ks + ld_id * 512);
-      } else if (ld_id < K_LOADS + V_LOADS) {
-        const int off = last ? off_last[j] : off_first[j] + tile * kAttBKV;
-        ET_LDS_DMA16(vtb + off, vs + (ld_id - K_LOADS) * 512);
-      } else {
-        ET_LDS_DMA16(vtb + off_first[j], lds + STAGES * STAGE + PAD - 512);
-      }
+    for (int j = 0; j < LOADS; ++j) ET_LDS_DMA16(cur[j], lds + (filler[j] ? dst_off[j] : sb + dst_off[j]));
+    ++next_tile;
+    if (next_tile == n_tiles - 1) {
+#pragma unroll
+      for (int j = 0; j < LOADS; ++j) cur[j] = src_last[j];
+    } else if (next_tile < n_tiles - 1) {
+#pragma unroll
+      for (int j = 0; j < LOADS; ++j) cur[j] += step[j];
     }
   };
 
 #pragma unroll
-  for (int st = 0; st < STAGES - 1; ++st) issue(st, st);
+  for (int st = 0; st < STAGES - 1; ++st) issue(st);
 
   if (SUM_BY_MFMA && tid < STAGES * (kAttBKV / 2)) {   // the rows of ones (the loop's first barrier orders them)
     const int st = tid / (kAttBKV / 2), j = tid % (kAttBKV / 2);
     reinterpret_cast<uint32_t *>(lds + st * STAGE + K_ELEMS + V_ELEMS)[j] = 0x3F803F80u;
   }
   // Q is scaled by log2(e) / sqrt(head_dim) once, here, and rounded back to bf16: the logits leave
-  // the MFMA already in the exponent's units.
-  u32x4 qf[NC];
-  {
-    const int q = q0 + wave * 32 + r32;
+  // the MFMA already in the exponent's units.  A wavefront owns QB blocks of 32 queries: every K and
+  // V^T fragment it reads from LDS feeds QB MFMAs.
+  u32x4 qf[QB][NC];
+#pragma unroll
+  for (int j = 0; j < QB; ++j) {
+    const int q = q0 + (wave * QB + j) * 32 + r32;
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
       const int d = c * 16 + grp * 8;
       u32x4 raw = u32x4{0u, 0u, 0u, 0u};
       if (q < n && d < HD) raw = *reinterpret_cast<const u32x4 *>(qbase + (size_t)q * ld + d);
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-        qf[c][j] = cvt_pk_bf16(bf16lo_to_f32(raw[j]) * scale_log2, bf16hi_to_f32(raw[j]) * scale_log2);
+      for (int e = 0; e < 4; ++e)
+        qf[j][c][e] = cvt_pk_bf16(bf16lo_to_f32(raw[e]) * scale_log2, bf16hi_to_f32(raw[e]) * scale_log2);
     }
   }
-  f32x16 o_acc[NDB];
+  f32x16 o_acc[QB][NDB];
 #pragma unroll
-  for (int b = 0; b < NDB; ++b)
+  for (int j = 0; j < QB; ++j)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) o_acc[b][i] = 0.f;
-  // Reference maximum of the online softmax, per query, in exponent units.  It is moved only when a
-  // tile's maximum exceeds it by more than kLazy (probabilities then stay below 2^kLazy, harmless in
-  // fp32 / bf16), so the rescaling of O^T is rare after the first tile; its negative is the initial
-  // accumulator of S^T, so that the MFMA delivers s - m_ref and the exponent needs no subtraction.
+    for (int b = 0; b < NDB; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o_acc[j][b][i] = 0.f;
+  // Reference maximum of the online softmax, per query, in exponent units.  It is moved only when
+  // the maximum of a 32-key block exceeds it by more than kLazy (probabilities then stay below
+  // 2^kLazy, harmless in fp32 / bf16), so the rescaling of O^T is rare after the first block.  With
+  // REF_IN_PAD it is kept bf16-representable (any reference serves as long as numerator and
+  // denominator use the same one).
   constexpr float kLazy = 8.0f;
-  float m_ref = 0.f, l_run = 0.f;
-  f32x16 neg_m;
+  float m_ref[QB], l_run[QB];
 #pragma unroll
-  for (int i = 0; i < 16; ++i) neg_m[i] = 0.f;
+  for (int j = 0; j < QB; ++j) m_ref[j] = l_run[j] = 0.f;
+  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   const int vfx = (r32 >> 1) & 7;              // swizzle of this lane's V^T rows (32 b + r32: same low bits)
 
   int stage = 0;
@@ -1274,134 +1292,148 @@ __global__ __launch_bounds__(kAttWaves * 64, MINB) void attention_dma_kernel(
     wait_vmcnt<(STAGES - 2) * LOADS>();        // tile t has landed (newer tiles may be in flight)
     __builtin_amdgcn_s_barrier();              // ... for every wavefront; everyone is done with tile t-1
     asm volatile("" ::: "memory");
-    issue(stage == 0 ? STAGES - 1 : stage - 1, t + STAGES - 1);
+    issue(stage == 0 ? STAGES - 1 : stage - 1);
     const uint16_t *ks = lds + stage * STAGE;
     const uint16_t *vs = ks + K_ELEMS;
     stage = (stage + 1 == STAGES) ? 0 : stage + 1;
 
-    // S^T = K Q^T for the tile's two 32-key blocks.  K fragments are double-buffered: the LDS
-    // reads of contraction chunk c+1 are issued before the MFMAs of chunk c (scheduling barriers
-    // keep that order), and the two key blocks alternate as independent MFMA chains.
-    f32x16 s_acc[2];
-    u32x4 kf[2][2];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) kf[0][kb] = *reinterpret_cast<const u32x4 *>(ks + (kb * 32 + r32) * HD + grp * 8);
+    for (int kb = 0; kb < 2; ++kb) {           // the tile's two 32-key blocks
+      // S^T = K Q^T.  K fragments are double-buffered: the LDS read of contraction chunk c+1 is
+      // issued before the MFMAs of chunk c (scheduling barriers keep that order); the query blocks
+      // are independent MFMA chains.
+      f32x16 s_acc[QB];
+      u32x4 kf[2];
+      kf[0] = *reinterpret_cast<const u32x4 *>(ks + (kb * 32 + r32) * HD + grp * 8);
 #pragma unroll
-    for (int c = 0; c < NC; ++c) {
-      if (c + 1 < NC) {
+      for (int c = 0; c < NC; ++c) {
+        if (c + 1 < NC)
+          kf[(c + 1) & 1] = *reinterpret_cast<const u32x4 *>(ks + (kb * 32 + r32) * HD + (c + 1) * 16 + grp * 8);
+        u32x4 kk = kf[c & 1];
+        if (REF_IN_PAD && c == NC - 1 && grp) kk = u32x4{0x3F80u, 0u, 0u, 0u};   // slot head_dim reads 1, the rest 0
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-          kf[(c + 1) & 1][kb] = *reinterpret_cast<const u32x4 *>(ks + (kb * 32 + r32) * HD + (c + 1) * 16 + grp * 8);
+        for (int j = 0; j < QB; ++j) s_acc[j] = mfma32(kk, qf[j][c], c == 0 ? zero16 : s_acc[j]);
+        __builtin_amdgcn_sched_barrier(0);
       }
+      // V^T fragments of the block's first 16 keys: fetched now, consumed after the softmax arithmetic
+      u32x4 vf[2][NDB];
+#pragma unroll
+      for (int b = 0; b < NDB; ++b)
+        vf[0][b] = *reinterpret_cast<const u32x4 *>(vs + (b * 32 + r32) * kAttBKV + (((4 * kb + grp) ^ vfx) * 8));
       __builtin_amdgcn_sched_barrier(0);
+      float mx[QB];
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) s_acc[kb] = mfma32(kf[c & 1][kb], qf[c], c == 0 ? neg_m : s_acc[kb]);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    // first V^T fragments: fetched now, consumed after the softmax arithmetic below
-    u32x4 vf[2][NDB];
+      for (int j = 0; j < QB; ++j) {
+        if (!REF_IN_PAD) {
 #pragma unroll
-    for (int b = 0; b < NDB; ++b)
-      vf[0][b] = *reinterpret_cast<const u32x4 *>(vs + (b * 32 + r32) * kAttBKV + ((grp ^ vfx) * 8));
-    __builtin_amdgcn_sched_barrier(0);
-    if (kv0 + kAttBKV > n) {                   // only the last tile can hold keys past the frame
+          for (int i = 0; i < 16; ++i) s_acc[j][i] -= m_ref[j];
+        }
+        if (kv0 + kAttBKV > n) {               // only the last tile can hold keys past the frame
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+          for (int i = 0; i < 16; ++i) {
+            const int key = kv0 + kb * 32 + (i >> 2) * 8 + grp * 4 + (i & 3);
+            if (key >= n) s_acc[j][i] = -INFINITY;
+          }
+        }
+        float m = s_acc[j][0];
+#pragma unroll
+        for (int i = 1; i < 16; ++i) m = fmaxf(m, s_acc[j][i]);
+        // maximum over the two lane halves (the other 16 keys of the same query), without an LDS round trip
+        const uint32_t mb = __float_as_uint(m);
+        const auto r = __builtin_amdgcn_permlane32_swap(mb, mb, false, false);
+        mx[j] = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));   // relative to m_ref
+      }
+      const bool first = t == 0 && kb == 0;    // (its block always holds a valid key: mx is finite)
+      bool over = false;
+#pragma unroll
+      for (int j = 0; j < QB; ++j) over = over || mx[j] > kLazy;
+      if (first || __any(over)) {              // wave-uniform: move the references
+#pragma unroll
+        for (int j = 0; j < QB; ++j) {
+          // a block of the last tile may hold no valid key at all (mx = -inf): it moves nothing
+          float target = m_ref[j] + (first ? mx[j] : fmaxf(mx[j], 0.f));
+          if (REF_IN_PAD) target = bf16lo_to_f32(cvt_pk_bf16(target, 0.f));
+          const float delta = target - m_ref[j];
+          if (!first) {                        // (nothing accumulated yet in the first block; later delta >= 0)
+            const float alpha = __builtin_amdgcn_exp2f(-delta);
+            l_run[j] *= alpha;
+#pragma unroll
+            for (int b = 0; b < NDB; ++b)
+#pragma unroll
+              for (int i = 0; i < 16; ++i) o_acc[j][b][i] *= alpha;
+          }
+#pragma unroll
+          for (int i = 0; i < 16; ++i) s_acc[j][i] -= delta;
+          m_ref[j] = target;
+          if (REF_IN_PAD && grp) qf[j][NC - 1][0] = cvt_pk_bf16(-target, 0.f);
+        }
+      }
+      u32x4 pf[QB][2];
+#pragma unroll
+      for (int j = 0; j < QB; ++j) {
+        float p[16];
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          const int key = kv0 + kb * 32 + (i >> 2) * 8 + grp * 4 + (i & 3);
-          if (key >= n) s_acc[kb][i] = -INFINITY;
+          p[i] = __builtin_amdgcn_exp2f(s_acc[j][i]);
+          if (!SUM_BY_MFMA) l_run[j] += p[i];
         }
-    }
-    float m_tile = s_acc[0][0];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) m_tile = fmaxf(m_tile, s_acc[kb][i]);
-    {   // maximum over the two lane halves (the other 32 keys of the same query), without an LDS round trip
-      const uint32_t mb = __float_as_uint(m_tile);
-      const auto r = __builtin_amdgcn_permlane32_swap(mb, mb, false, false);
-      m_tile = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));   // relative to m_ref; finite: the tile has a valid key
-    }
-    if (t == 0 || __any(m_tile > kLazy)) {      // wave-uniform: move the reference (always after the first tile)
-      const float delta = t == 0 ? m_tile : fmaxf(m_tile, 0.f);
-      if (t > 0) {                              // (nothing accumulated yet in the first tile; later delta >= 0)
-        const float alpha = __builtin_amdgcn_exp2f(-delta);
-        l_run *= alpha;
-#pragma unroll
-        for (int b = 0; b < NDB; ++b)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) o_acc[b][i] *= alpha;
+        for (int hh = 0; hh < 2; ++hh) {
+          u32x4 v;
+          v.x = cvt_pk_bf16(p[hh * 8 + 0], p[hh * 8 + 1]); v.y = cvt_pk_bf16(p[hh * 8 + 2], p[hh * 8 + 3]);
+          v.z = cvt_pk_bf16(p[hh * 8 + 4], p[hh * 8 + 5]); v.w = cvt_pk_bf16(p[hh * 8 + 6], p[hh * 8 + 7]);
+          pf[j][hh] = v;
+        }
       }
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) s_acc[kb][i] -= delta;
-      m_ref += delta;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) neg_m[i] = -m_ref;
-    }
-    float l_tile = 0.f;
-    u32x4 pf[4];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      float p[16];
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        p[i] = __builtin_amdgcn_exp2f(s_acc[kb][i]);
-        if (!SUM_BY_MFMA) l_tile += p[i];
-      }
+      // O^T += V^T P^T.  P's k-slots of 16-key chunk c, lane group grp, are keys 16c + 4 grp + (0..3) and
+      // 16c + 8 + 4 grp + (0..3); transpose_v_kernel stored exactly those 8 keys in 16-byte slot
+      // 2c + grp of the V^T row.  Row blocks and query blocks are independent MFMA chains.
 #pragma unroll
       for (int hh = 0; hh < 2; ++hh) {
-        u32x4 v;
-        v.x = cvt_pk_bf16(p[hh * 8 + 0], p[hh * 8 + 1]); v.y = cvt_pk_bf16(p[hh * 8 + 2], p[hh * 8 + 3]);
-        v.z = cvt_pk_bf16(p[hh * 8 + 4], p[hh * 8 + 5]); v.w = cvt_pk_bf16(p[hh * 8 + 6], p[hh * 8 + 7]);
-        pf[kb * 2 + hh] = v;
-      }
-    }
-    l_run += l_tile;
-    // O^T += V^T P^T.  P's k-slots of chunk c, lane group grp, are keys 16c + 4 grp + (0..3) and
-    // 16c + 8 + 4 grp + (0..3); transpose_v_kernel stored exactly those 8 keys in 16-byte slot
-    // 2c + grp of the V^T row.  Row blocks alternate inside a chunk: independent MFMA chains.
+        if (hh == 0) {
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      if (c + 1 < 4) {
+          for (int b = 0; b < NDB; ++b)
+            vf[1][b] = *reinterpret_cast<const u32x4 *>(vs + (b * 32 + r32) * kAttBKV +
+                                                        (((2 * (2 * kb + 1) + grp) ^ vfx) * 8));
+        }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int b = 0; b < NDB; ++b)
-          vf[(c + 1) & 1][b] =
-              *reinterpret_cast<const u32x4 *>(vs + (b * 32 + r32) * kAttBKV + (((2 * (c + 1) + grp) ^ vfx) * 8));
-      }
-      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int b = 0; b < NDB; ++b) o_acc[b] = mfma32(vf[c & 1][b], pf[c], o_acc[b]);
-      __builtin_amdgcn_sched_barrier(0);
+          for (int j = 0; j < QB; ++j) o_acc[j][b] = mfma32(vf[hh][b], pf[j][hh], o_acc[j][b]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
   }
 
   wait_vmcnt<0>();                            // drain filler / past-the-end loads before LDS is released
-  float l_tot;
-  if (SUM_BY_MFMA) {                          // accumulator row head_dim of O^T: lane group (row % 8) / 4, register (row / 8) * 4 + row % 4
-    constexpr int ROW = HD % 32;
-    l_tot = __shfl(o_acc[NDB - 1][(ROW / 8) * 4 + (ROW % 4)], r32 + 32 * ((ROW % 8) / 4), 64);
-  } else {
-    l_tot = l_run + __shfl_xor(l_run, 32, 64);
-  }
-  const float inv = 1.0f / l_tot;
-  const int q = q0 + wave * 32 + r32;
-  if (q < n) {
-    uint16_t *orow = out + ((size_t)f * n + q) * D + h * HD;
 #pragma unroll
-    for (int b = 0; b < NDB; ++b)
+  for (int j = 0; j < QB; ++j) {
+    float l_tot;
+    if (SUM_BY_MFMA) {                        // accumulator row head_dim of O^T: lane group (row % 8) / 4, register (row / 8) * 4 + row % 4
+      constexpr int ROW = HD % 32;
+      l_tot = __shfl(o_acc[j][NDB - 1][(ROW / 8) * 4 + (ROW % 4)], r32 + 32 * ((ROW % 8) / 4), 64);
+    } else {
+      l_tot = l_run[j] + __shfl_xor(l_run[j], 32, 64);
+    }
+    const float inv = 1.0f / l_tot;
+    const int q = q0 + (wave * QB + j) * 32 + r32;
+    if (q < n) {
+      uint16_t *orow = out + ((size_t)f * n + q) * D + h * HD;
 #pragma unroll
-      for (int qd = 0; qd < 4; ++qd) {
-        const int d = b * 32 + qd * 8 + grp * 4;
-        if (d < HD) {
-          uint2 o;
-          o.x = cvt_pk_bf16(o_acc[b][qd * 4 + 0] * inv, o_acc[b][qd * 4 + 1] * inv);
-          o.y = cvt_pk_bf16(o_acc[b][qd * 4 + 2] * inv, o_acc[b][qd * 4 + 3] * inv);
-          *reinterpret_cast<uint2 *>(orow + d) = o;
+      for (int b = 0; b < NDB; ++b)
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+          const int d = b * 32 + qd * 8 + grp * 4;
+          if (d < HD) {
+            uint2 o;
+            o.x = cvt_pk_bf16(o_acc[j][b][qd * 4 + 0] * inv, o_acc[j][b][qd * 4 + 1] * inv);
+            o.y = cvt_pk_bf16(o_acc[j][b][qd * 4 + 2] * inv, o_acc[j][b][qd * 4 + 3] * inv);
+            *reinterpret_cast<uint2 *>(orow + d) = o;
+          }
         }
-      }
+    }
   }
 }
 
@@ -1579,16 +1611,27 @@ int launch_attention_uniform(const uint16_t *qkv, int n_frames, int len, int n_h
   if (n_frames <= 0 || len <= 0) return ET_OK;
   const int Lpad = (len + 63) / 64 * 64;
   const dim3 tgrid(Lpad / 64, n_heads, n_frames), agrid((len + kAttBQ - 1) / kAttBQ, n_heads, n_frames);
+  const dim3 agrid2((len + 2 * kAttBQ - 1) / (2 * kAttBQ), n_heads, n_frames);
+  // two query blocks per wavefront (half the LDS reads and loads per query) when that still leaves
+  // every workgroup slot of the chip (2 per compute unit) with work
+  static int n_cu = 0;
+  if (n_cu == 0) {
+    int dev = 0;
+    ET_HIP(hipGetDevice(&dev));
+    ET_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+    if (n_cu <= 0) n_cu = 256;
+  }
+  const bool wide = (long long)agrid2.x * agrid2.y * agrid2.z >= 2LL * n_cu;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)head_dim);
 #define ET_ATT(HD)                                                                                        \
   case HD:                                                                                                \
     hipLaunchKernelGGL(transpose_v_kernel<HD>, tgrid, dim3(256), 0, s, qkv, len, n_heads, Lpad, vt_ws);   \
-    if (HD == 72 && getenv("ET_ATT_VARIANT"))                                                               \
-      hipLaunchKernelGGL((attention_dma_kernel<72, 2, 3>), agrid, dim3(kAttWaves * 64), 0, s, qkv, vt_ws, len, \
-                         n_heads, Lpad, scale_log2, out);                                                 \
+    if (HD <= 80 && wide)                                                                                 \
+      hipLaunchKernelGGL((attention_dma_kernel<HD, 3, (HD <= 80 ? 2 : 1), (HD <= 96 ? 2 : 1)>), agrid2, dim3(kAttWaves * 64), 0, s,  \
+                         qkv, vt_ws, len, n_heads, Lpad, scale_log2, out);                                \
     else                                                                                                  \
-    hipLaunchKernelGGL((attention_dma_kernel<HD, 3>), agrid, dim3(kAttWaves * 64), 0, s, qkv, vt_ws, len,      \
-                       n_heads, Lpad, scale_log2, out);                                                   \
+      hipLaunchKernelGGL((attention_dma_kernel<HD, 3, 1, (HD <= 96 ? 2 : 1)>), agrid, dim3(kAttWaves * 64), 0, s,   \
+                         qkv, vt_ws, len, n_heads, Lpad, scale_log2, out);                                \
     break;
   switch (head_dim) {
     ET_ATT(16) ET_ATT(32) ET_ATT(64) ET_ATT(72) ET_ATT(80) ET_ATT(96) ET_ATT(128)

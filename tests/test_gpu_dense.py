@@ -140,7 +140,9 @@ def test_attention_matches_oracle(n_heads, hd):
 @pytest.mark.parametrize("n_heads,hd,n_frames,length", [(16, 72, 3, 729), (16, 72, 5, 364), (16, 72, 2, 182),
                                                         (4, 16, 8, 64), (4, 16, 2, 32), (2, 64, 3, 130),
                                                         (2, 128, 2, 70), (3, 32, 2, 1), (2, 80, 2, 129),
-                                                        (2, 96, 2, 65), (16, 72, 1, 218)])
+                                                        (2, 96, 2, 65), (16, 72, 1, 218),
+                                                        # enough workgroups for two query blocks per wavefront
+                                                        (16, 72, 11, 729), (4, 16, 130, 70), (2, 80, 90, 300)])
 def test_attention_uniform_matches_oracle(n_heads, hd, n_frames, length):
     rng = np.random.default_rng(n_heads * hd + length)
     D, rows = n_heads * hd, n_frames * length
@@ -166,7 +168,8 @@ def test_attention_uniform_moving_maxima(order):
     2^8; these inputs make the row maxima climb by far more than that from tile to tile (rising), never
     move after the first tile (falling), start far below zero (negative_first), or jump in the last,
     partly filled tile (spike_last)."""
-    n_heads, hd, n_frames, length = 16, 72, 2, 729
+    n_heads, hd, length = 16, 72, 729
+    n_frames = 11 if order in ("rising", "spike_last") else 2    # 11 frames: two query blocks per wavefront
     rng = np.random.default_rng({"rising": 1, "falling": 2, "negative_first": 3, "spike_last": 4}[order])
     D, rows = n_heads * hd, n_frames * length
     _, qkv = _bf(rng, (rows, 3 * D))
