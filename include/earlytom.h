@@ -264,9 +264,10 @@ int et_attention(const uint16_t *qkv_dev, const int32_t *cu_tokens_dev, int32_t 
                  void *hip_stream);
 
 /* The same attention for frames of equal length `len` (frame f = rows f*len .. f*len+len-1),
- * which is what the hot path runs: V is first transposed per (frame, head) into scratch_dev
- * (et_attention_uniform_scratch_bytes bytes), then K and V^T tiles stream through LDS by
- * direct global -> LDS loads. */
+ * which is what the hot path runs: K and V tiles stream through LDS by direct global -> LDS
+ * loads and the V^T fragments are taken with LDS transpose reads.  scratch_dev / scratch_bytes
+ * are not used any more (et_attention_uniform_scratch_bytes returns 0; NULL is accepted); they
+ * stay in the signature for callers written against the earlier form. */
 int et_attention_uniform(const uint16_t *qkv_dev, int32_t n_frames, int32_t len, int32_t n_heads,
                          int32_t head_dim, void *scratch_dev, size_t scratch_bytes, uint16_t *out_dev,
                          void *hip_stream);

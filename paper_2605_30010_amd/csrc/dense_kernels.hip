@@ -1106,79 +1106,52 @@ __global__ __launch_bounds__(kAttWaves * 64) void attention_kernel(
 // ---------------------------------------------------------------------------------------
 // Fast attention path for frames of equal length (always the case on the hot path).
 //
-// Step 1, transpose_v_kernel: V^T per (frame, head) as vt[frame][head][d][Lpad], Lpad = length
-// rounded up to 64, tokens past the length written as zeros.  MFMA wants the contraction index
-// (the key) contiguous per lane for the P V product; doing the transpose once per layer in a
-// bandwidth-bound pass removes all 2-byte LDS scatter writes from the attention loop.
-//
-// Step 2, attention_dma_kernel: same transposed online-softmax scheme as attention_kernel, but
-// K and V^T tiles are brought in by direct global -> LDS loads, double buffered, one barrier per
-// 64-key tile.  K rows sit back to back in LDS (row stride = head_dim * 2 bytes; 144 bytes for
-// head_dim 72 spreads 16-byte reads of consecutive rows over all banks); V^T rows are 128 bytes
-// (keys permuted inside each 16-key chunk, see transpose_v_kernel) with the 16-byte slots
-// XOR-swizzled by (row >> 1) & 7.  When head_dim is not a multiple of 16
-// the last contraction chunk of a K row runs 16 bytes into the next row; those values meet the
-// zero padding of Q, and the data behind the last row is the (finite) V^T tile.
+// attention_dma_kernel: same transposed online-softmax scheme as attention_kernel, but K and V
+// tiles are brought in by direct global -> LDS loads, three stages, one barrier per 64-key tile.
+// Both tiles sit in LDS as they are in memory, rows back to back (row stride = head_dim * 2
+// bytes; 144 bytes for head_dim 72 spreads 16-byte reads of consecutive rows over all banks).
+// MFMA wants the contraction index (the key) contiguous per lane for the P V product, i.e. V^T:
+// its fragments are taken from the row-major tile with the LDS transpose read of gfx950
+// (ds_read_b64_tr_b16), two per fragment, so V is never transposed in memory.  When head_dim is
+// not a multiple of 16 the last contraction chunk of a K row runs 16 bytes into the next row;
+// those slots carry the reference maximum (see below).  O^T row blocks past head_dim read
+// whatever follows a V row; that only reaches accumulator rows >= head_dim, which are never
+// stored (MFMA output rows are independent).
 // ---------------------------------------------------------------------------------------
-template <int HD>
-__global__ __launch_bounds__(256) void transpose_v_kernel(const uint16_t *__restrict__ qkv, int n, int n_heads,
-                                                          int Lpad, uint16_t *__restrict__ vt) {
-  constexpr int NCH = HD / 8;
-  constexpr int TROW = HD + 2;                          // 2-byte pad: column reads spread over banks
-  __shared__ uint16_t tile[64 * TROW];
-  const int f = blockIdx.z, h = blockIdx.y, t0 = blockIdx.x * 64;
-  const int D = n_heads * HD, ld = 3 * D;
-  const uint16_t *vbase = qkv + (size_t)f * n * ld + 2 * D + h * HD;
-  for (int i = threadIdx.x; i < 64 * NCH; i += 256) {
-    const int tok = i / NCH, ch = i % NCH;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (t0 + tok < n) v = *reinterpret_cast<const uint4 *>(vbase + (size_t)(t0 + tok) * ld + ch * 8);
-    uint32_t *dst = reinterpret_cast<uint32_t *>(tile + tok * TROW + ch * 8);   // 4-byte aligned: TROW even
-    dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
-  }
-  __syncthreads();
-  uint16_t *obase = vt + ((size_t)(f * n_heads + h) * HD) * Lpad + t0;
-  for (int i = threadIdx.x; i < HD * 8; i += 256) {
-    const int d = i / 8, tc = i % 8;
-    // 8 output positions tc*8 .. tc*8+7 of the row; position p of a 16-key chunk holds key
-    // (p & 3) + 4 * (p >> 3) + 8 * ((p >> 2) & 1): the order in which the S^T accumulator of the
-    // attention kernel presents keys to one lane group, so that its 8 keys are one 16-byte read
-    uint32_t w[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int p0 = (tc & 1) * 8 + 2 * j, p1 = p0 + 1;
-      const int k0 = (tc >> 1) * 16 + (p0 & 3) + 4 * (p0 >> 3) + 8 * ((p0 >> 2) & 1);
-      const int k1 = (tc >> 1) * 16 + (p1 & 3) + 4 * (p1 >> 3) + 8 * ((p1 >> 2) & 1);
-      const uint32_t lo = tile[k0 * TROW + d], hi = tile[k1 * TROW + d];
-      w[j] = lo | (hi << 16);
-    }
-    *reinterpret_cast<uint4 *>(obase + (size_t)d * Lpad + tc * 8) = make_uint4(w[0], w[1], w[2], w[3]);
-  }
+// LDS transpose read: every lane of a 16-lane group supplies the address of four consecutive 16-bit
+// elements; lane j of the group receives element j % 4 of the lanes j / 4, 4 + j / 4, 8 + j / 4 and
+// 12 + j / 4 (layout checked on the device).  With lane s of a group pointing at row s / 4, columns
+// 4 (s % 4) .. + 3 of a row-major matrix, lane j gets column j of four consecutive rows.
+__device__ __forceinline__ uint2 lds_read_tr16(const uint16_t *p) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  typedef short s16x4 __attribute__((ext_vector_type(4)));
+  const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)p);
+  return __builtin_bit_cast(uint2, v);
+#else
+  return make_uint2(0u, 0u);
+#endif
 }
 
 template <int HD, int STAGES, int QB, int MINB>
 __global__ __launch_bounds__(kAttWaves * 64, MINB) void attention_dma_kernel(
-    const uint16_t *__restrict__ qkv, const uint16_t *__restrict__ vt, int n, int n_heads, int Lpad,
-    float scale_log2, uint16_t *__restrict__ out) {
+    const uint16_t *__restrict__ qkv, int n, int n_heads, float scale_log2, uint16_t *__restrict__ out) {
   constexpr int NC = (HD + 15) / 16;
   constexpr int NDB = (HD + 31) / 32;
   constexpr int K_LOADS = HD / 8;            // 1 KiB loads per K tile  (64 keys * HD * 2 bytes)
-  constexpr int V_LOADS = HD / 8;            // 1 KiB loads per V^T tile (HD rows * 128 bytes)
+  constexpr int V_LOADS = HD / 8;            // 1 KiB loads per V tile
   constexpr int LOADS = (K_LOADS + V_LOADS + kAttWaves - 1) / kAttWaves;   // per wavefront per tile
-  // When head_dim is not a multiple of 32 the last O^T row block has spare rows: V^T row head_dim
-  // is then a row of ones kept behind each stage's V^T tile, and accumulator row head_dim of O^T
-  // is the softmax denominator (the sum of the bf16-rounded probabilities, exactly what the
-  // numerator used), for free.
+  // When head_dim is not a multiple of 32 the last O^T row block has spare rows: the V^T fragment
+  // of row head_dim is overridden with ones, and accumulator row head_dim of O^T is the softmax
+  // denominator (the sum of the bf16-rounded probabilities, exactly what the numerator used), for free.
   constexpr bool SUM_BY_MFMA = (HD % 32) != 0;
   // When head_dim is not a multiple of 16 the Q K^T contraction has spare slots: slot head_dim of
   // every K row is read as 1 and slot head_dim of a query holds minus its reference maximum, so
   // the MFMA delivers s - m_ref.  Otherwise the subtraction is a vector instruction per logit.
   constexpr bool REF_IN_PAD = (HD % 16) != 0;
-  constexpr int ONES = SUM_BY_MFMA ? kAttBKV : 0;
-  constexpr int K_ELEMS = kAttBKV * HD, V_ELEMS = HD * kAttBKV;
-  constexpr int STAGE = K_ELEMS + V_ELEMS + ONES;
-  // tail pad: O^T row blocks past head_dim read rows behind the V^T tile; whatever they hold only
-  // reaches accumulator rows >= head_dim, which are never stored (MFMA output rows are independent).
+  constexpr int K_ELEMS = kAttBKV * HD, V_ELEMS = kAttBKV * HD;
+  constexpr int STAGE = K_ELEMS + V_ELEMS;
+  // tail pad: the last V row's fragments of row blocks past head_dim read up to NDB * 32 - HD elements
+  // behind the tile (rounded up generously).
   // The last 512 elements absorb the filler loads that keep every wavefront at LOADS loads per tile.
   constexpr int PAD = (NDB * 32 - HD) * kAttBKV + 512;
   __shared__ __align__(16) uint16_t lds[STAGES * STAGE + PAD];
@@ -1190,7 +1163,7 @@ __global__ __launch_bounds__(kAttWaves * 64, MINB) void attention_dma_kernel(
   const int D = n_heads * HD, ld = 3 * D;
   const uint16_t *qbase = qkv + (size_t)f * n * ld + h * HD;
   const uint16_t *kbase = qbase + D;
-  const uint16_t *vtb = vt + ((size_t)(f * n_heads + h) * HD) * Lpad;
+  const uint16_t *vbase = kbase + D;
   const int n_tiles = (n + kAttBKV - 1) / kAttBKV;
 
   // loads j = wave, wave + 4, ... of a tile belong to this wavefront; ids past the tile's 2*HD/8
@@ -1214,14 +1187,16 @@ __global__ __launch_bounds__(kAttWaves * 64, MINB) void attention_dma_kernel(
       src_last[j] = kbase + (size_t)kl * ld + ch * 8;
       dst_off[j] = ld_id * 512;
       step[j] = kAttBKV * ld;
-    } else if (ld_id < K_LOADS + V_LOADS) {
-      const int q = (ld_id - K_LOADS) * 64 + lane, d = q >> 3, slot = q & 7;
-      cur[j] = vtb + (size_t)d * Lpad + ((slot ^ ((d >> 1) & 7)) * 8);
-      src_last[j] = cur[j] + (n_tiles - 1) * kAttBKV;
+    } else if (ld_id < K_LOADS + V_LOADS) {             // V rows exactly like K rows
+      const int q = (ld_id - K_LOADS) * 64 + lane, key = q / (HD / 8), ch = q % (HD / 8);
+      int kl = (n_tiles - 1) * kAttBKV + key;
+      if (kl >= n) kl = n - 1;
+      cur[j] = vbase + (size_t)key * ld + ch * 8;
+      src_last[j] = vbase + (size_t)kl * ld + ch * 8;
       dst_off[j] = K_ELEMS + (ld_id - K_LOADS) * 512;
-      step[j] = kAttBKV;
+      step[j] = kAttBKV * ld;
     } else {
-      cur[j] = src_last[j] = vtb + lane * 8;
+      cur[j] = src_last[j] = kbase + lane * 8;
       dst_off[j] = STAGES * STAGE + PAD - 512;
       step[j] = 0;
       filler[j] = true;
@@ -1246,10 +1221,6 @@ __global__ __launch_bounds__(kAttWaves * 64, MINB) void attention_dma_kernel(
 #pragma unroll
   for (int st = 0; st < STAGES - 1; ++st) issue(st);
 
-  if (SUM_BY_MFMA && tid < STAGES * (kAttBKV / 2)) {   // the rows of ones (the loop's first barrier orders them)
-    const int st = tid / (kAttBKV / 2), j = tid % (kAttBKV / 2);
-    reinterpret_cast<uint32_t *>(lds + st * STAGE + K_ELEMS + V_ELEMS)[j] = 0x3F803F80u;
-  }
   // Q is scaled by log2(e) / sqrt(head_dim) once, here, and rounded back to bf16: the logits leave
   // the MFMA already in the exponent's units.  A wavefront owns QB blocks of 32 queries: every K and
   // V^T fragment it reads from LDS feeds QB MFMAs.
@@ -1284,7 +1255,17 @@ __global__ __launch_bounds__(kAttWaves * 64, MINB) void attention_dma_kernel(
 #pragma unroll
   for (int j = 0; j < QB; ++j) m_ref[j] = l_run[j] = 0.f;
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  const int vfx = (r32 >> 1) & 7;              // swizzle of this lane's V^T rows (32 b + r32: same low bits)
+  // V^T fragment of 16-key chunk c, row block b = two transpose reads.  P's k-slots 0-3 of lane group
+  // grp are keys 16 c + 4 grp + (0..3), slots 4-7 keys 16 c + 8 + 4 grp + (0..3); lane s of a 16-lane
+  // group points at key + s / 4, features 32 b + 16 (group % 2) + 4 (s % 4) .. + 3.
+  const int vr_off = (4 * grp + ((lane & 15) >> 2)) * HD + ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
+  auto read_vfrag = [&](const uint16_t *vs, int c, int b) -> u32x4 {
+    const uint16_t *p = vs + vr_off + c * 16 * HD + b * 32;
+    const uint2 lo = lds_read_tr16(p), hi = lds_read_tr16(p + 8 * HD);
+    u32x4 v = u32x4{lo.x, lo.y, hi.x, hi.y};
+    if (SUM_BY_MFMA && b == NDB - 1 && r32 == HD % 32) v = u32x4{0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+    return v;
+  };
 
   int stage = 0;
   for (int t = 0; t < n_tiles; ++t) {
@@ -1320,7 +1301,7 @@ __global__ __launch_bounds__(kAttWaves * 64, MINB) void attention_dma_kernel(
       u32x4 vf[2][NDB];
 #pragma unroll
       for (int b = 0; b < NDB; ++b)
-        vf[0][b] = *reinterpret_cast<const u32x4 *>(vs + (b * 32 + r32) * kAttBKV + (((4 * kb + grp) ^ vfx) * 8));
+        vf[0][b] = read_vfrag(vs, 2 * kb, b);
       __builtin_amdgcn_sched_barrier(0);
       float mx[QB];
 #pragma unroll
@@ -1386,16 +1367,13 @@ __global__ __launch_bounds__(kAttWaves * 64, MINB) void attention_dma_kernel(
           pf[j][hh] = v;
         }
       }
-      // O^T += V^T P^T.  P's k-slots of 16-key chunk c, lane group grp, are keys 16c + 4 grp + (0..3) and
-      // 16c + 8 + 4 grp + (0..3); transpose_v_kernel stored exactly those 8 keys in 16-byte slot
-      // 2c + grp of the V^T row.  Row blocks and query blocks are independent MFMA chains.
+      // O^T += V^T P^T; row blocks and query blocks are independent MFMA chains.
 #pragma unroll
       for (int hh = 0; hh < 2; ++hh) {
         if (hh == 0) {
 #pragma unroll
           for (int b = 0; b < NDB; ++b)
-            vf[1][b] = *reinterpret_cast<const u32x4 *>(vs + (b * 32 + r32) * kAttBKV +
-                                                        (((2 * (2 * kb + 1) + grp) ^ vfx) * 8));
+            vf[1][b] = read_vfrag(vs, 2 * kb + 1, b);
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -1599,18 +1577,12 @@ int launch_attention(const uint16_t *qkv, const int32_t *cu, int n_frames, int m
   return ET_OK;
 }
 
-size_t attention_uniform_workspace_bytes(int n_frames, int len, int n_heads, int head_dim) {
-  const size_t Lpad = (size_t)(len + 63) / 64 * 64;
-  return (size_t)n_frames * n_heads * head_dim * Lpad * sizeof(uint16_t);
-}
-
 bool attention_uniform_supported(int head_dim) { return head_dim == 72 || head_dim == 64 || head_dim == 128 || head_dim == 16 || head_dim == 32 || head_dim == 80 || head_dim == 96; }
 
 int launch_attention_uniform(const uint16_t *qkv, int n_frames, int len, int n_heads, int head_dim,
-                             uint16_t *vt_ws, uint16_t *out, hipStream_t s) {
+                             uint16_t *out, hipStream_t s) {
   if (n_frames <= 0 || len <= 0) return ET_OK;
-  const int Lpad = (len + 63) / 64 * 64;
-  const dim3 tgrid(Lpad / 64, n_heads, n_frames), agrid((len + kAttBQ - 1) / kAttBQ, n_heads, n_frames);
+  const dim3 agrid((len + kAttBQ - 1) / kAttBQ, n_heads, n_frames);
   const dim3 agrid2((len + 2 * kAttBQ - 1) / (2 * kAttBQ), n_heads, n_frames);
   // two query blocks per wavefront (half the LDS reads and loads per query) when that still leaves
   // every workgroup slot of the chip (2 per compute unit) with work
@@ -1625,13 +1597,12 @@ int launch_attention_uniform(const uint16_t *qkv, int n_frames, int len, int n_h
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)head_dim);
 #define ET_ATT(HD)                                                                                        \
   case HD:                                                                                                \
-    hipLaunchKernelGGL(transpose_v_kernel<HD>, tgrid, dim3(256), 0, s, qkv, len, n_heads, Lpad, vt_ws);   \
     if (HD <= 80 && wide)                                                                                 \
-      hipLaunchKernelGGL((attention_dma_kernel<HD, 3, (HD <= 80 ? 2 : 1), (HD <= 96 ? 2 : 1)>), agrid2, dim3(kAttWaves * 64), 0, s,  \
-                         qkv, vt_ws, len, n_heads, Lpad, scale_log2, out);                                \
+      hipLaunchKernelGGL((attention_dma_kernel<HD, 3, (HD <= 80 ? 2 : 1), (HD <= 96 ? 2 : 1)>), agrid2,   \
+                         dim3(kAttWaves * 64), 0, s, qkv, len, n_heads, scale_log2, out);                 \
     else                                                                                                  \
       hipLaunchKernelGGL((attention_dma_kernel<HD, 3, 1, (HD <= 96 ? 2 : 1)>), agrid, dim3(kAttWaves * 64), 0, s,   \
-                         qkv, vt_ws, len, n_heads, Lpad, scale_log2, out);                                \
+                         qkv, len, n_heads, scale_log2, out);                                             \
     break;
   switch (head_dim) {
     ET_ATT(16) ET_ATT(32) ET_ATT(64) ET_ATT(72) ET_ATT(80) ET_ATT(96) ET_ATT(128)

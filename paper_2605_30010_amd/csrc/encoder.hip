@@ -81,7 +81,7 @@ static int upload_f32(et_encoder *e, const float *src, int n, int n_pad, float *
 }
 
 struct EncWs {
-  uint16_t *x, *xn, *qkv, *att, *hid, *vt;
+  uint16_t *x, *xn, *qkv, *att, *hid;
   int32_t *cu_full;
   void *merge;
   void *score_ws;      // row statistics and per-head column sums of the attention-received scores
@@ -105,7 +105,6 @@ static EncWs carve_encoder(const et_encoder *e, void *ws, int T) {
   w.att = static_cast<uint16_t *>(take(R * e->D * 2));
   const size_t hid_cols = (size_t)(e->Mhp > e->Kp_pad ? e->Mhp : e->Kp_pad);
   w.hid = static_cast<uint16_t *>(take(R * hid_cols * 2));
-  w.vt = static_cast<uint16_t *>(take(attention_uniform_workspace_bytes(T, e->L, e->cfg.n_heads, e->hd)));
   w.cu_full = static_cast<int32_t *>(take((size_t)(T + 1) * 4));
   w.merge = take(carve_merge(nullptr, T, e->L, e->D).bytes);
   w.score_ws = take(attention_scores_workspace_bytes(T, e->L, e->cfg.n_heads));
@@ -128,7 +127,6 @@ static EncWs frames_from(const et_encoder *e, const EncWs &w, int f0, int len) {
   v.qkv += r0 * 3 * e->D;
   v.att += r0 * e->D;
   v.hid += r0 * hid_cols;
-  v.vt += attention_uniform_workspace_bytes(f0, len, e->cfg.n_heads, e->hd) / sizeof(uint16_t);
   return v;
 }
 
@@ -145,7 +143,7 @@ static int run_block(et_encoder *e, const LayerDev &lw, const EncWs &w, int rows
   if (ragged) {   // frames of different lengths (decoupled selection): the general kernel
     ET_TIMED(ET_K_ATTENTION, launch_attention(w.qkv, cu, n_frames, max_len, c.n_heads, e->hd, w.att, s));
   } else {        // every frame has max_len tokens
-    ET_TIMED(ET_K_ATTENTION, launch_attention_uniform(w.qkv, n_frames, max_len, c.n_heads, e->hd, w.vt, w.att, s));
+    ET_TIMED(ET_K_ATTENTION, launch_attention_uniform(w.qkv, n_frames, max_len, c.n_heads, e->hd, w.att, s));
   }
   g = GemmArgs{w.att, D, lw.wo, lw.bo, w.x, D, rows, w.x, D, rows, D, D, EPI_BIAS_RES};
   ET_TIMED(ET_K_GEMM_OUT, launch_gemm(g, s));
@@ -614,15 +612,11 @@ int et_attention(const uint16_t *qkv_dev, const int32_t *cu_tokens_dev, int32_t 
                           static_cast<hipStream_t>(hip_stream));
 }
 
-size_t et_attention_uniform_scratch_bytes(int32_t n_frames, int32_t len, int32_t n_heads, int32_t head_dim) {
-  if (n_frames < 1 || len < 1 || n_heads < 1 || !head_dim_supported(head_dim)) return 0;
-  return attention_uniform_workspace_bytes(n_frames, len, n_heads, head_dim);
-}
+size_t et_attention_uniform_scratch_bytes(int32_t, int32_t, int32_t, int32_t) { return 0; }
 
 int et_attention_uniform(const uint16_t *qkv_dev, int32_t n_frames, int32_t len, int32_t n_heads,
-                         int32_t head_dim, void *scratch_dev, size_t scratch_bytes, uint16_t *out_dev,
-                         void *hip_stream) {
-  ET_REQUIRE(qkv_dev && scratch_dev && out_dev, "a pointer argument is NULL");
+                         int32_t head_dim, void *, size_t, uint16_t *out_dev, void *hip_stream) {
+  ET_REQUIRE(qkv_dev && out_dev, "a pointer argument is NULL");
   ET_REQUIRE(n_frames >= 0 && len >= 0 && n_heads >= 1, "n_frames/len/n_heads out of range");
   if (!head_dim_supported(head_dim)) {
     set_error("head_dim = %d is not instantiated (16, 32, 64, 72, 80, 96, 128)", head_dim);
@@ -630,13 +624,8 @@ int et_attention_uniform(const uint16_t *qkv_dev, int32_t n_frames, int32_t len,
   }
   ET_REQUIRE((double)n_frames * len * n_heads * head_dim * 3 < 2.0e9, "qkv exceeds 2^31 elements");
   if (n_frames == 0 || len == 0) return ET_OK;
-  const size_t need = attention_uniform_workspace_bytes(n_frames, len, n_heads, head_dim);
-  if (scratch_bytes < need) {
-    set_error("scratch of %zu bytes is smaller than the %zu needed", scratch_bytes, need);
-    return ET_ERR_WORKSPACE;
-  }
-  return launch_attention_uniform(qkv_dev, n_frames, len, n_heads, head_dim, static_cast<uint16_t *>(scratch_dev),
-                                  out_dev, static_cast<hipStream_t>(hip_stream));
+  return launch_attention_uniform(qkv_dev, n_frames, len, n_heads, head_dim, out_dev,
+                                  static_cast<hipStream_t>(hip_stream));
 }
 
 int et_gemm_bf16(const uint16_t *a_dev, const uint16_t *w_dev, const float *bias_dev, const uint16_t *res_dev,

@@ -214,10 +214,9 @@ int gemm_config_count();
 int launch_attention(const uint16_t *qkv, const int32_t *cu, int n_frames, int max_len, int n_heads,
                      int head_dim, uint16_t *out, hipStream_t s);
 bool head_dim_supported(int hd);
-// Equal-length frames: needs attention_uniform_workspace_bytes() of scratch for V^T.
-size_t attention_uniform_workspace_bytes(int n_frames, int len, int n_heads, int head_dim);
+// Equal-length frames (frame f = rows f * len .. f * len + len - 1).
 int launch_attention_uniform(const uint16_t *qkv, int n_frames, int len, int n_heads, int head_dim,
-                             uint16_t *vt_ws, uint16_t *out, hipStream_t s);
+                             uint16_t *out, hipStream_t s);
 
 // score_kernels.hip: attention received per token, equal-length frames
 size_t attention_scores_workspace_bytes(int n_frames, int L, int n_heads);
