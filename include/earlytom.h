@@ -112,6 +112,10 @@ size_t et_workspace_bytes(const et_encoder *enc, int32_t T);
  *                opens one).  +INFINITY makes every frame its own segment.  NaN is rejected.
  *   keep_ratio   in (0, 1]; k = et_keep_count(L, keep_ratio) tokens are kept per output frame.
  * Synchronises `hip_stream` once in the middle (to learn N) and once before returning.
+ * Blocks that run on fewer than 8192 rows (those after the selection) have their weights read
+ * ahead by small kernels on a stream the encoder owns (default priority), released by an event on
+ * `hip_stream` and joined to it before the call returns; they read encoder memory only.  One
+ * encoder therefore serves one encode call at a time.
  * Errors: INVALID_ARG (incl. T < 1 or T > max_frames), WORKSPACE, HIP. */
 int et_encode_clip(et_encoder *enc, const float *frames_dev, int32_t T, int32_t merge_layer,
                    float sim_threshold, float keep_ratio, void *workspace_dev,
