@@ -1106,8 +1106,9 @@ __global__ __launch_bounds__(kAttWaves * 64) void attention_kernel(
 // ---------------------------------------------------------------------------------------
 // Fast attention path for frames of equal length (always the case on the hot path).
 //
-// attention_dma_kernel: same transposed online-softmax scheme as attention_kernel, but K and V
-// tiles are brought in by direct global -> LDS loads, three stages, one barrier per 64-key tile.
+// attention_dma_kernel: same transposed online-softmax scheme as attention_kernel, but the K tile
+// is brought in by direct global -> LDS loads and the V tile through registers, one tile ahead,
+// two LDS stages, one barrier per 64-key tile.
 // Both tiles sit in LDS as they are in memory, rows back to back (row stride = head_dim * 2
 // bytes; 144 bytes for head_dim 72 spreads 16-byte reads of consecutive rows over all banks).
 // MFMA wants the contraction index (the key) contiguous per lane for the P V product, i.e. V^T:
@@ -1132,14 +1133,14 @@ __device__ __forceinline__ uint2 lds_read_tr16(const uint16_t *p) {
 #endif
 }
 
-template <int HD, int STAGES, int QB, int MINB>
+template <int HD, int QB, int MINB>
 __global__ __launch_bounds__(kAttWaves * 64, MINB) void attention_dma_kernel(
     const uint16_t *__restrict__ qkv, int n, int n_heads, float scale_log2, uint16_t *__restrict__ out) {
   constexpr int NC = (HD + 15) / 16;
   constexpr int NDB = (HD + 31) / 32;
-  constexpr int K_LOADS = HD / 8;            // 1 KiB loads per K tile  (64 keys * HD * 2 bytes)
-  constexpr int V_LOADS = HD / 8;            // 1 KiB loads per V tile
-  constexpr int LOADS = (K_LOADS + V_LOADS + kAttWaves - 1) / kAttWaves;   // per wavefront per tile
+  constexpr int STAGES = 2;
+  constexpr int T_LOADS = HD / 8;            // 1 KiB pieces of a K (or V) tile: 64 keys * HD * 2 bytes
+  constexpr int PW = (T_LOADS + kAttWaves - 1) / kAttWaves;   // pieces per wavefront
   // When head_dim is not a multiple of 32 the last O^T row block has spare rows: the V^T fragment
   // of row head_dim is overridden with ones, and accumulator row head_dim of O^T is the softmax
   // denominator (the sum of the bf16-rounded probabilities, exactly what the numerator used), for free.
@@ -1152,8 +1153,7 @@ __global__ __launch_bounds__(kAttWaves * 64, MINB) void attention_dma_kernel(
   constexpr int STAGE = K_ELEMS + V_ELEMS;
   // tail pad: the last V row's fragments of row blocks past head_dim read up to NDB * 32 - HD elements
   // behind the tile (rounded up generously).
-  // The last 512 elements absorb the filler loads that keep every wavefront at LOADS loads per tile.
-  constexpr int PAD = (NDB * 32 - HD) * kAttBKV + 512;
+  constexpr int PAD = (NDB * 32 - HD) * kAttBKV + 64;
   __shared__ __align__(16) uint16_t lds[STAGES * STAGE + PAD];
 
   const int f = blockIdx.z, h = blockIdx.y, q0 = blockIdx.x * (kAttBQ * QB);
@@ -1166,60 +1166,55 @@ __global__ __launch_bounds__(kAttWaves * 64, MINB) void attention_dma_kernel(
   const uint16_t *vbase = kbase + D;
   const int n_tiles = (n + kAttBKV - 1) / kAttBKV;
 
-  // loads j = wave, wave + 4, ... of a tile belong to this wavefront; ids past the tile's 2*HD/8
-  // loads are fillers (same count for every wavefront, so one vmcnt immediate serves all).
-  // Everything a load needs is prepared here, so that issuing a tile is straight-line code: a
-  // per-lane source pointer that advances by a constant per tile (the last tile has pointers of its
-  // own, with the key rows clamped to the frame; tiles past the end re-read it, unused) and a
-  // wave-uniform destination offset inside the stage.
-  const uint16_t *cur[LOADS], *src_last[LOADS];
-  int dst_off[LOADS], step[LOADS];           // elements into the stage (fillers: into the array); elements per tile
-  bool filler[LOADS];
+  // Pieces j = wave, wave + 4, ... of a tile belong to this wavefront.  The K tile comes in by direct
+  // global -> LDS loads, the V tile through registers (ordinary loads now, written to LDS one tile
+  // later): a compute unit keeps only about 20 KiB of direct loads in flight (measured: the 19th
+  // 1-KiB load of a wavefront, or the 6th of each of four, blocks until the first has landed), and
+  // two workgroups' K and V tiles, 36 KiB per step, kept the wavefronts blocked at the issue.
+  // Per-lane source pointers advance by a constant per tile; the last tile has pointers of its own,
+  // with the key rows clamped to the frame (masked later, in bounds).  V's pointers are K's + D.
+  const uint16_t *cur[PW], *src_last[PW];
+  int dst_off[PW];                           // elements into the K (or V) tile
+  bool mine[PW];
 #pragma unroll
-  for (int j = 0; j < LOADS; ++j) {
+  for (int j = 0; j < PW; ++j) {
     const int ld_id = j * kAttWaves + wave;
-    filler[j] = false;
-    if (ld_id < K_LOADS) {
-      const int q = ld_id * 64 + lane, key = q / (HD / 8), ch = q % (HD / 8);
-      int kl = (n_tiles - 1) * kAttBKV + key;
-      if (kl >= n) kl = n - 1;                         // clamp: masked later, stays in bounds
-      cur[j] = kbase + (size_t)key * ld + ch * 8;
-      src_last[j] = kbase + (size_t)kl * ld + ch * 8;
-      dst_off[j] = ld_id * 512;
-      step[j] = kAttBKV * ld;
-    } else if (ld_id < K_LOADS + V_LOADS) {             // V rows exactly like K rows
-      const int q = (ld_id - K_LOADS) * 64 + lane, key = q / (HD / 8), ch = q % (HD / 8);
-      int kl = (n_tiles - 1) * kAttBKV + key;
-      if (kl >= n) kl = n - 1;
-      cur[j] = vbase + (size_t)key * ld + ch * 8;
-      src_last[j] = vbase + (size_t)kl * ld + ch * 8;
-      dst_off[j] = K_ELEMS + (ld_id - K_LOADS) * 512;
-      step[j] = kAttBKV * ld;
-    } else {
-      cur[j] = src_last[j] = kbase + lane * 8;
-      dst_off[j] = STAGES * STAGE + PAD - 512;
-      step[j] = 0;
-      filler[j] = true;
-    }
+    mine[j] = ld_id < T_LOADS;               // wave-uniform
+    const int q = (mine[j] ? ld_id : 0) * 64 + lane, key = q / (HD / 8), ch = q % (HD / 8);
+    int kl = (n_tiles - 1) * kAttBKV + key;
+    if (kl >= n) kl = n - 1;
+    cur[j] = kbase + (size_t)key * ld + ch * 8;
+    src_last[j] = kbase + (size_t)kl * ld + ch * 8;
+    dst_off[j] = (mine[j] ? ld_id : 0) * 512;
     if (n_tiles == 1) cur[j] = src_last[j];
   }
+  u32x4 vreg[PW];
   int next_tile = 0;
-  auto issue = [&](int stage) {                        // the loads of tile `next_tile` into `stage`
+  auto issue = [&](int stage) {                        // tile `next_tile`: K into `stage`, V into registers
     const int sb = stage * STAGE;
 #pragma unroll
-    for (int j = 0; j < LOADS; ++j) ET_LDS_DMA16(cur[j], lds + (filler[j] ? dst_off[j] : sb + dst_off[j]));
+    for (int j = 0; j < PW; ++j)
+      if (mine[j]) ET_LDS_DMA16(cur[j], lds + sb + dst_off[j]);
+#pragma unroll
+    for (int j = 0; j < PW; ++j)
+      if (mine[j]) vreg[j] = *reinterpret_cast<const u32x4 *>(cur[j] + D);
     ++next_tile;
     if (next_tile == n_tiles - 1) {
 #pragma unroll
-      for (int j = 0; j < LOADS; ++j) cur[j] = src_last[j];
+      for (int j = 0; j < PW; ++j) cur[j] = src_last[j];
     } else if (next_tile < n_tiles - 1) {
 #pragma unroll
-      for (int j = 0; j < LOADS; ++j) cur[j] += step[j];
+      for (int j = 0; j < PW; ++j) cur[j] += kAttBKV * ld;
     }
   };
-
+  auto write_v = [&](int stage) {                      // the V tile in registers -> `stage`
+    uint16_t *vd = lds + stage * STAGE + K_ELEMS + lane * 8;
 #pragma unroll
-  for (int st = 0; st < STAGES - 1; ++st) issue(st);
+    for (int j = 0; j < PW; ++j)
+      if (mine[j]) *reinterpret_cast<u32x4 *>(vd + dst_off[j]) = vreg[j];
+  };
+
+  issue(0);
 
   // Q is scaled by log2(e) / sqrt(head_dim) once, here, and rounded back to bf16: the logits leave
   // the MFMA already in the exponent's units.  A wavefront owns QB blocks of 32 queries: every K and
@@ -1267,16 +1262,16 @@ __global__ __launch_bounds__(kAttWaves * 64, MINB) void attention_dma_kernel(
     return v;
   };
 
-  int stage = 0;
   for (int t = 0; t < n_tiles; ++t) {
-    const int kv0 = t * kAttBKV;
-    wait_vmcnt<(STAGES - 2) * LOADS>();        // tile t has landed (newer tiles may be in flight)
+    const int kv0 = t * kAttBKV, stage = t & 1;
+    wait_vmcnt<0>();                           // tile t: K has landed in LDS, V in registers
+    write_v(stage);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();              // ... for every wavefront; everyone is done with tile t-1
     asm volatile("" ::: "memory");
-    issue(stage == 0 ? STAGES - 1 : stage - 1);
+    if (t + 1 < n_tiles) issue(stage ^ 1);
     const uint16_t *ks = lds + stage * STAGE;
     const uint16_t *vs = ks + K_ELEMS;
-    stage = (stage + 1 == STAGES) ? 0 : stage + 1;
 
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {           // the tile's two 32-key blocks
@@ -1385,7 +1380,6 @@ __global__ __launch_bounds__(kAttWaves * 64, MINB) void attention_dma_kernel(
     }
   }
 
-  wait_vmcnt<0>();                            // drain filler / past-the-end loads before LDS is released
 #pragma unroll
   for (int j = 0; j < QB; ++j) {
     float l_tot;
@@ -1614,10 +1608,10 @@ int launch_attention_uniform(const uint16_t *qkv, int n_frames, int len, int n_h
 #define ET_ATT(HD)                                                                                        \
   case HD:                                                                                                \
     if (HD <= 80 && wide)                                                                                 \
-      hipLaunchKernelGGL((attention_dma_kernel<HD, 3, (HD <= 80 ? 2 : 1), (HD <= 96 ? 2 : 1)>), agrid2,   \
+      hipLaunchKernelGGL((attention_dma_kernel<HD, (HD <= 80 ? 2 : 1), (HD <= 96 ? 2 : 1)>), agrid2,   \
                          dim3(kAttWaves * 64), 0, s, qkv, len, n_heads, scale_log2, out);                 \
     else                                                                                                  \
-      hipLaunchKernelGGL((attention_dma_kernel<HD, 3, 1, (HD <= 96 ? 2 : 1)>), agrid, dim3(kAttWaves * 64), 0, s,   \
+      hipLaunchKernelGGL((attention_dma_kernel<HD, 1, (HD <= 96 ? 2 : 1)>), agrid, dim3(kAttWaves * 64), 0, s,   \
                          qkv, len, n_heads, scale_log2, out);                                             \
     break;
   switch (head_dim) {
