@@ -1162,8 +1162,7 @@ __global__ __launch_bounds__(kAttWaves * 64, MINB) void attention_dma_kernel(
   const int r32 = lane & 31, grp = lane >> 5;
   const int D = n_heads * HD, ld = 3 * D;
   const uint16_t *qbase = qkv + (size_t)f * n * ld + h * HD;
-  const uint16_t *kbase = qbase + D;
-  const uint16_t *vbase = kbase + D;
+  const uint16_t *kbase = qbase + D;                    // (V: + D again)
   const int n_tiles = (n + kAttBKV - 1) / kAttBKV;
 
   // Pieces j = wave, wave + 4, ... of a tile belong to this wavefront.  The K tile comes in by direct
