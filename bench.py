@@ -48,8 +48,10 @@ def bytes_tables(shape, T, N, k):
         ("merge", 0): X + N * L * D * 2 + N * L * 4,
         ("select", 0): N * L * 4 + N * k * 4,
         ("compact", 0): 2 * N * k * D * 2 + N * k * 4,
-        ("layernorm", 0): 2 * T * L * D * 2,
-        ("layernorm", 1): 2 * N * k * D * 2,
+        # row statistics of the LayerNorms folded into the QKV / fc1 GEMMs: the rows are read, one float per row
+        # is written (phase 1 also holds the one real LayerNorm, the final one: slightly under-counted)
+        ("layernorm", 0): T * L * D * 2 + T * L * 4,
+        ("layernorm", 1): N * k * D * 2 + N * k * 4,
         ("im2col", 0): T * shape.channels * shape.image_h * shape.image_w * 4
                        + T * L * ((shape.patch_dim + 63) // 64 * 64) * 2,
     }

@@ -83,7 +83,12 @@ typedef struct {
 /* ---- the hot path ------------------------------------------------------------------- */
 
 /* Pack `weights` for `config` onto the current HIP device.  max_frames bounds T of later
- * calls.  On success *out receives the encoder.  Errors: INVALID_ARG, UNSUPPORTED, ALLOC, HIP. */
+ * calls.  On success *out receives the encoder.  The two LayerNorms of every block are folded
+ * into the QKV and fc1 weights here (gamma scales the weight columns, each folded row is centred
+ * so that the row mean of the input drops out, beta goes into the bias), so the blocks compute
+ * only the row scale 1 / sqrt(var + eps) and apply it in the GEMM epilogue; the folded weights are
+ * rounded to bfloat16 with error diffusion along each row.  Errors: INVALID_ARG, UNSUPPORTED,
+ * ALLOC, HIP. */
 int et_encoder_create(const et_config *config, const et_weights *weights, int32_t max_frames,
                       et_encoder **out);
 void et_encoder_destroy(et_encoder *enc); /* NULL is allowed */

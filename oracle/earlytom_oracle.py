@@ -103,6 +103,29 @@ def round_bf16(a):
     return b.astype(np.uint32).view(np.float32).reshape(f.shape).astype(np.float64)
 
 
+def folded_layernorm_linear(x, gamma, beta, eps, W, bias, round_weights=False):
+    """LayerNorm followed by a linear layer, written with the LayerNorm folded into the weights:
+    LN(x) W^T + b = rstd * (x Wf^T) + c with Wf[n, k] = W[n, k] gamma[k] - mean_k(W[n, :] gamma) and
+    c = W beta + b (the row mean of x drops out because every row of Wf sums to zero).  Equal to
+    layer_norm(x) @ W.T + bias up to rounding; with round_weights the folded weights pass through
+    bfloat16, which is where a device that multiplies the un-normalised x in bfloat16 rounds: along
+    each row, k ascending, with the rounding error of one element carried into the next (so that a
+    rounded row still sums to zero within one step), every step through the nearest float32."""
+    Wg = W * gamma[None, :]
+    Wf = Wg - Wg.mean(axis=1, keepdims=True)
+    if round_weights:
+        carry = np.zeros(Wf.shape[0])
+        out = np.empty_like(Wf)
+        for k in range(Wf.shape[1]):
+            t = Wf[:, k] + carry
+            out[:, k] = round_bf16(t)
+            carry = t - out[:, k]
+        Wf = out.astype(x.dtype)
+    c = W @ beta + bias
+    var = x.var(axis=-1, keepdims=True)
+    return (x @ Wf.T) / np.sqrt(var + eps) + c
+
+
 def attention_received(x, lw, n_heads, eps, storage_bf16=False):
     """Per-token attention score of Sec. 3.3 / Alg. 2 ("attentions A from the vision encoder").
 
@@ -110,17 +133,26 @@ def attention_received(x, lw, n_heads, eps, storage_bf16=False):
     here: the attention a token RECEIVES in the block with weights `lw`, i.e. the column mean of the
     softmax matrix over all queries of its frame, averaged over the heads.  x: [F, n, D] is the
     input of that block.  Returns [F, n]; every row sums to 1.
-    storage_bf16: round the LayerNorm output and q, k to bfloat16 first, the points where the device
-    path stores bfloat16, so that a ranking is decided from the same numbers on both sides."""
+    storage_bf16: where a ranking has to be decided from the same numbers as on a device that stores
+    bfloat16.  True: the LayerNorm output and q, k are rounded to bfloat16.  "folded": the LayerNorm is
+    folded into the projection (folded_layernorm_linear), the folded weights and q, k are rounded."""
     F, n, D = x.shape
     hd = D // n_heads
     dt = x.dtype
-    xn = layer_norm(x, np.asarray(lw["ln1_g"], dt), np.asarray(lw["ln1_b"], dt), eps)
-    if storage_bf16:
-        xn = round_bf16(xn).astype(dt)
-    qk = xn @ np.asarray(lw["wqkv"], dtype=dt)[:2 * D].T + np.asarray(lw["bqkv"], dtype=dt)[:2 * D]
-    if storage_bf16:
+    if isinstance(storage_bf16, str):
+        if storage_bf16 != "folded":
+            raise ValueError("storage_bf16 = %r" % (storage_bf16,))
+        qk = folded_layernorm_linear(x, np.asarray(lw["ln1_g"], dt), np.asarray(lw["ln1_b"], dt), eps,
+                                     np.asarray(lw["wqkv"], dtype=dt)[:2 * D], np.asarray(lw["bqkv"], dtype=dt)[:2 * D],
+                                     round_weights=True)
         qk = round_bf16(qk).astype(dt)
+    else:
+        xn = layer_norm(x, np.asarray(lw["ln1_g"], dt), np.asarray(lw["ln1_b"], dt), eps)
+        if storage_bf16:
+            xn = round_bf16(xn).astype(dt)
+        qk = xn @ np.asarray(lw["wqkv"], dtype=dt)[:2 * D].T + np.asarray(lw["bqkv"], dtype=dt)[:2 * D]
+        if storage_bf16:
+            qk = round_bf16(qk).astype(dt)
     q = qk[..., :D].reshape(F, n, n_heads, hd).transpose(0, 2, 1, 3)
     k = qk[..., D:].reshape(F, n, n_heads, hd).transpose(0, 2, 1, 3)
     p = softmax_rows((q @ k.transpose(0, 1, 3, 2)) / math.sqrt(hd))        # F, H, query, key

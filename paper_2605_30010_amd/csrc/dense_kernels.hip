@@ -88,6 +88,37 @@ __global__ __launch_bounds__(kLnRows * kWave) void layernorm_kernel(
   }
 }
 
+// The row statistics alone: 1 / sqrt(var + eps) per row (same arithmetic as layernorm_kernel), for
+// GEMMs that have the LayerNorm folded into their weights and epilogue.
+template <int NV>
+__global__ __launch_bounds__(kLnRows * kWave) void rowstats_kernel(const uint16_t *__restrict__ x, float eps, int rows,
+                                                                   int D, float *__restrict__ rstd_out) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * kLnRows + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  uint4 raw[NV];
+  Row<NV> r;
+  load_row<NV>(x + (size_t)row * D, D, lane, raw);
+  unpack_row<NV>(raw, r);
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV * 8; ++i) s += r.v[i];           // pad lanes hold zeros
+  const float mean = wave_sum(s) / (float)D;
+  float q = 0.f;
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    if ((j * kWave + lane) * 8 < D) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float d = r.v[j * 8 + e] - mean;
+        q = fmaf(d, d, q);
+      }
+    }
+  }
+  const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)D + eps);
+  if (lane == 0) rstd_out[row] = rstd;
+}
+
 // ---------------------------------------------------------------------------------------
 // Patch extraction: frames fp32 [T, C, H, W] -> bf16 [T * L, Kpad]; row (t, gy, gx), column
 // (c, py, px) flattened; columns >= C*P*P are zero.  One thread writes 8 columns (16 bytes).
@@ -155,6 +186,7 @@ __device__ __forceinline__ void gemm_epilogue(f32x16 (&acc)[FN][FM], const GemmA
     uint16_t *crow = g.C + (size_t)m * g.ldc;
     const uint16_t *rrow = nullptr;
     if (EPI == EPI_BIAS_RES) rrow = g.res + (size_t)(m % g.res_mod) * g.ldr;
+    const float rs = g.row_scale ? g.row_scale[m] : 1.0f;      // (fma(1, acc, bias) == acc + bias exactly)
 #pragma unroll
     for (int a = 0; a < FN; ++a) {
 #pragma unroll
@@ -162,8 +194,8 @@ __device__ __forceinline__ void gemm_epilogue(f32x16 (&acc)[FN][FM], const GemmA
         const int n = n_base + a * 32 + q * 8 + grp * 4;
         if (n >= g.n_store) continue;
         const float4 bi = *reinterpret_cast<const float4 *>(g.bias + n);
-        float v0 = acc[a][b][q * 4 + 0] + bi.x, v1 = acc[a][b][q * 4 + 1] + bi.y;
-        float v2 = acc[a][b][q * 4 + 2] + bi.z, v3 = acc[a][b][q * 4 + 3] + bi.w;
+        float v0 = fmaf(rs, acc[a][b][q * 4 + 0], bi.x), v1 = fmaf(rs, acc[a][b][q * 4 + 1], bi.y);
+        float v2 = fmaf(rs, acc[a][b][q * 4 + 2], bi.z), v3 = fmaf(rs, acc[a][b][q * 4 + 3], bi.w);
         if (EPI == EPI_BIAS_GELU) {
           v0 = gelu_tanh_f(v0); v1 = gelu_tanh_f(v1); v2 = gelu_tanh_f(v2); v3 = gelu_tanh_f(v3);
         }
@@ -196,6 +228,12 @@ __device__ __forceinline__ void gemm_epilogue_lds(f32x16 (&acc)[FN][FM], const G
   const int r32 = lane & 31, grp = lane >> 5;
   const int prow = lane >> 3, pch = lane & 7;                 // row-wise phase: 8 rows x 8 chunks per pass
   const int wsw = (r32 >> 1) & 7;
+  float rsv[FM];                                              // row scales of this lane's rows, fetched up front
+#pragma unroll
+  for (int b = 0; b < FM; ++b) {
+    const int m = m_base + b * 32 + r32;
+    rsv[b] = (g.row_scale && m < g.M) ? g.row_scale[m] : 1.0f;   // (fma(1, acc, bias) == acc + bias exactly)
+  }
 #pragma unroll
   for (int half = 0; half < FN / 2; ++half) {
   const int nb = n_base + half * 64;
@@ -226,6 +264,7 @@ __device__ __forceinline__ void gemm_epilogue_lds(f32x16 (&acc)[FN][FM], const G
   for (int b = 0; b < FM; ++b) {
     const int mb = m_base + b * 32;
     if (mb >= g.M) break;                                     // wave-uniform: whole block past the last row
+    const float rs = rsv[b];
     if (EPI == EPI_BIAS_RES) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
@@ -243,8 +282,8 @@ __device__ __forceinline__ void gemm_epilogue_lds(f32x16 (&acc)[FN][FM], const G
       }
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        float v0 = av[q * 4 + 0] + bi[a][q].x, v1 = av[q * 4 + 1] + bi[a][q].y;
-        float v2 = av[q * 4 + 2] + bi[a][q].z, v3 = av[q * 4 + 3] + bi[a][q].w;
+        float v0 = fmaf(rs, av[q * 4 + 0], bi[a][q].x), v1 = fmaf(rs, av[q * 4 + 1], bi[a][q].y);
+        float v2 = fmaf(rs, av[q * 4 + 2], bi[a][q].z), v3 = fmaf(rs, av[q * 4 + 3], bi[a][q].w);
         if (EPI == EPI_BIAS_GELU) {
           v0 = gelu_tanh_f(v0); v1 = gelu_tanh_f(v1); v2 = gelu_tanh_f(v2); v3 = gelu_tanh_f(v3);
         }
@@ -1419,6 +1458,14 @@ int launch_layernorm(const uint16_t *x, const float *g, const float *b, float ep
   return ET_OK;
 }
 
+int launch_rowstats(const uint16_t *x, float eps, int rows, int D, float *rstd, hipStream_t s) {
+  if (rows <= 0) return ET_OK;
+  dim3 grid((rows + kLnRows - 1) / kLnRows), block(kLnRows * kWave);
+  ET_DISPATCH_NV(D, hipLaunchKernelGGL(rowstats_kernel<NV>, grid, block, 0, s, x, eps, rows, D, rstd));
+  ET_LAUNCH_CHECK();
+  return ET_OK;
+}
+
 int launch_im2col(const float *frames, int T, int C, int H, int W, int P, int Kpad, uint16_t *out,
                   hipStream_t s) {
   const int GX = W / P, GY = H / P, L = GX * GY;
@@ -1544,6 +1591,7 @@ int launch_gemm(const GemmArgs &g, hipStream_t s, int force_cfg) {
     part.A = g.A + (size_t)rm * g.lda;
     part.C = g.C + (size_t)rm * g.ldc;
     if (g.res) part.res = g.res + (size_t)rm * g.ldr;
+    if (g.row_scale) part.row_scale = g.row_scale + rm;
     part.M = g.M - rm;
     rc = launch_gemm(part, s);
   }

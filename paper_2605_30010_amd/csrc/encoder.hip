@@ -23,7 +23,6 @@ static uint16_t host_f32_to_bf16(float f) {
 constexpr int kMaxGroups = 8;
 
 struct LayerDev {
-  float *ln1_g, *ln1_b, *ln2_g, *ln2_b;
   uint16_t *wqkv, *wo, *w1, *w2;
   float *bqkv, *bo, *b1, *b2;
 };
@@ -49,6 +48,41 @@ struct et_encoder {
 };
 
 namespace et {
+
+// LayerNorm folded into the linear layer that follows it.  With mu, rstd the row statistics,
+//   LN(x) W^T + b = rstd (x - mu) (W . gamma)^T + (W beta + b) = rstd * (x Wf^T) + c,
+//   Wf[n][k] = W[n][k] gamma[k] - mean_k(W[n][:] gamma),   c[n] = sum_k W[n][k] beta[k] + b[n]:
+// subtracting each folded row's mean makes the mu term vanish (sum_k (x_k - mu) w_k = sum_k x_k (w_k - mean w)),
+// so the GEMM reads the residual stream itself and its epilogue multiplies by the row's rstd.
+// The folded weights are rounded to bfloat16 here, along each row with the rounding error carried
+// into the next element (first-order error diffusion, k ascending, every step through the nearest
+// float32): a row of rounded weights then still sums to zero within one step of one element, where
+// independent rounding would leave ~sqrt(K) half-steps that a row's mean multiplies.
+static void fold_layernorm(const float *W, const float *bias, const float *gamma, const float *beta, int N, int K,
+                           std::vector<float> &Wf, std::vector<float> &c) {
+  Wf.resize((size_t)N * K);
+  c.resize(N);
+  std::vector<double> row(K);
+  for (int n = 0; n < N; ++n) {
+    double mean = 0.0, cb = bias[n];
+    for (int k = 0; k < K; ++k) {
+      row[k] = (double)W[(size_t)n * K + k] * gamma[k];
+      mean += row[k];
+      cb += (double)W[(size_t)n * K + k] * beta[k];
+    }
+    mean /= K;
+    double carry = 0.0;
+    for (int k = 0; k < K; ++k) {
+      const double t = row[k] - mean + carry;
+      const uint32_t bits = (uint32_t)host_f32_to_bf16((float)t) << 16;
+      float y;
+      memcpy(&y, &bits, 4);
+      Wf[(size_t)n * K + k] = y;
+      carry = t - (double)y;
+    }
+    c[n] = (float)cb;
+  }
+}
 
 // Uploads a host fp32 matrix [rows, cols] as bf16 [rows_pad, cols_pad], zero padded.
 static int upload_bf16(et_encoder *e, const float *src, int rows, int cols, int rows_pad, int cols_pad,
@@ -84,7 +118,8 @@ static int upload_f32(et_encoder *e, const float *src, int n, int n_pad, float *
 }
 
 struct EncWs {
-  uint16_t *x, *xn, *qkv, *att, *hid;
+  uint16_t *x, *qkv, *att, *hid;
+  float *rstd;         // [R]: 1 / sqrt(var + eps) of the rows of x (LayerNorm folded into the next GEMM)
   int32_t *cu_full;
   void *merge;
   void *score_ws;      // row statistics and per-head column sums of the attention-received scores
@@ -103,7 +138,7 @@ static EncWs carve_encoder(const et_encoder *e, void *ws, int T) {
   const size_t R = (size_t)T * e->L;
   EncWs w;
   w.x = static_cast<uint16_t *>(take(R * e->D * 2));
-  w.xn = static_cast<uint16_t *>(take(R * e->D * 2));
+  w.rstd = static_cast<float *>(take(R * sizeof(float)));
   w.qkv = static_cast<uint16_t *>(take(R * 3 * e->D * 2));
   w.att = static_cast<uint16_t *>(take(R * e->D * 2));
   const size_t hid_cols = (size_t)(e->Mhp > e->Kp_pad ? e->Mhp : e->Kp_pad);
@@ -126,7 +161,7 @@ static EncWs frames_from(const et_encoder *e, const EncWs &w, int f0, int len) {
   const size_t r0 = (size_t)f0 * len;
   const size_t hid_cols = (size_t)(e->Mhp > e->Kp_pad ? e->Mhp : e->Kp_pad);
   v.x += r0 * e->D;
-  v.xn += r0 * e->D;
+  v.rstd += r0;
   v.qkv += r0 * 3 * e->D;
   v.att += r0 * e->D;
   v.hid += r0 * hid_cols;
@@ -137,9 +172,10 @@ static int run_block(et_encoder *e, const LayerDev &lw, const EncWs &w, int rows
                      int n_frames, int max_len, bool ragged, hipStream_t s, bool with_scores = false) {
   const et_config &c = e->cfg;
   const int D = e->D;
-  ET_TIMED(ET_K_LAYERNORM, launch_layernorm(w.x, lw.ln1_g, lw.ln1_b, c.ln_eps, rows, D, w.xn, s));
+  // LayerNorm 1 and 2 are folded into the QKV and fc1 weights (fold_layernorm): only the row scales are computed here
+  ET_TIMED(ET_K_LAYERNORM, launch_rowstats(w.x, c.ln_eps, rows, D, w.rstd, s));
   GemmArgs g;
-  g = GemmArgs{w.xn, D, lw.wqkv, lw.bqkv, nullptr, 0, 1, w.qkv, 3 * D, rows, 3 * D, D, EPI_BIAS};
+  g = GemmArgs{w.x, D, lw.wqkv, lw.bqkv, nullptr, 0, 1, w.qkv, 3 * D, rows, 3 * D, D, EPI_BIAS, w.rstd};
   ET_TIMED(ET_K_GEMM_QKV, launch_gemm(g, s));
   if (with_scores)
     ET_TIMED(ET_K_SCORE, launch_attention_scores(w.qkv, n_frames, max_len, c.n_heads, e->hd, w.score_ws, w.att_score, s));
@@ -150,8 +186,8 @@ static int run_block(et_encoder *e, const LayerDev &lw, const EncWs &w, int rows
   }
   g = GemmArgs{w.att, D, lw.wo, lw.bo, w.x, D, rows, w.x, D, rows, D, D, EPI_BIAS_RES};
   ET_TIMED(ET_K_GEMM_OUT, launch_gemm(g, s));
-  ET_TIMED(ET_K_LAYERNORM, launch_layernorm(w.x, lw.ln2_g, lw.ln2_b, c.ln_eps, rows, D, w.xn, s));
-  g = GemmArgs{w.xn, D, lw.w1, lw.b1, nullptr, 0, 1, w.hid, e->Mhp, rows, e->Mhp, D, EPI_BIAS_GELU};
+  ET_TIMED(ET_K_LAYERNORM, launch_rowstats(w.x, c.ln_eps, rows, D, w.rstd, s));
+  g = GemmArgs{w.x, D, lw.w1, lw.b1, nullptr, 0, 1, w.hid, e->Mhp, rows, e->Mhp, D, EPI_BIAS_GELU, w.rstd};
   ET_TIMED(ET_K_GEMM_FC1, launch_gemm(g, s));
   g = GemmArgs{w.hid, e->Mhp, lw.w2, lw.b2, w.x, D, rows, w.x, D, rows, D, e->Mhp, EPI_BIAS_RES};
   ET_TIMED(ET_K_GEMM_FC2, launch_gemm(g, s));
@@ -298,17 +334,16 @@ int et_encoder_create(const et_config *config, const et_weights *weights, int32_
   e->layers.resize(c.n_layers);
   for (int i = 0; i < c.n_layers; ++i) {
     LayerDev &l = e->layers[i];
-    ET_TRY(upload_f32(e, weights->ln1_g[i], D, D, &l.ln1_g));
-    ET_TRY(upload_f32(e, weights->ln1_b[i], D, D, &l.ln1_b));
-    ET_TRY(upload_f32(e, weights->ln2_g[i], D, D, &l.ln2_g));
-    ET_TRY(upload_f32(e, weights->ln2_b[i], D, D, &l.ln2_b));
-    ET_TRY(upload_bf16(e, weights->wqkv[i], 3 * D, D, round_up(3 * D, 256), D, &l.wqkv));
-    ET_TRY(upload_f32(e, weights->bqkv[i], 3 * D, round_up(3 * D, 256), &l.bqkv));
+    std::vector<float> wf, cf;
+    fold_layernorm(weights->wqkv[i], weights->bqkv[i], weights->ln1_g[i], weights->ln1_b[i], 3 * D, D, wf, cf);
+    ET_TRY(upload_bf16(e, wf.data(), 3 * D, D, round_up(3 * D, 256), D, &l.wqkv));
+    ET_TRY(upload_f32(e, cf.data(), 3 * D, round_up(3 * D, 256), &l.bqkv));
     ET_TRY(upload_bf16(e, weights->wo[i], D, D, Dn, D, &l.wo));
     ET_TRY(upload_f32(e, weights->bo[i], D, Dn, &l.bo));
     // MLP width padded to a multiple of 64 with zero rows / bias (GELU(0) = 0) and zero columns
-    ET_TRY(upload_bf16(e, weights->w1[i], c.d_mlp, D, round_up(e->Mhp, 256), D, &l.w1));
-    ET_TRY(upload_f32(e, weights->b1[i], c.d_mlp, round_up(e->Mhp, 256), &l.b1));
+    fold_layernorm(weights->w1[i], weights->b1[i], weights->ln2_g[i], weights->ln2_b[i], c.d_mlp, D, wf, cf);
+    ET_TRY(upload_bf16(e, wf.data(), c.d_mlp, D, round_up(e->Mhp, 256), D, &l.w1));
+    ET_TRY(upload_f32(e, cf.data(), c.d_mlp, round_up(e->Mhp, 256), &l.b1));
     ET_TRY(upload_bf16(e, weights->w2[i], D, c.d_mlp, Dn, e->Mhp, &l.w2));
     ET_TRY(upload_f32(e, weights->b2[i], D, Dn, &l.b2));
   }

@@ -202,13 +202,18 @@ enum { EPI_BIAS = 0, EPI_BIAS_GELU = 1, EPI_BIAS_RES = 2 };
 // A [M, lda] bf16 (K <= lda, K % 64 == 0, pad columns readable), W [Npad, K] bf16 with
 // Npad % 256 == 0 (pad rows zero), bias [Npad] fp32, C [M, ldc], residual rows indexed
 // (m % res_mod) with leading dimension ldr.  Columns n < n_store are written.
+// row_scale (optional, [M] fp32): the accumulator of row m is multiplied by row_scale[m] before the
+// bias is added (LayerNorm folded into the GEMM: see fold_layernorm in encoder.hip).
 struct GemmArgs {
   const uint16_t *A; int lda;
   const uint16_t *W; const float *bias;
   const uint16_t *res; int ldr; int res_mod;
   uint16_t *C; int ldc;
   int M, n_store, K, epilogue;
+  const float *row_scale = nullptr;
 };
+// 1 / sqrt(var + eps) of every row of x [rows, D] bf16 (biased variance, fp32 two-pass like layernorm_kernel).
+int launch_rowstats(const uint16_t *x, float eps, int rows, int D, float *rstd, hipStream_t s);
 int launch_gemm(const GemmArgs &g, hipStream_t s, int force_cfg = -1);
 int gemm_config_count();
 int launch_attention(const uint16_t *qkv, const int32_t *cu, int n_frames, int max_len, int n_heads,

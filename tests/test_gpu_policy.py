@@ -449,7 +449,7 @@ def test_attention_scores_match_oracle(F, n, H, hd):
 def test_tiny_encoder_selection_by_attention_scores(merge_layers, select_layer, pi):
     rec = build_workload("c1_tiny")
     w = rec["weights"]
-    pol = _f32_policy(dict(POLICIES[pi], tau_seg=0.9, tau_merge=0.9, score_mode="attention", score_storage_bf16=True))
+    pol = _f32_policy(dict(POLICIES[pi], tau_seg=0.9, tau_merge=0.9, score_mode="attention", score_storage_bf16="folded"))
     for seed in range(40):
         frames = make_clip(TINY, [7, 2, 6, 1], 400 + seed, base="uniform", sigma=0.02)
         res = _multi_check(TINY, w, frames, merge_layers, select_layer, pol, strict_selection=False)
@@ -482,7 +482,7 @@ def test_siglip_32_frames_attention_scores_after_encoder():
     output ranked by the attention received in the last block."""
     rec = build_workload("c3_siglip_t32")
     pol = _f32_policy(dict(merge_mode="alg1", select_mode="decoupled", alpha=0.9, tau_seg=0.8, tau_merge=0.8,
-                           ratio=0.2, score_mode="attention", score_storage_bf16=True))
+                           ratio=0.2, score_mode="attention", score_storage_bf16="folded"))
     for seed in range(4):
         frames = make_clip(SIGLIP, rec["lengths"], 900 + seed, base=rec["base"], sigma=0.2)
         res = _multi_check(SIGLIP, rec["weights"], frames, [6, 14, 20], 27, pol, strict_selection=False)
@@ -504,7 +504,7 @@ def test_multi_layer_degenerate_clips(score_mode):
     rec = build_workload("c1_tiny")
     w = rec["weights"]
     L = TINY.tokens_per_frame
-    base = dict(alpha=0.9, tau_seg=0.9, tau_merge=0.9, ratio=0.25, score_mode=score_mode, score_storage_bf16=True)
+    base = dict(alpha=0.9, tau_seg=0.9, tau_merge=0.9, ratio=0.25, score_mode=score_mode, score_storage_bf16="folded")
     one = make_clip(TINY, [1], 5, base="uniform", sigma=0.02)
     same = np.repeat(one, 6, axis=0)
     scenes = make_clip(TINY, [1] * 5, 6, base="smooth", sigma=0.02)

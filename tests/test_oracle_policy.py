@@ -315,3 +315,39 @@ def test_multi_layer_selection_by_attention_scores(tiny):
         assert np.array_equal(kept, want)
     with pytest.raises(AssertionError):
         O.encode_clip_multi(TINY, w, frames, [1, 3], 3, pol)       # a merge between the scoring block and the selection
+
+
+def test_folded_layernorm_linear_is_layernorm_then_linear():
+    """The folded form (row-centred gamma-scaled weights, bias W beta + b, division by the row's standard
+    deviation) is an algebraic identity: it must agree with layer_norm followed by the linear layer to
+    rounding, also for rows with a large mean; rounding the folded weights moves the result by ~2^-9."""
+    rng = np.random.default_rng(7)
+    D, N = 48, 20
+    x = rng.standard_normal((3, 5, D)) * rng.uniform(0.5, 3.0, (3, 5, 1)) + rng.uniform(-20.0, 20.0, (3, 5, 1))
+    g, b = 1.0 + 0.2 * rng.standard_normal(D), 0.3 * rng.standard_normal(D)
+    W, bias = rng.standard_normal((N, D)), rng.standard_normal(N)
+    want = O.layer_norm(x, g, b, 1e-6) @ W.T + bias
+    got = O.folded_layernorm_linear(x, g, b, 1e-6, W, bias)
+    assert np.max(np.abs(got - want)) < 1e-10
+    # a mistake in any term shows: dropping the centring leaves the mean term, dropping W beta the shift
+    Wg = W * g[None, :]
+    no_centre = (x @ Wg.T) / np.sqrt(x.var(axis=-1, keepdims=True) + 1e-6) + W @ b + bias
+    assert np.max(np.abs(no_centre - want)) > 1.0
+    rounded = O.folded_layernorm_linear(x, g, b, 1e-6, W, bias, round_weights=True)
+    err = np.max(np.abs(rounded - want))
+    assert 1e-6 < err < 0.1                              # (independent rounding of the weights: 0.8 on these rows)
+
+
+def test_attention_received_folded_storage_is_close_to_the_plain_form():
+    rng = np.random.default_rng(8)
+    F, n, H, hd = 2, 9, 2, 8
+    D = H * hd
+    x = rng.standard_normal((F, n, D))
+    lw = dict(ln1_g=1.0 + 0.1 * rng.standard_normal(D), ln1_b=0.1 * rng.standard_normal(D),
+              wqkv=rng.standard_normal((3 * D, D)) * 0.3, bqkv=0.1 * rng.standard_normal(3 * D))
+    plain = O.attention_received(x, lw, H, 1e-6)
+    folded = O.attention_received(x, lw, H, 1e-6, storage_bf16="folded")
+    assert np.allclose(folded.sum(axis=1), 1.0)
+    assert 0 < np.max(np.abs(folded - plain) / plain) < 5e-2
+    with pytest.raises(ValueError):
+        O.attention_received(x, lw, H, 1e-6, storage_bf16="other")
