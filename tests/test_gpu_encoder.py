@@ -91,6 +91,28 @@ def test_tiny_plain_encoder_matches_oracle(tiny):
     enc.close()
 
 
+@pytest.mark.parametrize("offset", [1.0, -1.0])
+def test_rows_with_a_large_mean(tiny, offset):
+    """The block LayerNorms are folded into the GEMMs that follow them; the row mean then cancels only
+    because every folded weight row sums to (almost) zero.  A constant added to the patch-embedding bias
+    gives every row of the residual stream a mean of several standard deviations (more than that and the
+    bfloat16 residual stream itself no longer resolves the signal: at |x| = 4 its step is 0.03, and a
+    float64 model of the bfloat16 storage points alone, LayerNorm unfolded, is then 7 % away from the oracle): the output
+    must still match the oracle, which keeps LayerNorm and linear layer apart.  Without the centring of the
+    folded weights the error would be of the order of the mean."""
+    w, frames = tiny
+    w2 = dict(w)
+    w2["patch_b"] = (np.asarray(w["patch_b"], dtype=np.float32) + np.float32(offset)).astype(np.float32)
+    enc = et.Encoder(TINY, w2, 8)
+    got = _encode(enc, frames, -1, 0.9, 0.5)
+    ref = O.encode_clip(TINY, w2, frames, -1, 0.9, 0.5)
+    x0 = O.patch_embed(frames, w2, TINY.patch)
+    assert np.mean(np.abs(x0.mean(-1)) / x0.std(-1)) > 3.0           # the premise: |mean| well above the standard deviation
+    err = rel_l2(dev_to_f64(got["tokens"]), ref["tokens"])
+    assert err <= TOL, err
+    enc.close()
+
+
 def test_tiny_config_end_to_end(tiny):
     """Config 1: two scenes of four frames -> two segments, 32 of 64 tokens each."""
     w, frames = tiny
