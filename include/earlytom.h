@@ -116,7 +116,9 @@ size_t et_workspace_bytes(const et_encoder *enc, int32_t T);
  *   sim_threshold  tau of Eq. 1: frame t opens a new segment iff s_t < tau (NaN s_t also
  *                opens one).  +INFINITY makes every frame its own segment.  NaN is rejected.
  *   keep_ratio   in (0, 1]; k = et_keep_count(L, keep_ratio) tokens are kept per output frame.
- * Synchronises `hip_stream` once in the middle (to learn N) and once before returning.
+ * The host waits twice: in the middle for an event on `hip_stream` (N is copied to pinned memory
+ * of the encoder right after the boundary scan, so the blocks that follow are enqueued while the
+ * merge, selection and compaction still run) and for the whole stream before returning.
  * Blocks that run on fewer than 8192 rows (those after the selection) have their weights read
  * ahead by small kernels on a stream the encoder owns (default priority), released by an event on
  * `hip_stream` and joined to it before the call returns; they read encoder memory only.  One

@@ -45,6 +45,8 @@ struct et_encoder {
   // weight warm-up (see warm_weights): a stream and two events of its own
   hipStream_t warm_stream = nullptr;
   hipEvent_t warm_go = nullptr, warm_done = nullptr;
+  int32_t *count_host = nullptr;        // pinned: segment count read back in the middle of the compression stage
+  hipEvent_t count_ready = nullptr;
 };
 
 namespace et {
@@ -350,10 +352,12 @@ int et_encoder_create(const et_config *config, const et_weights *weights, int32_
 #undef ET_TRY
   if (hipStreamCreateWithFlags(&e->warm_stream, hipStreamNonBlocking) != hipSuccess ||      // (default priority)
       hipEventCreateWithFlags(&e->warm_go, hipEventDisableTiming) != hipSuccess ||
-      hipEventCreateWithFlags(&e->warm_done, hipEventDisableTiming) != hipSuccess) {
+      hipEventCreateWithFlags(&e->warm_done, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&e->count_ready, hipEventDisableTiming) != hipSuccess ||
+      hipHostMalloc(reinterpret_cast<void **>(&e->count_host), 64, hipHostMallocDefault) != hipSuccess) {
     (void)hipGetLastError();
     et_encoder_destroy(e);
-    set_error("creating the warm-up stream failed");
+    set_error("creating the warm-up stream, the read-back event or its pinned word failed");
     return ET_ERR_HIP;
   }
   *out = e;
@@ -378,6 +382,8 @@ void et_encoder_destroy(et_encoder *e) {
   if (e->warm_stream) (void)hipStreamDestroy(e->warm_stream);
   if (e->warm_go) (void)hipEventDestroy(e->warm_go);
   if (e->warm_done) (void)hipEventDestroy(e->warm_done);
+  if (e->count_ready) (void)hipEventDestroy(e->count_ready);
+  if (e->count_host) (void)hipHostFree(e->count_host);
   for (void *p : e->allocs) (void)hipFree(p);
   e->prof.destroy();
   delete e;
@@ -538,12 +544,15 @@ static int encode_impl(et_encoder *e, const float *frames_dev, int32_t T, int32_
     } else if (select_here) {
       const MergeWs mw = carve_merge(w.merge, T, L, D);
       k = et_keep_count(L, keep_ratio);
+      // The segment count is final after the scan: the host waits for that copy only and enqueues the
+      // next blocks while the merge, the selection and the compaction still run.
+      const EarlyCount early{e->count_host, e->count_ready};
+      *e->count_host = 0;
       int rc = enqueue_merge_stage(w.x, T, L, D, sim_threshold, k, mw, out->frame_sim_dev, out->seg_start_dev,
-                                   out->kept_idx_dev, out->cu_tokens_dev, w.x, s, &e->prof);
+                                   out->kept_idx_dev, out->cu_tokens_dev, w.x, s, &e->prof, &early);
       if (rc) return rc;
-      int32_t n_seg = 0;
-      ET_HIP(hipMemcpyAsync(&n_seg, mw.n_seg, sizeof(int32_t), hipMemcpyDeviceToHost, s));
-      ET_HIP(hipStreamSynchronize(s));
+      ET_HIP(hipEventSynchronize(e->count_ready));
+      const int32_t n_seg = *e->count_host;
       if (n_seg < 1 || n_seg > T) {
         set_error("segment count %d read back from the device is outside [1, T = %d]", n_seg, T);
         return ET_ERR_HIP;

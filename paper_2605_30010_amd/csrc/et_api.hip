@@ -76,10 +76,14 @@ static int check_outputs(const et_output *out) {
 
 int enqueue_merge_stage(const uint16_t *x, int T, int L, int D, float tau, int k, const MergeWs &w,
                         float *sim_out, int32_t *seg_start, int32_t *kept, int32_t *cu_tokens,
-                        uint16_t *packed, hipStream_t s, Profiler *prof) {
+                        uint16_t *packed, hipStream_t s, Profiler *prof, const EarlyCount *early) {
   float *sim = sim_out ? sim_out : w.sim;
   ET_TIMED_P(prof, ET_K_SIMILARITY, launch_similarity(x, T, L, D, w.cos, s));
   ET_TIMED_P(prof, ET_K_SCAN, launch_sim_mean_scan(w.cos, T, L, tau, sim, seg_start, w.n_seg, true, true, s));
+  if (early) {
+    ET_HIP(hipMemcpyAsync(early->host, w.n_seg, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    ET_HIP(hipEventRecord(early->ready, s));
+  }
   ET_TIMED_P(prof, ET_K_MERGE, launch_segment_mean(x, T, L, D, seg_start, w.n_seg, w.merged, w.score, s));
   ET_TIMED_P(prof, ET_K_SELECT, launch_topk(w.score, T, w.n_seg, L, k, kept, cu_tokens, s));
   ET_TIMED_P(prof, ET_K_COMPACT, launch_compact(w.merged, kept, T, w.n_seg, L, D, k, packed, s));

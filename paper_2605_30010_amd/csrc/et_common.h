@@ -158,10 +158,17 @@ int enqueue_policy_stage(const uint16_t *x, int T, int L, int D, const et_policy
                          struct Profiler *prof, const float *score_override = nullptr);
 int copy_plan_out(const MergeWs &w, int N, et_plan_out *plan, hipStream_t s);
 MergeWs carve_merge(void *ws, int T, int L, int D);
+// Where the host learns the segment count while the stage is still running: right after the scan
+// kernel the count is copied to `host` (pinned memory) and `ready` is recorded, so the host waits
+// for that event only and enqueues the following blocks under the merge, selection and compaction.
+struct EarlyCount {
+  int32_t *host;
+  hipEvent_t ready;
+};
 // Enqueues similarity -> scan -> segment mean (+score) -> top-k -> compaction; no host sync.
 int enqueue_merge_stage(const uint16_t *x, int T, int L, int D, float tau, int k, const MergeWs &w,
                         float *sim_out, int32_t *seg_start, int32_t *kept, int32_t *cu_tokens,
-                        uint16_t *packed, hipStream_t s, Profiler *prof);
+                        uint16_t *packed, hipStream_t s, Profiler *prof, const EarlyCount *early = nullptr);
 
 // ---- launchers implemented in merge_kernels.hip ----
 int launch_similarity(const uint16_t *x, int T, int L, int D, float *cos_out, hipStream_t s);
