@@ -1174,7 +1174,7 @@ __device__ __forceinline__ uint2 lds_read_tr16(const uint16_t *p) {
 
 template <int HD, int QB, int MINB>
 __global__ __launch_bounds__(kAttWaves * 64, MINB) void attention_dma_kernel(
-    const uint16_t *__restrict__ qkv, int n, int n_heads, float scale_log2, uint16_t *__restrict__ out) {
+    const uint16_t *__restrict__ qkv, int n, int n_heads, int n_qblk, float scale_log2, uint16_t *__restrict__ out) {
   constexpr int NC = (HD + 15) / 16;
   constexpr int NDB = (HD + 31) / 32;
   constexpr int STAGES = 2;
@@ -1195,7 +1195,15 @@ __global__ __launch_bounds__(kAttWaves * 64, MINB) void attention_dma_kernel(
   constexpr int PAD = (NDB * 32 - HD) * kAttBKV + 64;
   __shared__ __align__(16) uint16_t lds[STAGES * STAGE + PAD];
 
-  const int f = blockIdx.z, h = blockIdx.y, q0 = blockIdx.x * (kAttBQ * QB);
+  // One-dimensional grid over (frame, head, query block), query block fastest.  Workgroups go to the
+  // 8 XCDs round-robin by index, so the index is remapped first: XCD x takes the x-th contiguous run
+  // of the order, and the query blocks of one (frame, head) - which read the same K and V - share an L2.
+  int v;
+  {
+    const int total = gridDim.x, per = total / 8, rem = total % 8, xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
+    v = xcd * per + (xcd < rem ? xcd : rem) + slot;
+  }
+  const int q0 = (v % n_qblk) * (kAttBQ * QB), h = (v / n_qblk) % n_heads, f = v / (n_qblk * n_heads);
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps load dispatch scalar
   const int r32 = lane & 31, grp = lane >> 5;
@@ -1655,11 +1663,12 @@ int launch_attention_uniform(const uint16_t *qkv, int n_frames, int len, int n_h
 #define ET_ATT(HD)                                                                                        \
   case HD:                                                                                                \
     if (HD <= 80 && wide)                                                                                 \
-      hipLaunchKernelGGL((attention_dma_kernel<HD, (HD <= 80 ? 2 : 1), (HD <= 96 ? 2 : 1)>), agrid2,   \
-                         dim3(kAttWaves * 64), 0, s, qkv, len, n_heads, scale_log2, out);                 \
+      hipLaunchKernelGGL((attention_dma_kernel<HD, (HD <= 80 ? 2 : 1), (HD <= 96 ? 2 : 1)>),            \
+                         dim3(agrid2.x * agrid2.y * agrid2.z), dim3(kAttWaves * 64), 0, s, qkv, len, n_heads,   \
+                         (int)agrid2.x, scale_log2, out);                                                 \
     else                                                                                                  \
-      hipLaunchKernelGGL((attention_dma_kernel<HD, 1, (HD <= 96 ? 2 : 1)>), agrid, dim3(kAttWaves * 64), 0, s,   \
-                         qkv, len, n_heads, scale_log2, out);                                             \
+      hipLaunchKernelGGL((attention_dma_kernel<HD, 1, (HD <= 96 ? 2 : 1)>), dim3(agrid.x * agrid.y * agrid.z),   \
+                         dim3(kAttWaves * 64), 0, s, qkv, len, n_heads, (int)agrid.x, scale_log2, out);   \
     break;
   switch (head_dim) {
     ET_ATT(16) ET_ATT(32) ET_ATT(64) ET_ATT(72) ET_ATT(80) ET_ATT(96) ET_ATT(128)
