@@ -997,9 +997,17 @@ constexpr int kAttBQ = kAttWaves * 32;
 constexpr int kAttBKV = 64;
 constexpr int kVtRow = kAttBKV + 8;
 
+// Workgroups go to the 8 XCDs round-robin by index.  A one-dimensional grid whose order puts
+// workgroups that share data next to each other is therefore remapped first: XCD x takes the x-th
+// contiguous run of the order (a bijection of [0, gridDim.x)), and neighbours share an L2.
+__device__ __forceinline__ int xcd_contiguous_index() {
+  const int total = gridDim.x, per = total / 8, rem = total % 8, xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
+  return xcd * per + (xcd < rem ? xcd : rem) + slot;
+}
+
 template <int HD>
 __global__ __launch_bounds__(kAttWaves * 64) void attention_kernel(
-    const uint16_t *__restrict__ qkv, const int32_t *__restrict__ cu, int n_heads, float scale_log2,
+    const uint16_t *__restrict__ qkv, const int32_t *__restrict__ cu, int n_heads, int n_qblk, float scale_log2,
     uint16_t *__restrict__ out) {
   constexpr int NC = (HD + 15) / 16;        // 16-wide contraction chunks of Q K^T
   constexpr int HDP = NC * 16;
@@ -1010,9 +1018,11 @@ __global__ __launch_bounds__(kAttWaves * 64) void attention_kernel(
   __shared__ __align__(16) uint16_t Ks[kAttBKV * KROW];
   __shared__ __align__(16) uint16_t Vt[NDB * 32 * kVtRow];
 
-  const int f = blockIdx.z, h = blockIdx.y;
+  // grid over (frame, head, query block), query block fastest: the blocks of one (frame, head) read the same K and V
+  const int v = xcd_contiguous_index();
+  const int f = v / (n_qblk * n_heads), h = (v / n_qblk) % n_heads;
   const int start = cu[f], len = cu[f + 1] - start;
-  const int q0 = blockIdx.x * kAttBQ;
+  const int q0 = (v % n_qblk) * kAttBQ;
   if (q0 >= len) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r32 = lane & 31, grp = lane >> 5;
@@ -1195,14 +1205,9 @@ __global__ __launch_bounds__(kAttWaves * 64, MINB) void attention_dma_kernel(
   constexpr int PAD = (NDB * 32 - HD) * kAttBKV + 64;
   __shared__ __align__(16) uint16_t lds[STAGES * STAGE + PAD];
 
-  // One-dimensional grid over (frame, head, query block), query block fastest.  Workgroups go to the
-  // 8 XCDs round-robin by index, so the index is remapped first: XCD x takes the x-th contiguous run
-  // of the order, and the query blocks of one (frame, head) - which read the same K and V - share an L2.
-  int v;
-  {
-    const int total = gridDim.x, per = total / 8, rem = total % 8, xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
-    v = xcd * per + (xcd < rem ? xcd : rem) + slot;
-  }
+  // One-dimensional grid over (frame, head, query block), query block fastest, so that the query blocks
+  // of one (frame, head) - which read the same K and V - run on one XCD and share its L2.
+  const int v = xcd_contiguous_index();
   const int q0 = (v % n_qblk) * (kAttBQ * QB), h = (v / n_qblk) % n_heads, f = v / (n_qblk * n_heads);
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps load dispatch scalar
@@ -1629,10 +1634,11 @@ bool head_dim_supported(int hd) {
 int launch_attention(const uint16_t *qkv, const int32_t *cu, int n_frames, int max_len, int n_heads,
                      int head_dim, uint16_t *out, hipStream_t s) {
   if (n_frames <= 0 || max_len <= 0) return ET_OK;
-  const dim3 grid((max_len + kAttBQ - 1) / kAttBQ, n_heads, n_frames), block(kAttWaves * 64);
+  const int n_qblk = (max_len + kAttBQ - 1) / kAttBQ;
+  const dim3 grid((unsigned)n_qblk * n_heads * n_frames), block(kAttWaves * 64);
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)head_dim);
 #define ET_ATT(HD) \
-  case HD: hipLaunchKernelGGL(attention_kernel<HD>, grid, block, 0, s, qkv, cu, n_heads, scale_log2, out); break;
+  case HD: hipLaunchKernelGGL(attention_kernel<HD>, grid, block, 0, s, qkv, cu, n_heads, n_qblk, scale_log2, out); break;
   switch (head_dim) {
     ET_ATT(16) ET_ATT(32) ET_ATT(64) ET_ATT(72) ET_ATT(80) ET_ATT(96) ET_ATT(128)
     default: set_error("head_dim %d is not instantiated", head_dim); return ET_ERR_UNSUPPORTED;
