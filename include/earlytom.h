@@ -93,18 +93,6 @@ int et_encoder_create(const et_config *config, const et_weights *weights, int32_
                       et_encoder **out);
 void et_encoder_destroy(et_encoder *enc); /* NULL is allowed */
 
-/* Frame groups.  Inside the encoder blocks the frames of a clip do not interact (attention is per
- * frame, Sec. 3.1; everything else is per token), so the encode calls may split the current frames
- * into n_groups contiguous groups and run each group's kernel sequence on a stream of its own:
- * group 0 on the caller's stream, the others on streams the encoder owns (default priority), forked
- * from and joined to the caller's stream with events around every stretch of blocks; the compression
- * stages (Sec. 3.2, 3.3), which look across frames, run on the caller's stream alone.  The kernels of
- * different groups fill each other's partly filled last rounds.  Results are bit-identical for every
- * n_groups.  n_groups in [1, 8]; 1 (the default) keeps everything on the caller's stream.  Frames of
- * unequal length (decoupled selection) and calls with per-kernel timing on run ungrouped.  Must not be
- * called while an encode call of this encoder is running.  Errors: INVALID_ARG, HIP. */
-int et_encoder_set_frame_groups(et_encoder *enc, int32_t n_groups);
-
 /* Bytes of device workspace et_encode_clip needs for a clip of T frames (0 on bad arguments). */
 size_t et_workspace_bytes(const et_encoder *enc, int32_t T);
 
@@ -163,8 +151,8 @@ const char *et_last_error(void); /* thread-local, never NULL */
  *                segment start.  tau_seg: segment threshold.  tau_merge: Eq. 2 threshold.
  *   score_mode   ET_SCORE_L2NORM: a token's score is its squared L2 norm (as on the simple path).
  *                ET_SCORE_ATTENTION: the attention the token receives in the encoder block just
- *                before the selection (Sec. 3.3 ranks by "per-token attention scores" without
- *                defining them; this library's reading): the mean over heads and over the queries
+ *                before the selection (Sec. 3.3 and Alg. 2 rank by a score per token taken from the
+ *                encoder's attention without defining it; this library's reading): the mean over heads and over the queries
  *                of its frame of softmax(Q K^T / sqrt(hd))[query][token].  Needs a block before
  *                the selection (select layer >= 1) whose input is what the selection sees, so no
  *                merge may run at the select layer itself; only et_encode_clip_multi accepts it.
@@ -213,6 +201,13 @@ int et_profile_enable(et_encoder *enc, int32_t on);
  * compression stage), phase 1 = launches on the kept tokens; clears them if `reset` != 0. */
 int et_profile_read(et_encoder *enc, double *ms, int64_t *launches, int32_t reset);
 const char *et_kernel_name(int32_t kind);
+/* The same for the stand-alone stage: with it on, et_merge_select brackets
+ * every launch, and the whole launch sequence, with HIP events on `hip_stream`.  The read fills
+ * ms[ET_K_COUNT] / launches[ET_K_COUNT] per kernel kind, *total_ms with the summed time between the
+ * first launch's start and the last launch's end (launch gaps included, the final device-to-host copy
+ * and stream wait excluded) and *calls.  Process-wide state, not thread-safe; off by default. */
+int et_merge_profile_enable(int32_t on);
+int et_merge_profile_read(double *ms, int64_t *launches, double *total_ms, int64_t *calls, int32_t reset);
 
 /* ---- single steps (the same kernels the hot path launches; for parity tests and
  *      micro-benchmarks).  All asynchronous on `hip_stream` unless stated. ------------- */
@@ -251,21 +246,12 @@ int et_layernorm(const uint16_t *x_dev, const float *gamma_dev, const float *bet
  * epilogue: 0 bias only, 1 bias + GELU-tanh, 2 bias + residual (res_dev bf16 [M, N], may
  * alias c_dev).  bias_dev float32 [N].  Standalone form for tests: any M >= 1, N and K
  * multiples of 8; allocates and frees padded copies of the operands itself and synchronises.
- * tile_config: -1 = the library's choice, else a tiling listed at et_gemm_tune. */
+ * tile_config: -1 = the library's choice (which may also split a thin last tile row or column
+ * off into a launch of its own), else one workgroup tiling of the persistent kernel:
+ * 0 = 256 x 256 x 64 with 8 wavefronts, 1 = 128 x 128 x 64 and 2 = 64 x 128 x 64 with 4. */
 int et_gemm_bf16(const uint16_t *a_dev, const uint16_t *w_dev, const float *bias_dev,
                  const uint16_t *res_dev, int32_t M, int32_t N, int32_t K, int32_t epilogue,
                  int32_t tile_config, uint16_t *c_dev, void *hip_stream);
-
-/* Times `iters` back-to-back launches of the GEMM above on library-allocated operands of the
- * given logical shape with HIP events; *avg_ms (HOST) receives the mean milliseconds per
- * launch.  tile_config selects one of the library's workgroup tilings: 0-5 register-staged
- * kernels, 6-19 direct-to-LDS kernels (one tile per workgroup), 20-35 persistent k-tile stream
- * kernels (20: 256x256x64 with 8 wavefronts, 22: 128x128x64, 26: 64x128x64; 33-35: 256x256 with 4
- * wavefronts of 128x128 whose accumulators sit in the accumulation registers; the full table is in
- * launch_gemm_id); -1: the library's own choice, which may also split a thin last tile row or
- * column off into a launch of its own.  For tuning sweeps; allocates, frees, synchronises. */
-int et_gemm_tune(int32_t M, int32_t N, int32_t K, int32_t epilogue, int32_t tile_config, int32_t iters,
-                 float *avg_ms, void *hip_stream);
 
 /* Per-frame multi-head attention on a fused projection buffer qkv_dev bf16 [rows, 3D]
  * (q | k | v, head h at columns h*hd): out_dev bf16 [rows, D].  cu_tokens_dev [n_frames+1]
@@ -275,14 +261,18 @@ int et_attention(const uint16_t *qkv_dev, const int32_t *cu_tokens_dev, int32_t 
                  void *hip_stream);
 
 /* The same attention for frames of equal length `len` (frame f = rows f*len .. f*len+len-1),
- * which is what the hot path runs: K and V tiles stream through LDS by direct global -> LDS
- * loads and the V^T fragments are taken with LDS transpose reads.  scratch_dev / scratch_bytes
- * are not used any more (et_attention_uniform_scratch_bytes returns 0; NULL is accepted); they
- * stay in the signature for callers written against the earlier form. */
+ * which is what the hot path runs: K tiles stream through LDS by direct global -> LDS loads and
+ * the V^T fragments are taken with LDS transpose reads. */
 int et_attention_uniform(const uint16_t *qkv_dev, int32_t n_frames, int32_t len, int32_t n_heads,
-                         int32_t head_dim, void *scratch_dev, size_t scratch_bytes, uint16_t *out_dev,
-                         void *hip_stream);
-size_t et_attention_uniform_scratch_bytes(int32_t n_frames, int32_t len, int32_t n_heads, int32_t head_dim);
+                         int32_t head_dim, uint16_t *out_dev, void *hip_stream);
+
+/* The first two launches of encoder block `layer` on caller-supplied hidden states x_dev (bf16
+ * [rows, D]), exactly as et_encode_clip issues them: the row scales 1 / sqrt(var + eps) of
+ * LayerNorm 1 into rstd_dev (float32 [rows]) and the fused projection with the LayerNorm folded in
+ * into qkv_dev (bf16 [rows, 3D], q | k | v).  Lets a test rank attention-received scores on the very
+ * q and k the encoder used.  Errors: INVALID_ARG, HIP. */
+int et_encoder_block_qkv(et_encoder *enc, int32_t layer, const uint16_t *x_dev, int32_t rows,
+                         float *rstd_dev, uint16_t *qkv_dev, void *hip_stream);
 
 /* Stage I at several encoder layers, Stage II once (the paper merges at three layers, e.g. 6, 14,
  * 20, and selects after the encoder; Table 8).  At every layer of merge_layers[0..n_merge_layers)

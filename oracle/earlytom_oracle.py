@@ -95,68 +95,29 @@ def attention(xn, lw, n_heads):
     return o @ np.asarray(lw["wo"], dtype=dt).T + np.asarray(lw["bo"], dtype=dt)
 
 
-def round_bf16(a):
-    """Round to bfloat16 (nearest, ties to even) and return the values as float64."""
-    f = np.ascontiguousarray(np.asarray(a, dtype=np.float32))
-    b = f.view(np.uint32).astype(np.uint64)
-    b = ((b + 0x7FFF + ((b >> 16) & 1)) >> 16) << 16
-    return b.astype(np.uint32).view(np.float32).reshape(f.shape).astype(np.float64)
+def attention_received_from_qk(q, k, n_heads):
+    """Column means of the softmax matrices: q, k [F, n, D] (head h = columns h*hd ..) -> [F, n],
+    entry [f, j] = mean over heads and over the queries i of frame f of softmax_j(q_i . k_j / sqrt(hd))."""
+    F, n, D = q.shape
+    hd = D // n_heads
+    qh = q.reshape(F, n, n_heads, hd).transpose(0, 2, 1, 3)
+    kh = k.reshape(F, n, n_heads, hd).transpose(0, 2, 1, 3)
+    p = softmax_rows((qh @ kh.transpose(0, 1, 3, 2)) / math.sqrt(hd))        # F, H, query, key
+    return p.mean(axis=(1, 2))
 
 
-def folded_layernorm_linear(x, gamma, beta, eps, W, bias, round_weights=False):
-    """LayerNorm followed by a linear layer, written with the LayerNorm folded into the weights:
-    LN(x) W^T + b = rstd * (x Wf^T) + c with Wf[n, k] = W[n, k] gamma[k] - mean_k(W[n, :] gamma) and
-    c = W beta + b (the row mean of x drops out because every row of Wf sums to zero).  Equal to
-    layer_norm(x) @ W.T + bias up to rounding; with round_weights the folded weights pass through
-    bfloat16, which is where a device that multiplies the un-normalised x in bfloat16 rounds: along
-    each row, k ascending, with the rounding error of one element carried into the next (so that a
-    rounded row still sums to zero within one step), every step through the nearest float32."""
-    Wg = W * gamma[None, :]
-    Wf = Wg - Wg.mean(axis=1, keepdims=True)
-    if round_weights:
-        carry = np.zeros(Wf.shape[0])
-        out = np.empty_like(Wf)
-        for k in range(Wf.shape[1]):
-            t = Wf[:, k] + carry
-            out[:, k] = round_bf16(t)
-            carry = t - out[:, k]
-        Wf = out.astype(x.dtype)
-    c = W @ beta + bias
-    var = x.var(axis=-1, keepdims=True)
-    return (x @ Wf.T) / np.sqrt(var + eps) + c
+def attention_received(x, lw, n_heads, eps):
+    """Per-token attention score for Sec. 3.3 / Alg. 2 (input A, the encoder's attentions).
 
-
-def attention_received(x, lw, n_heads, eps, storage_bf16=False):
-    """Per-token attention score of Sec. 3.3 / Alg. 2 ("attentions A from the vision encoder").
-
-    The paper does not say how a per-token score is taken from the attention maps; the reading
+    The paper does not say how one score per token is taken from the attention maps; the reading
     here: the attention a token RECEIVES in the block with weights `lw`, i.e. the column mean of the
     softmax matrix over all queries of its frame, averaged over the heads.  x: [F, n, D] is the
-    input of that block.  Returns [F, n]; every row sums to 1.
-    storage_bf16: where a ranking has to be decided from the same numbers as on a device that stores
-    bfloat16.  True: the LayerNorm output and q, k are rounded to bfloat16.  "folded": the LayerNorm is
-    folded into the projection (folded_layernorm_linear), the folded weights and q, k are rounded."""
+    input of that block.  Returns [F, n]; every row sums to 1."""
     F, n, D = x.shape
-    hd = D // n_heads
     dt = x.dtype
-    if isinstance(storage_bf16, str):
-        if storage_bf16 != "folded":
-            raise ValueError("storage_bf16 = %r" % (storage_bf16,))
-        qk = folded_layernorm_linear(x, np.asarray(lw["ln1_g"], dt), np.asarray(lw["ln1_b"], dt), eps,
-                                     np.asarray(lw["wqkv"], dtype=dt)[:2 * D], np.asarray(lw["bqkv"], dtype=dt)[:2 * D],
-                                     round_weights=True)
-        qk = round_bf16(qk).astype(dt)
-    else:
-        xn = layer_norm(x, np.asarray(lw["ln1_g"], dt), np.asarray(lw["ln1_b"], dt), eps)
-        if storage_bf16:
-            xn = round_bf16(xn).astype(dt)
-        qk = xn @ np.asarray(lw["wqkv"], dtype=dt)[:2 * D].T + np.asarray(lw["bqkv"], dtype=dt)[:2 * D]
-        if storage_bf16:
-            qk = round_bf16(qk).astype(dt)
-    q = qk[..., :D].reshape(F, n, n_heads, hd).transpose(0, 2, 1, 3)
-    k = qk[..., D:].reshape(F, n, n_heads, hd).transpose(0, 2, 1, 3)
-    p = softmax_rows((q @ k.transpose(0, 1, 3, 2)) / math.sqrt(hd))        # F, H, query, key
-    return p.mean(axis=(1, 2))
+    xn = layer_norm(x, np.asarray(lw["ln1_g"], dt), np.asarray(lw["ln1_b"], dt), eps)
+    qk = xn @ np.asarray(lw["wqkv"], dtype=dt)[:2 * D].T + np.asarray(lw["bqkv"], dtype=dt)[:2 * D]
+    return attention_received_from_qk(qk[..., :D], qk[..., D:], n_heads)
 
 
 def mlp(xn, lw):
@@ -506,7 +467,7 @@ def encode_clip(shape, w, frames, merge_layer, sim_threshold, keep_ratio,
 
 
 def encode_clip_multi(shape, w, frames, merge_layers, select_layer, policy, dtype=np.float64,
-                      x_at_layers=None, force_kept=None):
+                      x_at_layers=None, force_kept=None, qk_at_score_layer=None):
     """Stage I at several encoder layers, Stage II once (the paper merges at three layers, e.g.
     [6, 14, 20], and selects after the encoder).
 
@@ -517,6 +478,9 @@ def encode_clip_multi(shape, w, frames, merge_layers, select_layer, policy, dtyp
     dynamic if there was none), the re-scaled count uses the ORIGINAL frame count.
     `x_at_layers` (optional dict layer -> [frames, L, D]) replaces the hidden states seen at a merge /
     select layer (stage-wise parity); a block whose output would be replaced that way is not evaluated.
+    `qk_at_score_layer` (optional [frames, L, 2 D], attention scores only) replaces the queries and keys
+    of the scoring block in the same way: the scores are then the column means of the softmax of THOSE
+    q . k / sqrt(hd) (stage-wise parity of the ranking on identical inputs).
     Returns tokens, kept_idx, cu_tokens, frame_first / frame_count (ranges of original frames),
     frame_dynamic, seg_start (original frame index of each segment start of the last merge),
     n_frames_out, hidden (dict of the states seen at each layer), stages (per merge layer: frame_sim,
@@ -596,8 +560,14 @@ def encode_clip_multi(shape, w, frames, merge_layers, select_layer, policy, dtyp
                 rows = np.concatenate([x[n][per_frame[n]] for n in range(N)], axis=0)
         if by_attention and i == select_layer - 1:
             # (after this layer's own merge, if it has one: the block runs on the merged frames)
-            z_att = attention_received(x, w["layers"][i], shape.n_heads, shape.ln_eps,
-                                       storage_bf16=policy.get("score_storage_bf16", False))
+            if qk_at_score_layer is not None:
+                qk = np.asarray(qk_at_score_layer, dtype=dtype)
+                if qk.shape != (x.shape[0], L, 2 * shape.d_model):
+                    raise ValueError("qk_at_score_layer has shape %s, the scoring block sees %d frames"
+                                     % (qk.shape, x.shape[0]))
+                z_att = attention_received_from_qk(qk[..., :shape.d_model], qk[..., shape.d_model:], shape.n_heads)
+            else:
+                z_att = attention_received(x, w["layers"][i], shape.n_heads, shape.ln_eps)
         if i < n_layers:
             if rows is None:
                 if not replaced_later(i):

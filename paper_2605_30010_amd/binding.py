@@ -94,18 +94,19 @@ def load_library():
         "et_compact_tokens": (C.c_int, [vp, vp, i32, i32, i32, i32, vp, vp]),
         "et_layernorm": (C.c_int, [vp, vp, vp, f32, i32, i32, vp, vp]),
         "et_gemm_bf16": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp]),
-        "et_gemm_tune": (C.c_int, [i32, i32, i32, i32, i32, i32, C.POINTER(f32), vp]),
         "et_attention": (C.c_int, [vp, vp, i32, i32, i32, i32, vp, vp]),
-        "et_attention_uniform": (C.c_int, [vp, i32, i32, i32, i32, vp, sz, vp, vp]),
-        "et_attention_uniform_scratch_bytes": (sz, [i32, i32, i32, i32]),
+        "et_attention_uniform": (C.c_int, [vp, i32, i32, i32, i32, vp, vp]),
+        "et_encoder_block_qkv": (C.c_int, [vp, i32, vp, i32, vp, vp, vp]),
         "et_encoder_create": (C.c_int, [C.POINTER(_Config), C.POINTER(_Weights), i32, C.POINTER(vp)]),
         "et_encoder_destroy": (None, [vp]),
         "et_workspace_bytes": (sz, [vp, i32]),
         "et_encode_clip": (C.c_int, [vp, vp, i32, i32, f32, f32, vp, sz, vp, C.POINTER(_Output)]),
         "et_profile_enable": (C.c_int, [vp, i32]),
-        "et_encoder_set_frame_groups": (C.c_int, [vp, i32]),
         "et_profile_read": (C.c_int, [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), i32]),
         "et_kernel_name": (C.c_char_p, [i32]),
+        "et_merge_profile_enable": (C.c_int, [i32]),
+        "et_merge_profile_read": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double),
+                                           C.POINTER(C.c_int64), i32]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -364,14 +365,6 @@ def et_gemm_bf16(a, w, bias, epilogue=0, residual=None, tile_config=-1, stream=N
     return c
 
 
-def et_gemm_tune(M, N, K, epilogue=0, tile_config=-1, iters=20, stream=None):
-    """Mean milliseconds per launch of the GEMM kernel on library-allocated operands."""
-    ms = C.c_float(0.0)
-    _check(load_library().et_gemm_tune(M, N, K, int(epilogue), int(tile_config), int(iters), C.byref(ms),
-                                       _stream(stream)))
-    return float(ms.value)
-
-
 def et_attention(qkv, cu_tokens, max_len, n_heads, head_dim, stream=None):
     lib = load_library()
     _dev(qkv, torch.bfloat16, "qkv")
@@ -383,18 +376,11 @@ def et_attention(qkv, cu_tokens, max_len, n_heads, head_dim, stream=None):
     return out
 
 
-def et_attention_uniform_scratch_bytes(n_frames, length, n_heads, head_dim):
-    return int(load_library().et_attention_uniform_scratch_bytes(n_frames, length, n_heads, head_dim))
-
-
 def et_attention_uniform(qkv, n_frames, length, n_heads, head_dim, stream=None):
     lib = load_library()
     _dev(qkv, torch.bfloat16, "qkv")
-    need = et_attention_uniform_scratch_bytes(n_frames, length, n_heads, head_dim)
-    scratch = torch.empty((max(need, 1),), dtype=torch.uint8, device=qkv.device)
     out = torch.empty((qkv.shape[0], n_heads * head_dim), dtype=torch.bfloat16, device=qkv.device)
-    _check(lib.et_attention_uniform(_ptr(qkv), n_frames, int(length), n_heads, head_dim, _ptr(scratch),
-                                    scratch.numel(), _ptr(out), _stream(stream)))
+    _check(lib.et_attention_uniform(_ptr(qkv), n_frames, int(length), n_heads, head_dim, _ptr(out), _stream(stream)))
     return out
 
 
@@ -460,8 +446,16 @@ def et_encode_clip(handle, frames, merge_layer, sim_threshold, keep_ratio, L, D,
     return _trim(bufs, o, T)
 
 
-def et_encoder_set_frame_groups(handle, n_groups):
-    _check(load_library().et_encoder_set_frame_groups(handle, int(n_groups)))
+def et_encoder_block_qkv(handle, layer, x, stream=None):
+    """Row scales and fused q | k | v projection of encoder block `layer` on x (bf16 CUDA [rows, D]),
+    as the encode calls launch them.  Returns (qkv bf16 [rows, 3D], rstd float32 [rows])."""
+    lib = load_library()
+    _dev(x, torch.bfloat16, "x")
+    rows, D = x.shape
+    qkv = torch.empty((rows, 3 * D), dtype=torch.bfloat16, device=x.device)
+    rstd = torch.empty((max(rows, 1),), dtype=torch.float32, device=x.device)
+    _check(lib.et_encoder_block_qkv(handle, int(layer), _ptr(x), rows, _ptr(rstd), _ptr(qkv), _stream(stream)))
+    return qkv, rstd[:rows]
 
 
 def et_profile_enable(handle, on):
@@ -475,6 +469,20 @@ def et_profile_read(handle, reset=True):
     _check(load_library().et_profile_read(handle, ms, cnt, int(bool(reset))))
     return {(KERNEL_KINDS[i % ET_K_COUNT], i // ET_K_COUNT): (float(ms[i]), int(cnt[i]))
             for i in range(2 * ET_K_COUNT)}
+
+
+def et_merge_profile_enable(on):
+    _check(load_library().et_merge_profile_enable(int(bool(on))))
+
+
+def et_merge_profile_read(reset=True):
+    """Returns ({kind: (milliseconds, launches)}, total milliseconds, calls) of the stand-alone stage."""
+    ms = (C.c_double * ET_K_COUNT)()
+    cnt = (C.c_int64 * ET_K_COUNT)()
+    tot, calls = C.c_double(0.0), C.c_int64(0)
+    _check(load_library().et_merge_profile_read(ms, cnt, C.byref(tot), C.byref(calls), int(bool(reset))))
+    return ({KERNEL_KINDS[i]: (float(ms[i]), int(cnt[i])) for i in range(ET_K_COUNT) if cnt[i]},
+            float(tot.value), int(calls.value))
 
 
 def et_kernel_name(kind):
@@ -492,10 +500,6 @@ class Encoder:
         self.max_frames = max_frames
         self._ws = None
         self._bufs = {}
-
-    def set_frame_groups(self, n_groups):
-        with torch.cuda.device(self.device):
-            et_encoder_set_frame_groups(self.handle, n_groups)
 
     def encode(self, frames, merge_layer, sim_threshold, keep_ratio, stream=None):
         T = frames.shape[0]

@@ -156,13 +156,8 @@ __global__ __launch_bounds__(256) void im2col_kernel(const float *__restrict__ f
 // Both operands are k-contiguous, so both feed MFMA as 16-byte vectors straight from LDS.
 // The weight tile is MFMA operand "A" (rows = n) and the activation tile operand "B"
 // (columns = m): each lane then owns 4 consecutive n of one output row m per accumulator
-// quad, which packs to an 8-byte bf16 store.
-// Tiling: workgroup BM x BN x 64, WAVES_M x WAVES_N wavefronts, double-buffered LDS with the
-// next k-tile prefetched global -> registers while the current one is multiplied.
+// quad, which packs to an 8-byte bf16 piece.
 // ---------------------------------------------------------------------------------------
-constexpr int kBK = 64;
-constexpr int kLdsRow = kBK + 8;   // 144-byte row stride: 16-byte reads of 16 rows hit distinct banks
-
 __device__ __forceinline__ float gelu_tanh_f(float u) {
   // 0.5 u (1 + tanh(y)) = u / (1 + exp(-2y)),  y = sqrt(2/pi) (u + 0.044715 u^3)
   // exp(-2y) = exp2(u (c1 + c3 u^2)) with the factor -2 log2(e) sqrt(2/pi) folded into c1, c3;
@@ -173,46 +168,9 @@ __device__ __forceinline__ float gelu_tanh_f(float u) {
   return u * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(t));
 }
 
-// Epilogue shared by the GEMM kernels.  acc[a][b] is the 32 x 32 tile at rows n_base + 32a (MFMA
-// rows = output columns n) and columns m_base + 32b: the lane owns output row m = .. + r32 and,
-// per accumulator quad q, the four consecutive columns n = .. + 8q + 4grp + (0..3).
-template <int EPI, int FM, int FN>
-__device__ __forceinline__ void gemm_epilogue(f32x16 (&acc)[FN][FM], const GemmArgs &g, int m_base,
-                                              int n_base, int r32, int grp) {
-#pragma unroll
-  for (int b = 0; b < FM; ++b) {
-    const int m = m_base + b * 32 + r32;
-    if (m >= g.M) continue;
-    uint16_t *crow = g.C + (size_t)m * g.ldc;
-    const uint16_t *rrow = nullptr;
-    if (EPI == EPI_BIAS_RES) rrow = g.res + (size_t)(m % g.res_mod) * g.ldr;
-    const float rs = g.row_scale ? g.row_scale[m] : 1.0f;      // (fma(1, acc, bias) == acc + bias exactly)
-#pragma unroll
-    for (int a = 0; a < FN; ++a) {
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int n = n_base + a * 32 + q * 8 + grp * 4;
-        if (n >= g.n_store) continue;
-        const float4 bi = *reinterpret_cast<const float4 *>(g.bias + n);
-        float v0 = fmaf(rs, acc[a][b][q * 4 + 0], bi.x), v1 = fmaf(rs, acc[a][b][q * 4 + 1], bi.y);
-        float v2 = fmaf(rs, acc[a][b][q * 4 + 2], bi.z), v3 = fmaf(rs, acc[a][b][q * 4 + 3], bi.w);
-        if (EPI == EPI_BIAS_GELU) {
-          v0 = gelu_tanh_f(v0); v1 = gelu_tanh_f(v1); v2 = gelu_tanh_f(v2); v3 = gelu_tanh_f(v3);
-        }
-        if (EPI == EPI_BIAS_RES) {
-          const uint2 rr = *reinterpret_cast<const uint2 *>(rrow + n);
-          v0 += bf16lo_to_f32(rr.x); v1 += bf16hi_to_f32(rr.x);
-          v2 += bf16lo_to_f32(rr.y); v3 += bf16hi_to_f32(rr.y);
-        }
-        uint2 o;
-        o.x = cvt_pk_bf16(v0, v1);
-        o.y = cvt_pk_bf16(v2, v3);
-        *reinterpret_cast<uint2 *>(crow + n) = o;
-      }
-    }
-  }
-}
-
+// acc[a][b] is the 32 x 32 tile at rows n_base + 32a (MFMA rows = output columns n) and columns
+// m_base + 32b: the lane owns output row m = .. + r32 and, per accumulator quad q, the four
+// consecutive columns n = .. + 8q + 4grp + (0..3).
 // Epilogue for wavefront tiles 64 columns wide, staged through a private 4 KiB LDS slice per
 // wavefront so that every global access is a full 128-byte row segment (8 lanes x 16 bytes)
 // instead of 8-byte pieces scattered over 32 rows.  Per 32-row block: (residual only) the
@@ -221,7 +179,7 @@ __device__ __forceinline__ void gemm_epilogue(f32x16 (&acc)[FN][FM], const GemmA
 // pieces to the slice; finally the slice is read row-wise and stored.  16-byte slots of a row are
 // XOR-swizzled by (row >> 1) & 7.  LDS operations of one wavefront execute in order, so the phases
 // need no barrier.
-template <int EPI, int FM, int FN, int PIN = 0>
+template <int EPI, int FM, int FN>
 __device__ __forceinline__ void gemm_epilogue_lds(f32x16 (&acc)[FN][FM], const GemmArgs &g, int m_base,
                                                   int n_base, int lane, uint16_t *slice) {
   static_assert(FN % 2 == 0, "the staged epilogue handles 64-column pieces of the wavefront tile");
@@ -275,11 +233,7 @@ __device__ __forceinline__ void gemm_epilogue_lds(f32x16 (&acc)[FN][FM], const G
     }
 #pragma unroll
     for (int a = 0; a < 2; ++a) {
-      f32x16 av = acc[half * 2 + a][b];
-      if constexpr (PIN) {                      // one accumulator at a time leaves the accumulation registers
-        asm volatile("" : "+v"(av));
-        __builtin_amdgcn_sched_barrier(0);
-      }
+      const f32x16 av = acc[half * 2 + a][b];
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         float v0 = fmaf(rs, av[q * 4 + 0], bi[a][q].x), v1 = fmaf(rs, av[q * 4 + 1], bi[a][q].y);
@@ -309,114 +263,15 @@ __device__ __forceinline__ void gemm_epilogue_lds(f32x16 (&acc)[FN][FM], const G
   }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI>
-__global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(GemmArgs g, int tiles_m, int tiles_n) {
-  constexpr int NT = WAVES_M * WAVES_N * 64;
-  constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;    // wavefront tile
-  constexpr int FM = WTM / 32, FN = WTN / 32;              // MFMA tiles per wavefront
-  constexpr int A_CH = BM * (kBK / 8) / NT;                // 16-byte chunks per thread per k-tile
-  constexpr int W_CH = BN * (kBK / 8) / NT;
-  static_assert(BM * (kBK / 8) % NT == 0 && BN * (kBK / 8) % NT == 0, "tile/threads mismatch");
-  extern __shared__ __align__(16) uint16_t lds[];
-  uint16_t *As = lds;                                      // [2][BM][kLdsRow]
-  uint16_t *Ws = lds + 2 * BM * kLdsRow;                   // [2][BN][kLdsRow]
-
-  // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of tiles
-  // (n fastest) so that tiles sharing an activation row block meet in the same L2.
-  const int nblk = tiles_m * tiles_n;
-  int bid = blockIdx.x;
-  {
-    const int per = nblk / 8, rem = nblk % 8, xcd = bid % 8, slot = bid / 8;
-    bid = xcd * per + (xcd < rem ? xcd : rem) + slot;
-  }
-  const int tile_m = bid / tiles_n, tile_n = bid % tiles_n;
-  const int m0 = tile_m * BM, n0 = tile_n * BN;
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-  const int r32 = lane & 31, grp = lane >> 5;
-
-  const uint16_t *a_src[A_CH];
-  const uint16_t *w_src[W_CH];
-  int a_dst[A_CH], w_dst[W_CH];
-#pragma unroll
-  for (int i = 0; i < A_CH; ++i) {
-    const int c = i * NT + tid, row = c >> 3, kc = c & 7;
-    int m = m0 + row;
-    if (m >= g.M) m = g.M - 1;                             // clamp: rows past M are never stored
-    a_src[i] = g.A + (size_t)m * g.lda + kc * 8;
-    a_dst[i] = row * kLdsRow + kc * 8;
-  }
-#pragma unroll
-  for (int i = 0; i < W_CH; ++i) {
-    const int c = i * NT + tid, row = c >> 3, kc = c & 7;
-    w_src[i] = g.W + (size_t)(n0 + row) * g.K + kc * 8;    // W is padded to whole tiles in n
-    w_dst[i] = row * kLdsRow + kc * 8;
-  }
-
-  f32x16 acc[FN][FM];
-#pragma unroll
-  for (int a = 0; a < FN; ++a)
-#pragma unroll
-    for (int b = 0; b < FM; ++b)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
-
-  u32x4 a_reg[A_CH], w_reg[W_CH];
-#pragma unroll
-  for (int i = 0; i < A_CH; ++i) a_reg[i] = *reinterpret_cast<const u32x4 *>(a_src[i]);
-#pragma unroll
-  for (int i = 0; i < W_CH; ++i) w_reg[i] = *reinterpret_cast<const u32x4 *>(w_src[i]);
-#pragma unroll
-  for (int i = 0; i < A_CH; ++i) *reinterpret_cast<u32x4 *>(As + a_dst[i]) = a_reg[i];
-#pragma unroll
-  for (int i = 0; i < W_CH; ++i) *reinterpret_cast<u32x4 *>(Ws + w_dst[i]) = w_reg[i];
-  __syncthreads();
-
-  const int kt_n = g.K / kBK;
-  for (int kt = 0; kt < kt_n; ++kt) {
-    const int cur = kt & 1;
-    // prefetch the next k-tile (the last iteration re-reads its own tile; that copy is unused)
-    const int ko = (kt + 1 < kt_n ? kt + 1 : kt) * kBK;
-#pragma unroll
-    for (int i = 0; i < A_CH; ++i) a_reg[i] = *reinterpret_cast<const u32x4 *>(a_src[i] + ko);
-#pragma unroll
-    for (int i = 0; i < W_CH; ++i) w_reg[i] = *reinterpret_cast<const u32x4 *>(w_src[i] + ko);
-    const uint16_t *Ac = As + cur * BM * kLdsRow + (wm * WTM + r32) * kLdsRow + grp * 8;
-    const uint16_t *Wc = Ws + cur * BN * kLdsRow + (wn * WTN + r32) * kLdsRow + grp * 8;
-#pragma unroll
-    for (int ks = 0; ks < kBK / 16; ++ks) {
-      u32x4 fa[FM], fw[FN];
-#pragma unroll
-      for (int b = 0; b < FM; ++b) fa[b] = *reinterpret_cast<const u32x4 *>(Ac + b * 32 * kLdsRow + ks * 16);
-#pragma unroll
-      for (int a = 0; a < FN; ++a) fw[a] = *reinterpret_cast<const u32x4 *>(Wc + a * 32 * kLdsRow + ks * 16);
-#pragma unroll
-      for (int a = 0; a < FN; ++a)
-#pragma unroll
-        for (int b = 0; b < FM; ++b) acc[a][b] = mfma32(fw[a], fa[b], acc[a][b]);
-    }
-    uint16_t *An = As + (cur ^ 1) * BM * kLdsRow;
-    uint16_t *Wn = Ws + (cur ^ 1) * BN * kLdsRow;
-#pragma unroll
-    for (int i = 0; i < A_CH; ++i) *reinterpret_cast<u32x4 *>(An + a_dst[i]) = a_reg[i];
-#pragma unroll
-    for (int i = 0; i < W_CH; ++i) *reinterpret_cast<u32x4 *>(Wn + w_dst[i]) = w_reg[i];
-    __syncthreads();
-  }
-
-  gemm_epilogue<EPI, FM, FN>(acc, g, m0 + wm * WTM, n0 + wn * WTN, r32, grp);
-}
-
 // ---------------------------------------------------------------------------------------
-// Same GEMM, operands brought in by direct global -> LDS loads (global_load_lds_dwordx4): no
-// staging registers and no LDS write instructions.  One wavefront load moves 64 x 16 bytes to
-// 1 KiB of consecutive LDS, i.e. 8 tile rows of 64 bf16; lane L lands at row L / 8, slot L % 8
-// and fetches the global 16-byte chunk (slot ^ swz(row)), an XOR swizzle that spreads the
-// MFMA fragment reads (same k-chunk, consecutive rows) over the banks.  STAGES k-tiles are in
-// flight (one per stage); waits are explicit (vmcnt) because the loads are asynchronous to the
-// wavefront: a tile is complete once this wavefront's loads have landed AND the workgroup barrier
-// after that wait has been passed.
+// Operands are brought in by direct global -> LDS loads (global_load_lds_dwordx4): no staging
+// registers and no LDS write instructions.  One wavefront load moves 64 x 16 bytes to 1 KiB of
+// consecutive LDS, i.e. 8 tile rows of 64 bf16; lane L lands at row L / 8, slot L % 8 and fetches
+// the global 16-byte chunk (slot ^ swz(row)), an XOR swizzle that spreads the MFMA fragment reads
+// (same k-chunk, consecutive rows) over the banks.  STAGES k-tiles are in flight (one per stage);
+// waits are explicit (vmcnt) because the loads are asynchronous to the wavefront: a tile is
+// complete once this wavefront's loads have landed AND the workgroup barrier after that wait has
+// been passed.
 // ---------------------------------------------------------------------------------------
 #define ET_LDS_DMA16(gptr, lptr)                                                             \
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gptr),   \
@@ -433,147 +288,14 @@ __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, int MINB, int EPI>
-__global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_dma_kernel(GemmArgs g, int tiles_m, int tiles_n) {
-  constexpr int NW = WAVES_M * WAVES_N;
-  constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
-  constexpr int FM = WTM / 32, FN = WTN / 32;
-  constexpr int CPR = BK / 8;                       // 16-byte chunks per tile row
-  constexpr int RPB = 64 / CPR;                     // tile rows per 1 KiB wavefront load
-  constexpr int SWZ = (BK == 64) ? 1 : 2;           // rows 2^SWZ apart share a bank base
-  constexpr int A_BLK = BM / RPB / NW, W_BLK = BN / RPB / NW;   // loads per wavefront per k-tile
-  constexpr int LOADS = A_BLK + W_BLK;
-  constexpr int STAGE_ELEMS = (BM + BN) * BK;
-  constexpr int KS = BK / 16;
-  static_assert(BK == 64 || BK == 32, "k-tile is 64 or 32");
-  static_assert(BM % (RPB * NW) == 0 && BN % (RPB * NW) == 0, "tile rows must split evenly over the wavefronts");
-  extern __shared__ __align__(16) uint16_t lds[];
-
-  const int nblk = tiles_m * tiles_n;
-  int bid = blockIdx.x;
-  {
-    const int per = nblk / 8, rem = nblk % 8, xcd = bid % 8, slot = bid / 8;
-    bid = xcd * per + (xcd < rem ? xcd : rem) + slot;
-  }
-  const int tile_m = bid / tiles_n, tile_n = bid % tiles_n;
-  const int m0 = tile_m * BM, n0 = tile_n * BN;
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS destinations of the loads stay scalar
-  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-  const int r32 = lane & 31, grp = lane >> 5;
-
-  // global source of this lane for each of the wavefront's loads (advanced by BK elements per k-tile)
-  const uint16_t *a_src[A_BLK];
-  const uint16_t *w_src[W_BLK];
-  const int lrow = lane / CPR, lslot = lane % CPR;
-#pragma unroll
-  for (int i = 0; i < A_BLK; ++i) {
-    const int row = (wave * A_BLK + i) * RPB + lrow;
-    int m = m0 + row;
-    if (m >= g.M) m = g.M - 1;
-    a_src[i] = g.A + (size_t)m * g.lda + ((lslot ^ ((row >> SWZ) & (CPR - 1))) * 8);
-  }
-#pragma unroll
-  for (int i = 0; i < W_BLK; ++i) {
-    const int row = (wave * W_BLK + i) * RPB + lrow;
-    w_src[i] = g.W + (size_t)(n0 + row) * g.K + ((lslot ^ ((row >> SWZ) & (CPR - 1))) * 8);
-  }
-  auto issue = [&](int stage, int kt) {
-    uint16_t *as = lds + stage * STAGE_ELEMS;
-    uint16_t *ws = as + BM * BK;
-    const int ko = kt * BK;
-#pragma unroll
-    for (int i = 0; i < A_BLK; ++i) ET_LDS_DMA16(a_src[i] + ko, as + (wave * A_BLK + i) * 512);
-#pragma unroll
-    for (int i = 0; i < W_BLK; ++i) ET_LDS_DMA16(w_src[i] + ko, ws + (wave * W_BLK + i) * 512);
-  };
-
-  // fragment read offsets (elements): row R, k-chunk (2 ks + grp) lives at slot chunk ^ swz(R)
-  const int fx = (r32 >> SWZ) & (CPR - 1);
-  int koff[KS];
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks) koff[ks] = (((2 * ks + grp) ^ fx) * 8);
-  const int a_row = (wm * WTM + r32) * BK, w_row = (wn * WTN + r32) * BK;
-
-  f32x16 acc[FN][FM];
-#pragma unroll
-  for (int a = 0; a < FN; ++a)
-#pragma unroll
-    for (int b = 0; b < FM; ++b)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
-
-  const int kt_n = g.K / BK;
-  // prologue: every stage gets a tile (tiles past the end re-read the last one; never used)
-#pragma unroll
-  for (int st = 0; st < STAGES; ++st) issue(st, st < kt_n ? st : kt_n - 1);
-
-  // Fragments are double-buffered in registers: the LDS reads of k-step s+1 are issued under the
-  // MFMAs of step s, also across k-tiles (the one barrier per tile sits before the tile's last step).
-  u32x4 fa[2][FM], fw[2][FN];
-  auto read_frags = [&](int buf, int stage, int ks) {
-    const uint16_t *as = lds + stage * STAGE_ELEMS;
-    const uint16_t *ws = as + BM * BK;
-#pragma unroll
-    for (int b = 0; b < FM; ++b) fa[buf][b] = *reinterpret_cast<const u32x4 *>(as + a_row + b * 32 * BK + koff[ks]);
-#pragma unroll
-    for (int a = 0; a < FN; ++a) fw[buf][a] = *reinterpret_cast<const u32x4 *>(ws + w_row + a * 32 * BK + koff[ks]);
-  };
-  auto mfma_step = [&](int buf) {
-#pragma unroll
-    for (int a = 0; a < FN; ++a)
-#pragma unroll
-      for (int b = 0; b < FM; ++b) acc[a][b] = mfma32(fw[buf][a], fa[buf][b], acc[a][b]);
-  };
-  // scheduling hint for one step: alternate MFMA / LDS read until the reads are placed
-  auto interleave = [&]() {
-#pragma unroll
-    for (int i = 0; i < FM + FN; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
-    }
-    __builtin_amdgcn_sched_group_barrier(0x008, FM * FN - (FM + FN), 0);
-  };
-
-  wait_vmcnt<(STAGES - 1) * LOADS>();    // tile 0 has landed
-  __builtin_amdgcn_s_barrier();
-  asm volatile("" ::: "memory");
-  read_frags(0, 0, 0);
-
-  for (int kt = 0; kt < kt_n; ++kt) {
-    const int stage = kt % STAGES;
-#pragma unroll
-    for (int ks = 0; ks < KS - 1; ++ks) {
-      read_frags((ks + 1) & 1, stage, ks + 1);
-      mfma_step(ks & 1);
-      interleave();
-    }
-    // last step of tile kt: tile kt+1 must have landed (at most STAGES-2 newer tiles outstanding) and
-    // this wavefront's reads of tile kt must have returned before its stage is handed to the loads
-    wait_vmcnt<(STAGES - 2) * LOADS>();
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-    {
-      const int nk = kt + STAGES;
-      issue(stage, nk < kt_n ? nk : kt_n - 1);
-    }
-    read_frags(KS & 1, (kt + 1) % STAGES, 0);
-    mfma_step((KS - 1) & 1);
-    interleave();
-  }
-  wait_vmcnt<0>();                     // drain the padding loads before the workgroup's LDS is released
-  gemm_epilogue<EPI, FM, FN>(acc, g, m0 + wm * WTM, n0 + wn * WTN, r32, grp);
-}
-
 // ---------------------------------------------------------------------------------------
-// Persistent form of the kernel above: one workgroup per compute-unit slot walks over its output
-// tiles t = b, b + G, b + 2G, ... and treats their k-tiles as ONE stream through the LDS stages,
-// so the loads of the next output tile are already in flight (and its first fragments already in
+// The kernel is persistent: one workgroup per compute-unit slot walks over its output tiles
+// t = b, b + G, b + 2G, ... and treats their k-tiles as ONE stream through the LDS stages, so the
+// loads of the next output tile are already in flight (and its first fragments already in
 // registers) while the finished tile's epilogue runs.  That removes the per-tile prologue latency
 // and the workgroup relaunch between tiles.
 // ---------------------------------------------------------------------------------------
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, int MINB, int EPI, int ACCA = 0>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, int MINB, int EPI>
 __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kernel(GemmArgs g, int tiles_m, int tiles_n) {
   constexpr int NW = WAVES_M * WAVES_N;
   constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
@@ -586,13 +308,14 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
   // 64 KiB of a k-tile keep it busy for ~1000 cycles and block whoever issues them; the wavefront
   // that shares the SIMD and issues none goes straight on with its MFMAs, and the loader does its
   // own while the other one waits at the next barrier.
-  constexpr bool SPLIT_LOADERS = (NW == 8 && MINB == 1 && ACCA <= 0);
+  constexpr bool SPLIT_LOADERS = (NW == 8 && MINB == 1);
   constexpr int LW = SPLIT_LOADERS ? NW / 2 : NW;                    // wavefronts that load
   constexpr int A_BLK = BM / RPB / LW, W_BLK = BN / RPB / LW;
   constexpr int LOADS = A_BLK + W_BLK;
   constexpr int STAGE_ELEMS = (BM + BN) * BK;
   constexpr int KS = BK / 16;
   static_assert(BK == 64 || BK == 32, "k-tile is 64 or 32");
+  static_assert(WTN % 64 == 0, "the staged epilogue handles 64-column pieces of the wavefront tile");
   static_assert(BM % (RPB * LW) == 0 && BN % (RPB * LW) == 0, "tile rows must split evenly over the loading wavefronts");
   static_assert(A_BLK % 4 == 0 || A_BLK < 4, "loads are issued in groups of four sharing one M0 value");
   extern __shared__ __align__(16) uint16_t lds[];
@@ -683,7 +406,10 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
       default: ET_LDS_DMA16_OFF(src, dst, 3072); break;
     }
   };
-  auto issue_advance = [&]() {
+  auto issue_next = [&](int stage) {
+    if (!is_loader) return;
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) issue_one(stage, i);
     if (++load_kt == kt_n) {                        // past the stream's end the last k-tile is re-read (unused)
       if (load_tile + 1 < n_my) {
         load_kt = 0;
@@ -693,12 +419,6 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
       }
     }
   };
-  auto issue_next = [&](int stage) {
-    if (!is_loader) return;
-#pragma unroll
-    for (int i = 0; i < LOADS; ++i) issue_one(stage, i);
-    issue_advance();
-  };
 
   const int fx = (r32 >> SWZ) & (CPR - 1);
   int koff[KS];
@@ -707,36 +427,22 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
   const int a_row = (wm * WTM + r32) * BK, w_row = (wn * WTN + r32) * BK;
 
   f32x16 acc[FN][FM];
-  auto clear_acc = [&]() {        // in place: 0 * 0 + 0 through the matrix unit (no second copy of the accumulators)
-    const u32x4 z = u32x4{0u, 0u, 0u, 0u};
-#pragma unroll
-    for (int a = 0; a < FN; ++a)
-#pragma unroll
-      for (int b = 0; b < FM; ++b)
-        asm volatile("s_nop 4\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %1, 0" : "+a"(acc[a][b]) : "v"(z));   // idle states: the zero operand may have just been written
-  };
-  if constexpr (ACCA <= 0) {
+  auto clear_acc = [&]() {
 #pragma unroll
     for (int a = 0; a < FN; ++a)
 #pragma unroll
       for (int b = 0; b < FM; ++b)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
-  } else {
-    clear_acc();
-  }
+  };
+  clear_acc();
 
   if (is_loader) set_load_tile(0);
-  if constexpr (ACCA == 3) {      // spread loads: the last stage gets its first part here, the rest in the first unit
 #pragma unroll
-    for (int st = 0; st < STAGES - 1; ++st) issue_next(st);
-#pragma unroll
-    for (int i = 0; i < LOADS / KS; ++i) issue_one(STAGES - 1, i);
-  } else {
-#pragma unroll
-    for (int st = 0; st < STAGES; ++st) issue_next(st);
-  }
+  for (int st = 0; st < STAGES; ++st) issue_next(st);
 
+  // Fragments are double-buffered in registers: the LDS reads of k-step s+1 are issued under the
+  // MFMAs of step s, also across k-tiles (the one barrier per tile sits before the tile's last step).
   u32x4 fa[2][FM], fw[2][FN];
   auto read_frags = [&](int buf, int stage, int ks) {
     const uint16_t *as = lds + stage * STAGE_ELEMS;
@@ -750,86 +456,35 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
 #pragma unroll
     for (int a = 0; a < FN; ++a)
 #pragma unroll
-      for (int b = 0; b < FM; ++b) {
-        if constexpr (ACCA > 0) {
-          asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc[a][b]) : "v"(fw[buf][a]), "v"(fa[buf][b]));
-        } else {
-          acc[a][b] = mfma32(fw[buf][a], fa[buf][b], acc[a][b]);
-        }
-      }
+      for (int b = 0; b < FM; ++b) acc[a][b] = mfma32(fw[buf][a], fa[buf][b], acc[a][b]);
   };
-  auto mfma_first = [&](int buf) {            // first MFMA of an output tile: C = 0 (defines the accumulators)
-#pragma unroll
-    for (int a = 0; a < FN; ++a)
-#pragma unroll
-      for (int b = 0; b < FM; ++b)
-        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=a"(acc[a][b]) : "v"(fw[buf][a]), "v"(fa[buf][b]));
-  };
-  // ACCA: MFMAs on fragment buffer `cur` with the reads of the next k-slice (stage nst, slice nks, into
-  // the other buffer) placed one after each of the first FM + FN MFMAs.  The asm statements are
-  // volatile, so this order is the issue order.
-  // Loads lo .. hi-1 of the k-tile bound for `load_stage` ride under this group's MFMAs (lo == hi: none).
-  auto step_acca = [&](int cur, int nst, int nks, int lo, int hi, int load_stage) {
-    const uint16_t *as = lds + nst * STAGE_ELEMS;
-    const uint16_t *ws = as + BM * BK;
-    const int nxt = cur ^ 1;
-    int idx = 0;
-#pragma unroll
-    for (int a = 0; a < FN; ++a)
-#pragma unroll
-      for (int b = 0; b < FM; ++b) {
-        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc[a][b]) : "v"(fw[cur][a]), "v"(fa[cur][b]));
-        if (idx < FM)
-          fa[nxt][idx] = *reinterpret_cast<const u32x4 *>(as + a_row + idx * 32 * BK + koff[nks]);
-        else if (idx < FM + FN)
-          fw[nxt][idx - FM] = *reinterpret_cast<const u32x4 *>(ws + w_row + (idx - FM) * 32 * BK + koff[nks]);
-#pragma unroll
-        for (int i = lo + idx * (hi - lo) / (FM * FN); i < lo + (idx + 1) * (hi - lo) / (FM * FN); ++i)
-          issue_one(load_stage, i);
-        ++idx;
-      }
-    __builtin_amdgcn_sched_barrier(0);
-  };
-  // ACCA == 3 (needs STAGES >= 3): the loads of a k-tile are spread over all KS groups between two
-  // barriers instead of riding under one group, which keeps the address unit below its rate.
-  constexpr bool SPREAD = (ACCA == 3);
-  static_assert(!SPREAD || STAGES >= 3, "spread loads need a stage that stays free for a whole unit");
-  constexpr int PART = LOADS / KS;
+  // scheduling hint for one step: alternate MFMA / LDS read until the reads are placed
   auto interleave = [&]() {
-    if constexpr (ACCA > 0) {
-      __builtin_amdgcn_sched_barrier(0);
-    } else {
 #pragma unroll
-      for (int i = 0; i < FM + FN; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      }
-      __builtin_amdgcn_sched_group_barrier(0x008, FM * FN - (FM + FN), 0);
+    for (int i = 0; i < FM + FN; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
     }
+    __builtin_amdgcn_sched_group_barrier(0x008, FM * FN - (FM + FN), 0);
   };
 
-  wait_vmcnt<SPREAD ? (STAGES - 2) * LOADS + PART : (STAGES - 1) * LOADS>();
+  wait_vmcnt<(STAGES - 1) * LOADS>();    // k-tile 0 has landed
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
   read_frags(0, 0, 0);
 
-  int stage = 0, kt = 0, my_tile = 0, relax = 0, free_stage = STAGES - 1;
+  int stage = 0, kt = 0, my_tile = 0, relax = 0;
   constexpr int N_ST = FM * (FN / 2) * 4;            // global stores per wavefront in the staged epilogue
   const int units = n_my * kt_n;
   for (int u = 0; u < units; ++u) {
 #pragma unroll
     for (int ks = 0; ks < KS - 1; ++ks) {
-      if constexpr (SPREAD) {
-        step_acca(ks & 1, stage, ks + 1, (ks + 1) * PART, (ks + 2) * PART, free_stage);
-        if (ks == KS - 2) issue_advance();
-      } else if constexpr (ACCA > 0) {
-        step_acca(ks & 1, stage, ks + 1, 0, 0, 0);
-      } else {
-        read_frags((ks + 1) & 1, stage, ks + 1);
-        mfma_step(ks & 1);
-        interleave();
-      }
+      read_frags((ks + 1) & 1, stage, ks + 1);
+      mfma_step(ks & 1);
+      interleave();
     }
+    // Last step of k-tile u: tile u+1 must have landed (at most STAGES-2 newer tiles outstanding) and
+    // this wavefront's reads of tile u must have returned before its stage is handed to the loads.
     // Vector-memory operations retire in issue order.  For STAGES - 1 units after the epilogue of
     // an interior tile (every lane stored: exactly N_ST store instructions per wavefront) those
     // stores are younger than the loads awaited here, so they may stay in flight and drain under
@@ -844,54 +499,31 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, MINB) void gemm_stream_kerne
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     const int next_stage = (stage + 1 == STAGES) ? 0 : stage + 1;
-    if constexpr (SPREAD) {
-      free_stage = stage;
-      step_acca((KS - 1) & 1, next_stage, 0, 0, PART, stage);
-    } else if constexpr (ACCA > 0) {
-      step_acca((KS - 1) & 1, next_stage, 0, 0, LOADS, stage);
-      issue_advance();
-    } else {
-      issue_next(stage);
-      read_frags(KS & 1, next_stage, 0);
-      mfma_step((KS - 1) & 1);
-      interleave();
-    }
+    issue_next(stage);
+    read_frags(KS & 1, next_stage, 0);
+    mfma_step((KS - 1) & 1);
+    interleave();
     stage = next_stage;
     if (++kt == kt_n) {                             // an output tile is complete
       int m0, n0;
       tile_of(my_tile, m0, n0);
-      if constexpr (ACCA > 0) asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
-      if constexpr (WTN % 64 == 0) {
-        gemm_epilogue_lds<EPI, FM, FN, (ACCA > 0)>(acc, g, m0 + wm * WTM, n0 + wn * WTN, lane,
-                                             lds + STAGES * STAGE_ELEMS + wave * (32 * 64));
-        // (with spread loads the last k-tile issued before the stores is one unit older)
-        if (m0 + BM <= g.M && n0 + BN <= g.n_store) relax = SPREAD ? STAGES - 2 : STAGES - 1;
-      } else {
-        gemm_epilogue<EPI, FM, FN>(acc, g, m0 + wm * WTM, n0 + wn * WTN, r32, grp);
-      }
-      if constexpr (ACCA <= 0) {
-#pragma unroll
-        for (int a = 0; a < FN; ++a)
-#pragma unroll
-          for (int b = 0; b < FM; ++b)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
-      } else {
-        clear_acc();
-      }
+      gemm_epilogue_lds<EPI, FM, FN>(acc, g, m0 + wm * WTM, n0 + wn * WTN, lane,
+                                     lds + STAGES * STAGE_ELEMS + wave * (32 * 64));
+      if (m0 + BM <= g.M && n0 + BN <= g.n_store) relax = STAGES - 1;
+      clear_acc();
       kt = 0;
       ++my_tile;
     }
   }
-  wait_vmcnt<0>();
+  wait_vmcnt<0>();                     // drain the padding loads before the workgroup's LDS is released
 }
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, int MINB = 1, int ACCA = 0>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, int MINB = 1>
 int launch_gemm_stream_cfg(const GemmArgs &g, hipStream_t s) {
   constexpr int NT = WAVES_M * WAVES_N * 64;
-  // k-tile stages plus, for 64-column wavefront tiles, one 4 KiB epilogue slice per wavefront
+  // k-tile stages plus one 4 KiB epilogue slice per wavefront
   constexpr size_t lds_bytes = (size_t)STAGES * (BM + BN) * BK * sizeof(uint16_t) +
-                               (((BN / WAVES_N) % 64 == 0) ? (size_t)WAVES_M * WAVES_N * 32 * 64 * sizeof(uint16_t) : 0);
+                               (size_t)WAVES_M * WAVES_N * 32 * 64 * sizeof(uint16_t);
   static_assert(lds_bytes <= 160 * 1024, "LDS budget");
   static int n_cu = 0;
   if (n_cu == 0) {
@@ -906,64 +538,7 @@ int launch_gemm_stream_cfg(const GemmArgs &g, hipStream_t s) {
   const dim3 grid(n_tiles < slots ? n_tiles : slots), block(NT);
 #define ET_GEMM_LAUNCH(E)                                                                        \
   {                                                                                              \
-    auto kern = gemm_stream_kernel<BM, BN, BK, WAVES_M, WAVES_N, STAGES, MINB, E, ACCA>;         \
-    static bool attr_set = false;                                                                \
-    if (!attr_set) {                                                                             \
-      ET_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                           \
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));   \
-      attr_set = true;                                                                           \
-    }                                                                                            \
-    hipLaunchKernelGGL(kern, grid, block, lds_bytes, s, g, tiles_m, tiles_n);                    \
-  }
-  switch (g.epilogue) {
-    case EPI_BIAS: ET_GEMM_LAUNCH(EPI_BIAS); break;
-    case EPI_BIAS_GELU: ET_GEMM_LAUNCH(EPI_BIAS_GELU); break;
-    case EPI_BIAS_RES: ET_GEMM_LAUNCH(EPI_BIAS_RES); break;
-    default: set_error("unknown epilogue %d", g.epilogue); return ET_ERR_INVALID_ARG;
-  }
-#undef ET_GEMM_LAUNCH
-  ET_LAUNCH_CHECK();
-  return ET_OK;
-}
-
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, int MINB = 1>
-int launch_gemm_dma_cfg(const GemmArgs &g, hipStream_t s) {
-  constexpr int NT = WAVES_M * WAVES_N * 64;
-  constexpr size_t lds_bytes = (size_t)STAGES * (BM + BN) * BK * sizeof(uint16_t);
-  static_assert(lds_bytes <= 160 * 1024, "LDS budget");
-  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.n_store + BN - 1) / BN;
-  const dim3 grid(tiles_m * tiles_n), block(NT);
-#define ET_GEMM_LAUNCH(E)                                                                        \
-  {                                                                                              \
-    auto kern = gemm_dma_kernel<BM, BN, BK, WAVES_M, WAVES_N, STAGES, MINB, E>;                        \
-    static bool attr_set = false;                                                                \
-    if (!attr_set) {                                                                             \
-      ET_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                           \
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));   \
-      attr_set = true;                                                                           \
-    }                                                                                            \
-    hipLaunchKernelGGL(kern, grid, block, lds_bytes, s, g, tiles_m, tiles_n);                    \
-  }
-  switch (g.epilogue) {
-    case EPI_BIAS: ET_GEMM_LAUNCH(EPI_BIAS); break;
-    case EPI_BIAS_GELU: ET_GEMM_LAUNCH(EPI_BIAS_GELU); break;
-    case EPI_BIAS_RES: ET_GEMM_LAUNCH(EPI_BIAS_RES); break;
-    default: set_error("unknown epilogue %d", g.epilogue); return ET_ERR_INVALID_ARG;
-  }
-#undef ET_GEMM_LAUNCH
-  ET_LAUNCH_CHECK();
-  return ET_OK;
-}
-
-template <int BM, int BN, int WAVES_M, int WAVES_N>
-int launch_gemm_cfg(const GemmArgs &g, hipStream_t s) {
-  constexpr int NT = WAVES_M * WAVES_N * 64;
-  constexpr size_t lds_bytes = (size_t)2 * (BM + BN) * kLdsRow * sizeof(uint16_t);
-  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.n_store + BN - 1) / BN;
-  const dim3 grid(tiles_m * tiles_n), block(NT);
-#define ET_GEMM_LAUNCH(E)                                                                        \
-  {                                                                                              \
-    auto kern = gemm_kernel<BM, BN, WAVES_M, WAVES_N, E>;                                        \
+    auto kern = gemm_stream_kernel<BM, BN, BK, WAVES_M, WAVES_N, STAGES, MINB, E>;               \
     static bool attr_set = false;                                                                \
     if (!attr_set) {                                                                             \
       ET_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                           \
@@ -1489,54 +1064,26 @@ int launch_im2col(const float *frames, int T, int C, int H, int W, int P, int Kp
   return ET_OK;
 }
 
-int gemm_config_count() { return 36; }
+// Workgroup tilings of the GEMM kernel (tile_config of et_gemm_bf16):
+//   0  256 x 256 x 64, 8 wavefronts (2 x 4), one workgroup per compute unit
+//   1  128 x 128 x 64, 4 wavefronts (2 x 2), two workgroups per compute unit
+//   2   64 x 128 x 64, 4 wavefronts (2 x 2), two workgroups per compute unit
+enum { kCfgBig = 0, kCfg128 = 1, kCfg64 = 2, kCfgCount = 3 };
+int gemm_config_count() { return kCfgCount; }
 
 static int launch_gemm_id(const GemmArgs &g, hipStream_t s, int cfg) {
   switch (cfg) {
-    case 0: return launch_gemm_cfg<128, 128, 2, 2>(g, s);
-    case 1: return launch_gemm_cfg<256, 128, 2, 2>(g, s);
-    case 2: return launch_gemm_cfg<256, 256, 2, 4>(g, s);
-    case 3: return launch_gemm_cfg<256, 128, 2, 4>(g, s);
-    case 4: return launch_gemm_cfg<128, 256, 2, 2>(g, s);
-    case 5: return launch_gemm_cfg<256, 256, 2, 2>(g, s);
-    case 6: return launch_gemm_dma_cfg<256, 256, 64, 2, 4, 2>(g, s);
-    case 7: return launch_gemm_dma_cfg<256, 256, 32, 2, 4, 4>(g, s);
-    case 8: return launch_gemm_dma_cfg<128, 128, 64, 2, 2, 2>(g, s);
-    case 9: return launch_gemm_dma_cfg<128, 128, 32, 2, 2, 4>(g, s);
-    case 10: return launch_gemm_dma_cfg<128, 128, 32, 2, 2, 3>(g, s);
-    case 11: return launch_gemm_dma_cfg<256, 128, 64, 2, 2, 3>(g, s);
-    case 12: return launch_gemm_dma_cfg<256, 256, 32, 2, 2, 4>(g, s);
-    case 13: return launch_gemm_dma_cfg<256, 128, 32, 2, 4, 4>(g, s);
-    case 14: return launch_gemm_dma_cfg<256, 256, 32, 2, 4, 3>(g, s);
-    case 15: return launch_gemm_dma_cfg<256, 128, 32, 2, 2, 4>(g, s);
-    case 16: return launch_gemm_dma_cfg<256, 128, 32, 2, 2, 3, 2>(g, s);
-    case 17: return launch_gemm_dma_cfg<256, 128, 32, 2, 2, 2, 2>(g, s);
-    case 18: return launch_gemm_dma_cfg<128, 256, 32, 2, 2, 3, 2>(g, s);
-    case 19: return launch_gemm_dma_cfg<256, 128, 64, 2, 2, 2, 1>(g, s);
-    case 20: return launch_gemm_stream_cfg<256, 256, 64, 2, 4, 2>(g, s);
-    case 21: return launch_gemm_stream_cfg<256, 256, 32, 2, 4, 3>(g, s);
-    case 22: return launch_gemm_stream_cfg<128, 128, 64, 2, 2, 2, 2>(g, s);
-    case 23: return launch_gemm_stream_cfg<128, 128, 32, 2, 2, 4, 2>(g, s);
-    case 24: return launch_gemm_stream_cfg<256, 128, 64, 2, 4, 2>(g, s);
-    case 25: return launch_gemm_stream_cfg<256, 128, 32, 4, 2, 4>(g, s);
-    case 26: return launch_gemm_stream_cfg<64, 128, 64, 2, 2, 2, 2>(g, s);
-    case 27: return launch_gemm_stream_cfg<64, 128, 64, 2, 2, 3, 2>(g, s);
-    case 28: return launch_gemm_stream_cfg<128, 64, 64, 4, 1, 2, 2>(g, s);
-    case 29: return launch_gemm_stream_cfg<128, 128, 64, 2, 2, 3, 1>(g, s);
-    case 30: return launch_gemm_stream_cfg<256, 256, 32, 2, 4, 4, 1>(g, s);
-    case 31: return launch_gemm_stream_cfg<256, 256, 32, 4, 2, 4, 1>(g, s);
-    case 32: return launch_gemm_stream_cfg<256, 256, 32, 4, 2, 3, 1>(g, s);
-    case 33: return launch_gemm_stream_cfg<256, 256, 64, 2, 2, 2, 1, 1>(g, s);
-    case 34: return launch_gemm_stream_cfg<256, 256, 32, 2, 2, 4, 1, 3>(g, s);
-    case 35: return launch_gemm_stream_cfg<256, 256, 32, 2, 2, 3, 1, 3>(g, s);
+    case kCfgBig: return launch_gemm_stream_cfg<256, 256, 64, 2, 4, 2>(g, s);
+    case kCfg128: return launch_gemm_stream_cfg<128, 128, 64, 2, 2, 2, 2>(g, s);
+    case kCfg64: return launch_gemm_stream_cfg<64, 128, 64, 2, 2, 2, 2>(g, s);
     default: set_error("unknown gemm tile configuration %d", cfg); return ET_ERR_INVALID_ARG;
   }
 }
 
 int launch_gemm(const GemmArgs &g, hipStream_t s, int force_cfg) {
   if (g.M <= 0) return ET_OK;
-  if (g.K % 64 != 0 || g.n_store % 4 != 0) {
-    set_error("gemm: K = %d must be a multiple of 64 and n_store = %d of 4", g.K, g.n_store);
+  if (g.K % 64 != 0 || g.n_store % 8 != 0) {
+    set_error("gemm: K = %d must be a multiple of 64 and n_store = %d of 8", g.K, g.n_store);
     return ET_ERR_INVALID_ARG;
   }
   if (force_cfg >= 0) return launch_gemm_id(g, s, force_cfg);
@@ -1546,18 +1093,15 @@ int launch_gemm(const GemmArgs &g, hipStream_t s, int force_cfg) {
   // costs 0.6 of it, 0.52 when at most 256 tiles leave every workgroup alone on its unit, 0.57 per
   // round when there are several; 64 x 128 tiles 0.5 / 0.3 / 0.4.  The makespan is whole rounds:
   // a workgroup with one tile more than the others finishes a tile time later.
-  //  - n_store not a multiple of 8: the 4-column epilogue of the non-persistent kernels.
   //  - big tiles: a partly filled last tile row or column costs whole tiles, so it may be split
   //    off into a launch of its own with small tiles (only if that saves at least half a round).
   const long t256 = (long)((g.M + 255) / 256) * ((g.n_store + 255) / 256);
-  const long t128 = (long)((g.M + 127) / 128) * ((g.n_store + 127) / 128);
-  if (g.n_store % 8 != 0) return launch_gemm_id(g, s, t128 <= 256 ? 9 : 8);
   auto cost_small = [](long rows, long cols, int *cfg) {
     const long s128 = ((rows + 127) / 128) * ((cols + 127) / 128), s64 = ((rows + 63) / 64) * ((cols + 127) / 128);
     const long r128 = (s128 + 511) / 512, r64 = (s64 + 511) / 512;
     const double c128 = r128 > 1 ? 0.57 * (double)r128 : (s128 <= 256 ? 0.52 : 0.6);
     const double c64 = r64 > 1 ? 0.4 * (double)r64 : (s64 <= 256 ? 0.3 : 0.5);
-    if (cfg) *cfg = c128 <= c64 ? 22 : 26;
+    if (cfg) *cfg = c128 <= c64 ? kCfg128 : kCfg64;
     return c128 <= c64 ? c128 : c64;
   };
   const int tm = (g.M + 255) / 256, tn = (g.n_store + 255) / 256;
@@ -1580,15 +1124,15 @@ int launch_gemm(const GemmArgs &g, hipStream_t s, int force_cfg) {
       }
     if (best_dr || best_dc) best = split_best;
   }
-  int small_cfg = 26;
+  int small_cfg = kCfg64;
   const double small = cost_small(g.M, g.n_store, &small_cfg);
   if (small < best) return launch_gemm_id(g, s, small_cfg);
-  if (!best_dr && !best_dc) return launch_gemm_id(g, s, 20);
+  if (!best_dr && !best_dc) return launch_gemm_id(g, s, kCfgBig);
   const int rm = best_dr ? (tm - 1) * 256 : g.M, cm = best_dc ? (tn - 1) * 256 : g.n_store;
   GemmArgs part = g;
   part.M = rm;
   part.n_store = cm;
-  int rc = launch_gemm_id(part, s, 20);
+  int rc = launch_gemm_id(part, s, kCfgBig);
   if (rc == ET_OK && best_dc) {
     part = g;
     part.M = rm;
@@ -1647,8 +1191,6 @@ int launch_attention(const uint16_t *qkv, const int32_t *cu, int n_frames, int m
   ET_LAUNCH_CHECK();
   return ET_OK;
 }
-
-bool attention_uniform_supported(int head_dim) { return head_dim == 72 || head_dim == 64 || head_dim == 128 || head_dim == 16 || head_dim == 32 || head_dim == 80 || head_dim == 96; }
 
 int launch_attention_uniform(const uint16_t *qkv, int n_frames, int len, int n_heads, int head_dim,
                              uint16_t *out, hipStream_t s) {

@@ -20,8 +20,6 @@ static uint16_t host_f32_to_bf16(float f) {
   return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
 }
 
-constexpr int kMaxGroups = 8;
-
 struct LayerDev {
   uint16_t *wqkv, *wo, *w1, *w2;
   float *bqkv, *bo, *b1, *b2;
@@ -37,11 +35,6 @@ struct et_encoder {
   float *patch_b = nullptr, *final_g = nullptr, *final_b = nullptr;
   std::vector<et::LayerDev> layers;
   et::Profiler prof;
-  // frame groups: frames are independent inside the encoder blocks, so their rows can be split into
-  // groups whose kernel sequences run on streams of their own (group 0 on the caller's stream)
-  int n_groups = 1;
-  hipStream_t side[et::kMaxGroups - 1] = {};
-  hipEvent_t fork_ev = nullptr, join_ev[et::kMaxGroups - 1] = {};
   // weight warm-up (see warm_weights): a stream and two events of its own
   hipStream_t warm_stream = nullptr;
   hipEvent_t warm_go = nullptr, warm_done = nullptr;
@@ -157,19 +150,6 @@ static EncWs carve_encoder(const et_encoder *e, void *ws, int T) {
 
 // with_scores: also leave the attention each token receives in this block in w.att_score (frames of
 // equal length only).
-// The buffers of frames f0.. when every frame has `len` rows (the layouts are all frame-major).
-static EncWs frames_from(const et_encoder *e, const EncWs &w, int f0, int len) {
-  EncWs v = w;
-  const size_t r0 = (size_t)f0 * len;
-  const size_t hid_cols = (size_t)(e->Mhp > e->Kp_pad ? e->Mhp : e->Kp_pad);
-  v.x += r0 * e->D;
-  v.rstd += r0;
-  v.qkv += r0 * 3 * e->D;
-  v.att += r0 * e->D;
-  v.hid += r0 * hid_cols;
-  return v;
-}
-
 static int run_block(et_encoder *e, const LayerDev &lw, const EncWs &w, int rows, const int32_t *cu,
                      int n_frames, int max_len, bool ragged, hipStream_t s, bool with_scores = false) {
   const et_config &c = e->cfg;
@@ -193,53 +173,6 @@ static int run_block(et_encoder *e, const LayerDev &lw, const EncWs &w, int rows
   ET_TIMED(ET_K_GEMM_FC1, launch_gemm(g, s));
   g = GemmArgs{w.hid, e->Mhp, lw.w2, lw.b2, w.x, D, rows, w.x, D, rows, D, e->Mhp, EPI_BIAS_RES};
   ET_TIMED(ET_K_GEMM_FC2, launch_gemm(g, s));
-  return ET_OK;
-}
-
-// Side streams start after everything enqueued on `s` so far ...
-static int fork_groups(et_encoder *e, int n, hipStream_t s) {
-  ET_HIP(hipEventRecord(e->fork_ev, s));
-  for (int g = 0; g + 1 < n; ++g) ET_HIP(hipStreamWaitEvent(e->side[g], e->fork_ev, 0));
-  return ET_OK;
-}
-// ... and `s` continues after everything enqueued on them.
-static int join_groups(et_encoder *e, int n, hipStream_t s) {
-  for (int g = 0; g + 1 < n; ++g) {
-    ET_HIP(hipEventRecord(e->join_ev[g], e->side[g]));
-    ET_HIP(hipStreamWaitEvent(s, e->join_ev[g], 0));
-  }
-  return ET_OK;
-}
-// Joins on every way out of the encode, so that the caller's stream never runs ahead of a side stream.
-struct GroupScope {
-  et_encoder *e;
-  int n;
-  hipStream_t s;
-  bool forked = false;
-  int fork() {
-    if (forked || n <= 1) return ET_OK;
-    forked = true;
-    return fork_groups(e, n, s);
-  }
-  int join() {
-    if (!forked) return ET_OK;
-    forked = false;
-    return join_groups(e, n, s);
-  }
-  ~GroupScope() { (void)join(); }
-};
-
-// One encoder block over n_frames frames of `len` rows each, the frames split into n groups (group 0
-// on `s`, the others on the side streams; the scope must be forked).
-static int run_block_groups(et_encoder *e, const LayerDev &lw, const EncWs &w, int n_frames, int len, int n,
-                            hipStream_t s) {
-  for (int g = 0; g < n; ++g) {
-    const int f0 = (int)((int64_t)g * n_frames / n), f1 = (int)((int64_t)(g + 1) * n_frames / n);
-    if (f1 == f0) continue;
-    int rc = run_block(e, lw, frames_from(e, w, f0, len), (f1 - f0) * len, nullptr, f1 - f0, len, false,
-                       g == 0 ? s : e->side[g - 1]);
-    if (rc) return rc;
-  }
   return ET_OK;
 }
 
@@ -364,21 +297,8 @@ int et_encoder_create(const et_config *config, const et_weights *weights, int32_
   return ET_OK;
 }
 
-static void destroy_groups(et_encoder *e) {
-  for (int g = 0; g < kMaxGroups - 1; ++g) {
-    if (e->side[g]) (void)hipStreamDestroy(e->side[g]);
-    if (e->join_ev[g]) (void)hipEventDestroy(e->join_ev[g]);
-    e->side[g] = nullptr;
-    e->join_ev[g] = nullptr;
-  }
-  if (e->fork_ev) (void)hipEventDestroy(e->fork_ev);
-  e->fork_ev = nullptr;
-  e->n_groups = 1;
-}
-
 void et_encoder_destroy(et_encoder *e) {
   if (!e) return;
-  destroy_groups(e);
   if (e->warm_stream) (void)hipStreamDestroy(e->warm_stream);
   if (e->warm_go) (void)hipEventDestroy(e->warm_go);
   if (e->warm_done) (void)hipEventDestroy(e->warm_done);
@@ -387,20 +307,6 @@ void et_encoder_destroy(et_encoder *e) {
   for (void *p : e->allocs) (void)hipFree(p);
   e->prof.destroy();
   delete e;
-}
-
-int et_encoder_set_frame_groups(et_encoder *e, int32_t n_groups) {
-  ET_REQUIRE(e != nullptr, "encoder is NULL");
-  ET_REQUIRE(n_groups >= 1 && n_groups <= kMaxGroups, "n_groups = %d outside [1, %d]", n_groups, kMaxGroups);
-  destroy_groups(e);
-  if (n_groups == 1) return ET_OK;
-  ET_HIP(hipEventCreateWithFlags(&e->fork_ev, hipEventDisableTiming));
-  for (int g = 0; g + 1 < n_groups; ++g) {
-    ET_HIP(hipStreamCreateWithFlags(&e->side[g], hipStreamNonBlocking));   // (default priority)
-    ET_HIP(hipEventCreateWithFlags(&e->join_ev[g], hipEventDisableTiming));
-  }
-  e->n_groups = n_groups;
-  return ET_OK;
 }
 
 size_t et_workspace_bytes(const et_encoder *e, int32_t T) {
@@ -467,32 +373,10 @@ static int encode_impl(et_encoder *e, const float *frames_dev, int32_t T, int32_
     ET_TIMED(ET_K_MISC, launch_cu_uniform(T, L, w.cu_full, s));
   }
 
-  // Frame groups (per-kernel timing wants one kernel at a time on the device, so it runs ungrouped).
-  const int G = e->prof.on ? 1 : e->n_groups;
-  GroupScope groups{e, G, s};
-
   // patch embedding: x = patches * Wp^T + bp + pos_emb[l]
-  if (G > 1 && T >= 2) {
-    int rc = groups.fork();
-    if (rc) return rc;
-    const size_t frame_elems = (size_t)c.channels * c.image_h * c.image_w;
-    for (int gi = 0; gi < G; ++gi) {
-      const int f0 = (int)((int64_t)gi * T / G), f1 = (int)((int64_t)(gi + 1) * T / G);
-      if (f1 == f0) continue;
-      hipStream_t st = gi == 0 ? s : e->side[gi - 1];
-      const EncWs v = frames_from(e, w, f0, L);
-      if ((rc = launch_im2col(frames_dev + f0 * frame_elems, f1 - f0, c.channels, c.image_h, c.image_w, c.patch,
-                              e->Kp_pad, v.hid, st)))
-        return rc;
-      GemmArgs g{v.hid, e->Kp_pad, e->patch_w, e->patch_b, e->pos_emb, D, L, v.x, D, (f1 - f0) * L, D, e->Kp_pad,
-                 EPI_BIAS_RES};
-      if ((rc = launch_gemm(g, st))) return rc;
-    }
-  } else {
-    ET_TIMED(ET_K_IM2COL, launch_im2col(frames_dev, T, c.channels, c.image_h, c.image_w, c.patch, e->Kp_pad,
-                                        w.hid, s));
-    GemmArgs g{w.hid, e->Kp_pad, e->patch_w, e->patch_b, e->pos_emb, D, L, w.x, D, T * L, D, e->Kp_pad,
-               EPI_BIAS_RES};
+  ET_TIMED(ET_K_IM2COL, launch_im2col(frames_dev, T, c.channels, c.image_h, c.image_w, c.patch, e->Kp_pad, w.hid, s));
+  {
+    GemmArgs g{w.hid, e->Kp_pad, e->patch_w, e->patch_b, e->pos_emb, D, L, w.x, D, T * L, D, e->Kp_pad, EPI_BIAS_RES};
     ET_TIMED(ET_K_GEMM_PATCH, launch_gemm(g, s));
   }
 
@@ -501,10 +385,6 @@ static int encode_impl(et_encoder *e, const float *frames_dev, int32_t T, int32_
   for (int i = 0; i <= c.n_layers; ++i) {
     const bool merge_here = compress && policy && !selected && next_merge < n_merge && merge_layers[next_merge] == i;
     const bool select_here = compress && !selected && i == merge_layer;
-    if (merge_here || select_here) {       // the stage looks across frames
-      int rc = groups.join();
-      if (rc) return rc;
-    }
     if (policy && (merge_here || select_here)) {
       const MergeWs mw = carve_merge(w.merge, T, L, D);
       int32_t *info = mw.n_seg + 8;
@@ -571,23 +451,8 @@ static int encode_impl(et_encoder *e, const float *frames_dev, int32_t T, int32_
         if ((rc = warm_weights(e, i, s))) return rc;
         warmed = true;
       }
-      if (G > 1 && !ragged && n_frames >= 2) {
-        if ((rc = groups.fork())) return rc;
-        if ((rc = run_block_groups(e, e->layers[i], w, n_frames, max_len, G, s))) return rc;
-        if (with_scores) {   // the block's q and k stay in w.qkv until the next block: scores of all frames at once
-          if ((rc = groups.join())) return rc;
-          if ((rc = launch_attention_scores(w.qkv, n_frames, max_len, c.n_heads, e->hd, w.score_ws, w.att_score, s)))
-            return rc;
-        }
-      } else {
-        if ((rc = groups.join())) return rc;
-        if ((rc = run_block(e, e->layers[i], w, rows, cu, n_frames, max_len, ragged, s, with_scores))) return rc;
-      }
+      if ((rc = run_block(e, e->layers[i], w, rows, cu, n_frames, max_len, ragged, s, with_scores))) return rc;
     }
-  }
-  {
-    int rc = groups.join();
-    if (rc) return rc;
   }
   if (warmed) {      // the caller's stream ends after the warm-up stream
     ET_HIP(hipEventRecord(e->warm_done, e->warm_stream));
@@ -682,6 +547,22 @@ int et_attention_scores(const uint16_t *qkv_dev, int32_t n_frames, int32_t L, in
                                  static_cast<hipStream_t>(hip_stream));
 }
 
+int et_encoder_block_qkv(et_encoder *e, int32_t layer, const uint16_t *x_dev, int32_t rows, float *rstd_dev,
+                         uint16_t *qkv_dev, void *hip_stream) {
+  ET_REQUIRE(e != nullptr, "encoder is NULL");
+  ET_REQUIRE(layer >= 0 && layer < e->cfg.n_layers, "layer = %d outside [0, n_layers = %d)", layer, e->cfg.n_layers);
+  ET_REQUIRE(x_dev && rstd_dev && qkv_dev, "a pointer argument is NULL");
+  ET_REQUIRE(rows >= 0 && (double)rows * e->D * 3 < 2.0e9, "rows = %d out of range", rows);
+  if (rows == 0) return ET_OK;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const int D = e->D;
+  const LayerDev &lw = e->layers[layer];
+  int rc;
+  if ((rc = launch_rowstats(x_dev, e->cfg.ln_eps, rows, D, rstd_dev, s))) return rc;
+  const GemmArgs g{x_dev, D, lw.wqkv, lw.bqkv, nullptr, 0, 1, qkv_dev, 3 * D, rows, 3 * D, D, EPI_BIAS, rstd_dev};
+  return launch_gemm(g, s);
+}
+
 int et_layernorm(const uint16_t *x_dev, const float *gamma_dev, const float *beta_dev, float eps,
                  int32_t rows, int32_t D, uint16_t *y_dev, void *hip_stream) {
   ET_REQUIRE(x_dev && gamma_dev && beta_dev && y_dev, "a pointer argument is NULL");
@@ -701,10 +582,8 @@ int et_attention(const uint16_t *qkv_dev, const int32_t *cu_tokens_dev, int32_t 
                           static_cast<hipStream_t>(hip_stream));
 }
 
-size_t et_attention_uniform_scratch_bytes(int32_t, int32_t, int32_t, int32_t) { return 0; }
-
 int et_attention_uniform(const uint16_t *qkv_dev, int32_t n_frames, int32_t len, int32_t n_heads,
-                         int32_t head_dim, void *, size_t, uint16_t *out_dev, void *hip_stream) {
+                         int32_t head_dim, uint16_t *out_dev, void *hip_stream) {
   ET_REQUIRE(qkv_dev && out_dev, "a pointer argument is NULL");
   ET_REQUIRE(n_frames >= 0 && len >= 0 && n_heads >= 1, "n_frames/len/n_heads out of range");
   if (!head_dim_supported(head_dim)) {
@@ -757,59 +636,6 @@ int et_gemm_bf16(const uint16_t *a_dev, const uint16_t *w_dev, const float *bias
   if (rc == ET_OK && se != hipSuccess) rc = hip_fail(se, "hipStreamSynchronize", __FILE__, __LINE__);
   if (a) (void)hipFree(a);
   if (w) (void)hipFree(w);
-  if (b) (void)hipFree(b);
-  return rc;
-}
-
-
-int et_gemm_tune(int32_t M, int32_t N, int32_t K, int32_t epilogue, int32_t tile_config, int32_t iters,
-                 float *avg_ms, void *hip_stream) {
-  ET_REQUIRE(avg_ms != nullptr, "avg_ms is NULL");
-  ET_REQUIRE(M >= 1 && N >= 8 && K >= 8 && N % 8 == 0 && K % 8 == 0, "M = %d, N = %d, K = %d out of range", M, N, K);
-  ET_REQUIRE(epilogue >= 0 && epilogue <= 2, "epilogue = %d unknown", epilogue);
-  ET_REQUIRE(iters >= 1 && iters <= 10000, "iters = %d outside [1, 10000]", iters);
-  ET_REQUIRE(tile_config >= -1 && tile_config < gemm_config_count(), "tile_config = %d unknown", tile_config);
-  hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  const int Kp = round_up(K, 64), Np = round_up(N, 256);
-  uint16_t *a = nullptr, *w = nullptr, *c = nullptr;
-  float *b = nullptr;
-  hipEvent_t e0 = nullptr, e1 = nullptr;
-  int rc = ET_OK;
-  auto step = [&](hipError_t err, const char *what) {
-    if (rc == ET_OK && err != hipSuccess) rc = hip_fail(err, what, __FILE__, __LINE__);
-  };
-  step(hipMalloc((void **)&a, (size_t)M * Kp * 2), "hipMalloc a");
-  step(hipMalloc((void **)&w, (size_t)Np * Kp * 2), "hipMalloc w");
-  step(hipMalloc((void **)&c, (size_t)M * Np * 2), "hipMalloc c");
-  step(hipMalloc((void **)&b, (size_t)Np * 4), "hipMalloc bias");
-  if (rc == ET_OK) {
-    // pseudo-random finite values: switching activity (hence clocks under power limits) depends on the data
-    if (rc == ET_OK) rc = launch_fill_random_bf16(a, (size_t)M * Kp, 1u, s);
-    if (rc == ET_OK) rc = launch_fill_random_bf16(w, (size_t)Np * Kp, 2u, s);
-    if (rc == ET_OK) rc = launch_fill_random_bf16(c, (size_t)M * Np, 3u, s);
-    step(hipMemsetAsync(b, 0, (size_t)Np * 4, s), "fill bias");
-    step(hipEventCreate(&e0), "hipEventCreate");
-    step(hipEventCreate(&e1), "hipEventCreate");
-  }
-  if (rc == ET_OK) {
-    GemmArgs g{a, Kp, w, b, c, N, M, c, N, M, N, Kp, epilogue};
-    rc = launch_gemm(g, s, tile_config);                       // warm-up, also sets attributes
-    if (rc == ET_OK) step(hipEventRecord(e0, s), "hipEventRecord");
-    for (int i = 0; i < iters && rc == ET_OK; ++i) rc = launch_gemm(g, s, tile_config);
-    if (rc == ET_OK) step(hipEventRecord(e1, s), "hipEventRecord");
-  }
-  hipError_t se = hipStreamSynchronize(s);
-  if (rc == ET_OK && se != hipSuccess) rc = hip_fail(se, "hipStreamSynchronize", __FILE__, __LINE__);
-  if (rc == ET_OK) {
-    float ms = 0.f;
-    step(hipEventElapsedTime(&ms, e0, e1), "hipEventElapsedTime");
-    *avg_ms = ms / (float)iters;
-  }
-  if (e0) (void)hipEventDestroy(e0);
-  if (e1) (void)hipEventDestroy(e1);
-  if (a) (void)hipFree(a);
-  if (w) (void)hipFree(w);
-  if (c) (void)hipFree(c);
   if (b) (void)hipFree(b);
   return rc;
 }

@@ -44,6 +44,7 @@ MergeWs carve_merge(void *ws, int T, int L, int D) {
   MergeWs m;
   m.cos = c.take<float>((size_t)(T > 1 ? T - 1 : 1) * L);
   m.sim = c.take<float>((size_t)T);
+  m.part = c.take<float>((size_t)(T > 1 ? T - 1 : 1) * similarity_blocks(L));
   m.score = c.take<float>((size_t)T * L);
   m.n_seg = c.take<int32_t>(64);
   m.frame_first = c.take<int32_t>((size_t)T);
@@ -78,8 +79,9 @@ int enqueue_merge_stage(const uint16_t *x, int T, int L, int D, float tau, int k
                         float *sim_out, int32_t *seg_start, int32_t *kept, int32_t *cu_tokens,
                         uint16_t *packed, hipStream_t s, Profiler *prof, const EarlyCount *early) {
   float *sim = sim_out ? sim_out : w.sim;
-  ET_TIMED_P(prof, ET_K_SIMILARITY, launch_similarity(x, T, L, D, w.cos, s));
-  ET_TIMED_P(prof, ET_K_SCAN, launch_sim_mean_scan(w.cos, T, L, tau, sim, seg_start, w.n_seg, true, true, s));
+  ET_TIMED_P(prof, ET_K_SIMILARITY, launch_similarity(x, T, L, D, w.cos, w.part, s));
+  ET_TIMED_P(prof, ET_K_SCAN, launch_sim_mean_scan(w.part, similarity_blocks(L), T, L, tau, sim, seg_start, w.n_seg,
+                                                   true, true, s));
   if (early) {
     ET_HIP(hipMemcpyAsync(early->host, w.n_seg, sizeof(int32_t), hipMemcpyDeviceToHost, s));
     ET_HIP(hipEventRecord(early->ready, s));
@@ -111,8 +113,9 @@ int enqueue_policy_stage(const uint16_t *x, int T, int L, int D, const et_policy
   const PolicyArgs pa{pol.merge_mode, pol.select_mode, pol.alpha, pol.tau_seg, pol.tau_merge, pol.ratio};
   const int k_uniform = et_keep_count(L, pol.ratio);
   if (step.do_plan) {
-    ET_TIMED_P(prof, ET_K_SIMILARITY, launch_similarity(x, T, L, D, w.cos, s));
-    ET_TIMED_P(prof, ET_K_SCAN, launch_sim_mean_scan(w.cos, T, L, 0.f, sim, nullptr, nullptr, true, false, s));
+    ET_TIMED_P(prof, ET_K_SIMILARITY, launch_similarity(x, T, L, D, w.cos, w.part, s));
+    ET_TIMED_P(prof, ET_K_SCAN, launch_sim_mean_scan(w.part, similarity_blocks(L), T, L, 0.f, sim, nullptr, nullptr,
+                                                     true, false, s));
   }
   ET_TIMED_P(prof, ET_K_SCAN, launch_plan(sim, T, L, pa, k_uniform, step, seg_start, w.frame_first, w.frame_count,
                                           w.frame_dyn, w.frame_w, w.orig_first, w.orig_count, cu_tokens, info, s));
@@ -195,34 +198,92 @@ size_t et_merge_workspace_bytes(int32_t T, int32_t L, int32_t D) {
   return carve_merge(nullptr, T, L, D).bytes;
 }
 
-int et_merge_select(const uint16_t *x_dev, int32_t T, int32_t L, int32_t D, float sim_threshold,
-                    float keep_ratio, void *workspace_dev, size_t workspace_bytes, void *hip_stream,
-                    et_output *out) {
+static int check_merge_args(const uint16_t *x_dev, int32_t T, int32_t L, int32_t D, float sim_threshold,
+                            float keep_ratio, const et_output *out) {
   int rc;
   ET_REQUIRE(x_dev != nullptr, "x_dev is NULL");
   if ((rc = check_merge_shape(T, L, D))) return rc;
   if ((rc = check_outputs(out))) return rc;
   ET_REQUIRE(!isnan(sim_threshold), "sim_threshold is NaN");
   ET_REQUIRE(keep_ratio > 0.f && keep_ratio <= 1.f, "keep_ratio = %g outside (0, 1]", (double)keep_ratio);
+  return ET_OK;
+}
+
+// Optional timing of the stand-alone stage (et_merge_profile_*): HIP events around every launch and
+// around the whole sequence, on the caller's stream.  Process-wide; not thread-safe.
+static struct StageProfile {
+  Profiler p;
+  hipEvent_t t0 = nullptr, t1 = nullptr;
+  double total_ms = 0.0;
+  int64_t calls = 0;
+} g_stage;
+
+// The stage on a scratch area of at least et_merge_workspace_bytes(T, L, D) bytes; waits for the stream.
+static int merge_select_on(const uint16_t *x_dev, int32_t T, int32_t L, int32_t D, float sim_threshold,
+                           float keep_ratio, void *scratch_dev, hipStream_t s, et_output *out) {
+  int rc;
+  MergeWs w = carve_merge(scratch_dev, T, L, D);
+  const int k = et_keep_count(L, keep_ratio);
+  const bool timed = g_stage.p.on;
+  if (timed) {
+    g_stage.p.kinds.clear();
+    ET_HIP(hipEventRecord(g_stage.t0, s));
+  }
+  if ((rc = enqueue_merge_stage(x_dev, T, L, D, sim_threshold, k, w, out->frame_sim_dev,
+                                out->seg_start_dev, out->kept_idx_dev, out->cu_tokens_dev,
+                                out->tokens_dev, s, timed ? &g_stage.p : nullptr)))
+    return rc;
+  if (timed) ET_HIP(hipEventRecord(g_stage.t1, s));
+  int32_t n_seg = 0;
+  ET_HIP(hipMemcpyAsync(&n_seg, w.n_seg, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  ET_HIP(hipStreamSynchronize(s));
+  if (timed) {
+    float ms = 0.f;
+    ET_HIP(hipEventElapsedTime(&ms, g_stage.t0, g_stage.t1));
+    g_stage.total_ms += ms;
+    g_stage.calls += 1;
+    if ((rc = g_stage.p.collect())) return rc;
+  }
+  out->n_frames_out = n_seg;
+  out->n_tokens = n_seg * k;
+  return ET_OK;
+}
+
+int et_merge_profile_enable(int32_t on) {
+  if (on && !g_stage.t0) {
+    ET_HIP(hipEventCreate(&g_stage.t0));
+    ET_HIP(hipEventCreate(&g_stage.t1));
+  }
+  g_stage.p.on = on != 0;
+  return ET_OK;
+}
+
+int et_merge_profile_read(double *ms, int64_t *launches, double *total_ms, int64_t *calls, int32_t reset) {
+  ET_REQUIRE(ms && launches && total_ms && calls, "a pointer argument is NULL");
+  for (int i = 0; i < ET_K_COUNT; ++i) {
+    ms[i] = g_stage.p.ms[i];
+    launches[i] = g_stage.p.launches[i];
+    if (reset) { g_stage.p.ms[i] = 0; g_stage.p.launches[i] = 0; }
+  }
+  *total_ms = g_stage.total_ms;
+  *calls = g_stage.calls;
+  if (reset) { g_stage.total_ms = 0.0; g_stage.calls = 0; }
+  return ET_OK;
+}
+
+int et_merge_select(const uint16_t *x_dev, int32_t T, int32_t L, int32_t D, float sim_threshold,
+                    float keep_ratio, void *workspace_dev, size_t workspace_bytes, void *hip_stream,
+                    et_output *out) {
+  int rc;
+  if ((rc = check_merge_args(x_dev, T, L, D, sim_threshold, keep_ratio, out))) return rc;
   ET_REQUIRE(workspace_dev != nullptr, "workspace_dev is NULL");
   size_t need = et_merge_workspace_bytes(T, L, D);
   if (workspace_bytes < need) {
     set_error("workspace of %zu bytes is smaller than the %zu needed", workspace_bytes, need);
     return ET_ERR_WORKSPACE;
   }
-  hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  MergeWs w = carve_merge(workspace_dev, T, L, D);
-  const int k = et_keep_count(L, keep_ratio);
-  if ((rc = enqueue_merge_stage(x_dev, T, L, D, sim_threshold, k, w, out->frame_sim_dev,
-                                out->seg_start_dev, out->kept_idx_dev, out->cu_tokens_dev,
-                                out->tokens_dev, s, nullptr)))
-    return rc;
-  int32_t n_seg = 0;
-  ET_HIP(hipMemcpyAsync(&n_seg, w.n_seg, sizeof(int32_t), hipMemcpyDeviceToHost, s));
-  ET_HIP(hipStreamSynchronize(s));
-  out->n_frames_out = n_seg;
-  out->n_tokens = n_seg * k;
-  return ET_OK;
+  return merge_select_on(x_dev, T, L, D, sim_threshold, keep_ratio, workspace_dev,
+                         static_cast<hipStream_t>(hip_stream), out);
 }
 
 int et_merge_select_policy(const uint16_t *x_dev, int32_t T, int32_t L, int32_t D, const et_policy *policy,
@@ -268,8 +329,8 @@ int et_frame_similarity(const uint16_t *x_dev, int32_t T, int32_t L, int32_t D, 
   if ((rc = check_merge_shape(T, L, D))) return rc;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   if (T < 2) return ET_OK;
-  if ((rc = launch_similarity(x_dev, T, L, D, cos_dev, s))) return rc;
-  return launch_sim_mean_scan(cos_dev, T, L, 0.f, sim_dev, nullptr, nullptr, true, false, s);
+  if ((rc = launch_similarity(x_dev, T, L, D, cos_dev, nullptr, s))) return rc;
+  return launch_sim_mean_scan(cos_dev, L, T, L, 0.f, sim_dev, nullptr, nullptr, true, false, s);
 }
 
 int et_segment_scan(const float *sim_dev, int32_t T, float sim_threshold, int32_t *seg_start_dev,
@@ -278,7 +339,7 @@ int et_segment_scan(const float *sim_dev, int32_t T, float sim_threshold, int32_
   ET_REQUIRE(T >= 1, "T = %d: a clip needs at least one frame", T);
   ET_REQUIRE(T == 1 || sim_dev != nullptr, "sim_dev is NULL");
   ET_REQUIRE(!isnan(sim_threshold), "sim_threshold is NaN");
-  return launch_sim_mean_scan(nullptr, T, 1, sim_threshold, const_cast<float *>(sim_dev), seg_start_dev,
+  return launch_sim_mean_scan(nullptr, 0, T, 1, sim_threshold, const_cast<float *>(sim_dev), seg_start_dev,
                               n_seg_dev, false, true, static_cast<hipStream_t>(hip_stream));
 }
 

@@ -129,6 +129,7 @@ struct Profiler {
 // Scratch of the compression stage, carved from a caller workspace.
 struct MergeWs {
   float *cos, *sim, *score;
+  float *part;                    // [T-1, similarity_blocks(L)]: per-workgroup sums of cosines
   uint16_t *merged;
   int32_t *n_seg;                 // 64 ints: [0] segment count of the simple path; [8..12] policy info
   int32_t *frame_first, *frame_count, *frame_dyn;   // [T] each: output-frame plan (policy path)
@@ -171,8 +172,11 @@ int enqueue_merge_stage(const uint16_t *x, int T, int L, int D, float tau, int k
                         uint16_t *packed, hipStream_t s, Profiler *prof, const EarlyCount *early = nullptr);
 
 // ---- launchers implemented in merge_kernels.hip ----
-int launch_similarity(const uint16_t *x, int T, int L, int D, float *cos_out, hipStream_t s);
-int launch_sim_mean_scan(const float *cos_in, int T, int L, float tau, float *sim_out,
+// part [T-1, similarity_blocks(L)]: per pair and workgroup, the sum of the workgroup's cosines
+int similarity_blocks(int L);
+int launch_similarity(const uint16_t *x, int T, int L, int D, float *cos_out, float *part, hipStream_t s);
+// sim[t] = (sum of src[t, 0..n_src)) / L (do_mean), then the boundary scan (do_scan)
+int launch_sim_mean_scan(const float *src, int n_src, int T, int L, float tau, float *sim_out,
                          int32_t *seg_start, int32_t *n_seg, bool do_mean, bool do_scan,
                          hipStream_t s);
 int launch_segment_mean(const uint16_t *x, int T, int L, int D, const int32_t *seg_start,
@@ -184,8 +188,6 @@ int launch_compact(const uint16_t *merged, const int32_t *kept, int n_rows_max,
 int launch_identity_maps(int T, int L, int32_t *kept, int32_t *cu_tokens, int32_t *seg_start,
                          hipStream_t s);
 int launch_cu_uniform(int n, int step, int32_t *cu, hipStream_t s);
-// Fills with bf16 values in (-1, 1) from a counter hash (benchmark operands only).
-int launch_fill_random_bf16(uint16_t *p, size_t n, uint32_t seed, hipStream_t s);
 
 // ---- launchers implemented in policy_kernels.hip ----
 int launch_plan(const float *sim, int T, int L, const PolicyArgs &p, int k_uniform, const PlanStep &st,

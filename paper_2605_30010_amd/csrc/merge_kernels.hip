@@ -6,79 +6,98 @@
 // token row at a time and reads it as 16-byte vectors (8 bf16 per lane, lane-contiguous,
 // so every load instruction covers a contiguous 1 KiB).  All reductions run in a fixed
 // order (no floating-point atomics), so results are bit-reproducible run to run.
-#include "et_common.h"
+#include "select_common.h"
 
 namespace et {
 
 namespace {
 
 constexpr int kRowsPerBlock = 4;   // wavefronts per workgroup in the row-streaming kernels
-constexpr int kSimChunk = 8;       // frame pairs handled by one wavefront before it re-reads a halo row
 
 // ---------------------------------------------------------------------------------------
 // Similarity: cos[t-1, l] = <x[t,l], x[t-1,l]> / max(|x[t,l]| |x[t-1,l]|, 1e-8), t = 1..T-1.
-// One wavefront = one position l and kSimChunk consecutive pairs; the previous row stays in
-// registers, so x is read (kSimChunk+1)/kSimChunk times.
+// One wavefront = one position l and `chunk` consecutive pairs; the previous row stays in
+// registers, so x is read (chunk + 1) / chunk times; two further rows are in flight while one
+// is reduced.  The workgroup also leaves, per pair, the sum of its kRowsPerBlock cosines in
+// part[t-1, blockIdx.x] (added in wavefront order), so that the mean over positions needs
+// L / kRowsPerBlock values per pair instead of L (part may be NULL: not written).
 // ---------------------------------------------------------------------------------------
+constexpr int kSimMaxChunk = 16;
+
 template <int NV>
 __global__ __launch_bounds__(kRowsPerBlock * kWave) void similarity_kernel(
-    const uint16_t *__restrict__ x, int T, int L, int D, float *__restrict__ cos_out) {
-  const int lane = threadIdx.x & 63;
-  const int l = blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
-  if (l >= L) return;
-  const int t_first = blockIdx.y * kSimChunk + 1;               // first pair's later frame
-  const int t_last = min(t_first + kSimChunk - 1, T - 1);
-  if (t_first > t_last) return;
-  const size_t frame_stride = (size_t)L * D;
-  const uint16_t *p = x + (size_t)(t_first - 1) * frame_stride + (size_t)l * D;
+    const uint16_t *__restrict__ x, int T, int L, int D, int chunk, float *__restrict__ cos_out,
+    float *__restrict__ part) {
+  __shared__ float csum[kRowsPerBlock][kSimMaxChunk];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int l = blockIdx.x * kRowsPerBlock + wave;
+  const int t_first = blockIdx.y * chunk + 1;                   // first pair's later frame
+  const int t_last = min(t_first + chunk - 1, T - 1);           // (t_first <= T - 1 by the grid's size)
+  if (lane < kSimMaxChunk) csum[wave][lane] = 0.f;              // positions past L add nothing
+  if (l < L) {
+    const size_t frame_stride = (size_t)L * D;
+    const uint16_t *p = x + (size_t)(t_first - 1) * frame_stride + (size_t)l * D;
+    uint4 raw[NV], raw1[NV], raw2[NV];
+    Row<NV> prev, cur;
+    load_row<NV>(p, D, lane, raw);
+    load_row<NV>(p + frame_stride, D, lane, raw1);
+    if (t_first < t_last) load_row<NV>(p + 2 * frame_stride, D, lane, raw2);
+    unpack_row<NV>(raw, prev);
+    float nn_prev = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV * 8; ++i) nn_prev = fmaf(prev.v[i], prev.v[i], nn_prev);
+    nn_prev = wave_sum(nn_prev);
 
-  uint4 raw[NV], raw_next[NV];
-  Row<NV> prev, cur;
-  load_row<NV>(p, D, lane, raw);
-  load_row<NV>(p + frame_stride, D, lane, raw_next);
-  unpack_row<NV>(raw, prev);
-  float nn_prev = 0.f;
+    for (int t = t_first; t <= t_last; ++t) {
 #pragma unroll
-  for (int i = 0; i < NV * 8; ++i) nn_prev = fmaf(prev.v[i], prev.v[i], nn_prev);
-  nn_prev = wave_sum(nn_prev);
-
-  for (int t = t_first; t <= t_last; ++t) {
+      for (int j = 0; j < NV; ++j) { raw[j] = raw1[j]; raw1[j] = raw2[j]; }
+      if (t + 2 <= t_last) load_row<NV>(p + (size_t)(t - t_first + 3) * frame_stride, D, lane, raw2);
+      unpack_row<NV>(raw, cur);
+      float dot = 0.f, nn = 0.f;
 #pragma unroll
-    for (int j = 0; j < NV; ++j) raw[j] = raw_next[j];
-    if (t < t_last) load_row<NV>(p + (size_t)(t - t_first + 2) * frame_stride, D, lane, raw_next);
-    unpack_row<NV>(raw, cur);
-    float dot = 0.f, nn = 0.f;
+      for (int i = 0; i < NV * 8; ++i) {
+        dot = fmaf(cur.v[i], prev.v[i], dot);
+        nn = fmaf(cur.v[i], cur.v[i], nn);
+      }
+      dot = wave_sum(dot);
+      nn = wave_sum(nn);
+      if (lane == 0) {
+        const float den = fmaxf(sqrtf(nn) * sqrtf(nn_prev), 1e-8f);
+        const float c = dot / den;
+        cos_out[(size_t)(t - 1) * L + l] = c;
+        csum[wave][t - t_first] = c;
+      }
+      nn_prev = nn;
 #pragma unroll
-    for (int i = 0; i < NV * 8; ++i) {
-      dot = fmaf(cur.v[i], prev.v[i], dot);
-      nn = fmaf(cur.v[i], cur.v[i], nn);
+      for (int i = 0; i < NV * 8; ++i) prev.v[i] = cur.v[i];
     }
-    dot = wave_sum(dot);
-    nn = wave_sum(nn);
-    if (lane == 0) {
-      float den = fmaxf(sqrtf(nn) * sqrtf(nn_prev), 1e-8f);
-      cos_out[(size_t)(t - 1) * L + l] = dot / den;
-    }
-    nn_prev = nn;
+  }
+  __syncthreads();
+  const int i = threadIdx.x;
+  if (part && i <= t_last - t_first) {
+    float a = csum[0][i];
 #pragma unroll
-    for (int i = 0; i < NV * 8; ++i) prev.v[i] = cur.v[i];
+    for (int w = 1; w < kRowsPerBlock; ++w) a += csum[w][i];
+    part[(size_t)(t_first - 1 + i) * gridDim.x + blockIdx.x] = a;
   }
 }
 
 // ---------------------------------------------------------------------------------------
-// s_t = mean_l cos[t-1, l] (fixed-order: lane-strided partial sums, then a butterfly), then
-// the boundary scan of Eq. 1 with alpha = 1: frame t opens a segment iff !(s_t >= tau).
-// One workgroup; wavefront 0 does the scan with ballots.
+// s_t = (sum of the n_src values of row t of `src`) / L: src is either the per-workgroup
+// partial sums the similarity kernel left (n_src = its grid width) or the cosines themselves
+// (n_src = L).  Fixed order: lane-strided partial sums, then a butterfly; one wavefront per
+// pair.  Then the boundary scan of Eq. 1 with alpha = 1: frame t opens a segment iff
+// !(s_t >= tau).  One workgroup; wavefront 0 does the scan with ballots.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void sim_mean_scan_kernel(
-    const float *__restrict__ cos_in, int T, int L, float tau, float *__restrict__ sim,
+    const float *__restrict__ src, int n_src, int T, int L, float tau, float *__restrict__ sim,
     int32_t *__restrict__ seg_start, int32_t *__restrict__ n_seg, int do_mean, int do_scan) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
   if (do_mean) {
     for (int t = wave; t < T - 1; t += n_waves) {
-      const float *row = cos_in + (size_t)t * L;
+      const float *row = src + (size_t)t * n_src;
       float acc = 0.f;
-      for (int l = lane; l < L; l += kWave) acc += row[l];
+      for (int i = lane; i < n_src; i += kWave) acc += row[i];
       acc = wave_sum(acc);
       if (lane == 0) sim[t] = acc / (float)L;
     }
@@ -107,8 +126,8 @@ __global__ __launch_bounds__(1024) void sim_mean_scan_kernel(
 // ---------------------------------------------------------------------------------------
 // Segment mean + score: merged[n, l, :] = (sum over the segment's frames, ascending t, fp32)
 // / len, rounded once to bf16; score[n, l] = sum_d mean^2 from the unrounded fp32 mean.
-// One wavefront per (n, l); blockIdx.y runs over the maximum number of segments (T) and
-// exits when n >= *n_seg, so no host round trip is needed between scan and merge.
+// One wavefront per (n, l), four rows in flight; blockIdx.y runs over the maximum number of
+// segments (T) and exits when n >= *n_seg, so no host round trip is needed between scan and merge.
 // ---------------------------------------------------------------------------------------
 template <int NV>
 __global__ __launch_bounds__(kRowsPerBlock * kWave) void segment_mean_kernel(
@@ -126,24 +145,30 @@ __global__ __launch_bounds__(kRowsPerBlock * kWave) void segment_mean_kernel(
   Row<NV> acc, r;
 #pragma unroll
   for (int i = 0; i < NV * 8; ++i) acc.v[i] = 0.f;
-  uint4 raw0[NV], raw1[NV];
+  uint4 raw[4][NV];
   int t = a;
-  for (; t + 1 < b; t += 2) {           // two rows in flight per iteration, added in order
-    load_row<NV>(p, D, lane, raw0);
-    load_row<NV>(p + frame_stride, D, lane, raw1);
-    p += 2 * frame_stride;
-    unpack_row<NV>(raw0, r);
+  for (; t + 3 < b; t += 4) {           // four rows in flight per iteration, added in ascending t
 #pragma unroll
-    for (int i = 0; i < NV * 8; ++i) acc.v[i] += r.v[i];
-    unpack_row<NV>(raw1, r);
+    for (int u = 0; u < 4; ++u) load_row<NV>(p + (size_t)u * frame_stride, D, lane, raw[u]);
+    p += 4 * frame_stride;
 #pragma unroll
-    for (int i = 0; i < NV * 8; ++i) acc.v[i] += r.v[i];
+    for (int u = 0; u < 4; ++u) {
+      unpack_row<NV>(raw[u], r);
+#pragma unroll
+      for (int i = 0; i < NV * 8; ++i) acc.v[i] += r.v[i];
+    }
   }
-  if (t < b) {
-    load_row<NV>(p, D, lane, raw0);
-    unpack_row<NV>(raw0, r);
+  {                                     // the last b - t < 4 rows, loaded together
 #pragma unroll
-    for (int i = 0; i < NV * 8; ++i) acc.v[i] += r.v[i];
+    for (int u = 0; u < 3; ++u)
+      if (t + u < b) load_row<NV>(p + (size_t)u * frame_stride, D, lane, raw[u]);
+#pragma unroll
+    for (int u = 0; u < 3; ++u)
+      if (t + u < b) {
+        unpack_row<NV>(raw[u], r);
+#pragma unroll
+        for (int i = 0; i < NV * 8; ++i) acc.v[i] += r.v[i];
+      }
   }
   const float len = (float)(b - a);
   float z = 0.f;
@@ -169,111 +194,24 @@ __global__ __launch_bounds__(kRowsPerBlock * kWave) void segment_mean_kernel(
 }
 
 // ---------------------------------------------------------------------------------------
-// Per-frame top-k.  Scores are non-negative floats (or NaN), so key = bits + 1 (NaN -> 0)
-// orders them as unsigned integers.  Four 8-bit radix passes find the k-th largest key v*
-// and how many keys equal to v* still have to be taken; an ordered ballot compaction then
-// emits, in ascending position, every key > v* plus the first `need_eq` keys == v*
-// (lowest position wins ties).  One 256-thread workgroup per frame, keys staged in LDS.
+// Per-frame top-k: one 256-thread workgroup per frame, keys staged in LDS (select_common.h).
 // ---------------------------------------------------------------------------------------
-constexpr int kSelThreads = 256;
-
-__device__ __forceinline__ uint32_t score_key(float z) {
-  uint32_t u = __float_as_uint(z);
-  return (z != z) ? 0u : u + 1u;       // non-negative finite/inf floats: bits < 0x7F800001
-}
-
-// Exclusive prefix over the workgroup of a per-thread flag, in thread order; also the total.
-__device__ __forceinline__ int block_prefix_flag(bool flag, int lane, int wave, int *wave_tot,
-                                                 int &total) {
-  unsigned long long m = __ballot(flag);
-  int before = __popcll(m & ((1ull << lane) - 1ull));
-  __syncthreads();                      // wave_tot may still be read from the previous use
-  if (lane == 0) wave_tot[wave] = __popcll(m);
-  __syncthreads();
-  int base = 0;
-  total = 0;
-#pragma unroll
-  for (int w = 0; w < kSelThreads / kWave; ++w) {
-    int c = wave_tot[w];
-    if (w < wave) base += c;
-    total += c;
-  }
-  return base + before;
-}
-
 __global__ __launch_bounds__(kSelThreads) void topk_kernel(
     const float *__restrict__ score, const int32_t *__restrict__ n_rows_dev, int L, int k,
     int32_t *__restrict__ kept, int32_t *__restrict__ cu_tokens) {
-  extern __shared__ uint32_t smem[];
-  uint32_t *keys = smem;                 // [L]
-  __shared__ int hist[256];
-  __shared__ int scan[256];
-  __shared__ int wave_tot[kSelThreads / kWave];
-  __shared__ uint32_t sel_bin;
-  __shared__ int sel_remaining;
-
+  extern __shared__ uint32_t keys[];     // [L]
+  __shared__ SelectShared sh;
   const int n = blockIdx.x;
   const int n_rows = n_rows_dev ? *n_rows_dev : (int)gridDim.x;
   if (n >= n_rows) return;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x;
   if (cu_tokens && tid == 0) {
     cu_tokens[n] = n * k;
     if (n == 0) cu_tokens[n_rows] = n_rows * k;
   }
   const float *row = score + (size_t)n * L;
   for (int i = tid; i < L; i += kSelThreads) keys[i] = score_key(row[i]);
-
-  uint32_t prefix = 0, mask = 0;
-  int remaining = k;                     // how many of the keys matching `prefix` are wanted
-  for (int pass = 0; pass < 4; ++pass) {
-    const int shift = 24 - 8 * pass;
-    hist[tid] = 0;
-    __syncthreads();                     // also orders the key staging before the first pass
-    for (int i = tid; i < L; i += kSelThreads) {
-      uint32_t kk = keys[i];
-      if ((kk & mask) == prefix) atomicAdd(&hist[(kk >> shift) & 255u], 1);
-    }
-    __syncthreads();
-    // suffix[b] = number of candidates in bins > b  (inclusive scan of the reversed histogram)
-    const int mine = hist[255 - tid];
-    scan[tid] = mine;
-    __syncthreads();
-    for (int off = 1; off < 256; off <<= 1) {
-      int add = (tid >= off) ? scan[tid - off] : 0;
-      __syncthreads();
-      scan[tid] += add;
-      __syncthreads();
-    }
-    const int incl = scan[tid];          // candidates in bins >= (255 - tid)
-    const int above = incl - mine;       // candidates in bins >  (255 - tid)
-    if (above < remaining && remaining <= incl) {
-      sel_bin = 255u - (uint32_t)tid;
-      sel_remaining = remaining - above;
-    }
-    __syncthreads();
-    prefix |= sel_bin << shift;
-    mask |= 0xFFu << shift;
-    remaining = sel_remaining;
-    __syncthreads();
-  }
-  const uint32_t vstar = prefix;
-  const int need_eq = remaining;
-
-  int eq_base = 0, out_base = 0;
-  int32_t *dst = kept + (size_t)n * k;
-  for (int i0 = 0; i0 < L; i0 += kSelThreads) {
-    const int i = i0 + tid;
-    const uint32_t kk = (i < L) ? keys[i] : 0u;
-    const bool gt = (i < L) && kk > vstar;
-    const bool eq = (i < L) && kk == vstar;
-    int tot_eq, tot_keep;
-    const int eq_rank = eq_base + block_prefix_flag(eq, lane, wave, wave_tot, tot_eq);
-    const bool keep = gt || (eq && eq_rank < need_eq);
-    const int pos = out_base + block_prefix_flag(keep, lane, wave, wave_tot, tot_keep);
-    if (keep) dst[pos] = i;
-    eq_base += tot_eq;
-    out_base += tot_keep;
-  }
+  radix_select_emit(keys, L, k, kept + (size_t)n * k, sh);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -310,31 +248,26 @@ __global__ void cu_uniform_kernel(int n, int step, int32_t *cu) {
   if (i <= n) cu[i] = i * step;
 }
 
-__global__ void fill_random_bf16_kernel(uint16_t *p, size_t n, uint32_t seed) {
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
-    uint32_t h = (uint32_t)i * 2654435761u ^ (seed * 0x9E3779B9u) ^ (uint32_t)(i >> 32);
-    h ^= h >> 15; h *= 2246822519u; h ^= h >> 13; h *= 3266489917u; h ^= h >> 16;
-    // sign 1 bit, exponent 0x70..0x7E (2^-15 .. 2^-1), mantissa 7 bits
-    const uint32_t e = 0x70u + (h >> 8) % 15u;
-    p[i] = (uint16_t)(((h & 1u) << 15) | (e << 7) | ((h >> 1) & 0x7Fu));
-  }
-}
-
 }  // namespace
 
-int launch_similarity(const uint16_t *x, int T, int L, int D, float *cos_out, hipStream_t s) {
+int similarity_blocks(int L) { return (L + kRowsPerBlock - 1) / kRowsPerBlock; }
+
+int launch_similarity(const uint16_t *x, int T, int L, int D, float *cos_out, float *part, hipStream_t s) {
   if (T < 2) return ET_OK;
-  dim3 grid((L + kRowsPerBlock - 1) / kRowsPerBlock, (T - 1 + kSimChunk - 1) / kSimChunk);
+  // pairs per wavefront: as many as keep about 4096 wavefronts in the grid (x is re-read 1 / chunk times)
+  int chunk = (int)(((long long)(T - 1) * L + 4095) / 4096);
+  chunk = chunk < 4 ? 4 : (chunk > kSimMaxChunk ? kSimMaxChunk : chunk);
+  dim3 grid(similarity_blocks(L), (T - 1 + chunk - 1) / chunk);
   dim3 block(kRowsPerBlock * kWave);
-  ET_DISPATCH_NV(D, hipLaunchKernelGGL(similarity_kernel<NV>, grid, block, 0, s, x, T, L, D, cos_out));
+  ET_DISPATCH_NV(D, hipLaunchKernelGGL(similarity_kernel<NV>, grid, block, 0, s, x, T, L, D, chunk, cos_out, part));
   ET_LAUNCH_CHECK();
   return ET_OK;
 }
 
-int launch_sim_mean_scan(const float *cos_in, int T, int L, float tau, float *sim_out,
+int launch_sim_mean_scan(const float *src, int n_src, int T, int L, float tau, float *sim_out,
                          int32_t *seg_start, int32_t *n_seg, bool do_mean, bool do_scan,
                          hipStream_t s) {
-  hipLaunchKernelGGL(sim_mean_scan_kernel, dim3(1), dim3(1024), 0, s, cos_in, T, L, tau, sim_out,
+  hipLaunchKernelGGL(sim_mean_scan_kernel, dim3(1), dim3(1024), 0, s, src, n_src, T, L, tau, sim_out,
                      seg_start, n_seg, do_mean ? 1 : 0, do_scan ? 1 : 0);
   ET_LAUNCH_CHECK();
   return ET_OK;
@@ -376,13 +309,6 @@ int launch_identity_maps(int T, int L, int32_t *kept, int32_t *cu_tokens, int32_
   int n = T * L > T + 1 ? T * L : T + 1;
   hipLaunchKernelGGL(identity_maps_kernel, dim3((n + 255) / 256), dim3(256), 0, s, T, L, kept,
                      cu_tokens, seg_start);
-  ET_LAUNCH_CHECK();
-  return ET_OK;
-}
-
-int launch_fill_random_bf16(uint16_t *p, size_t n, uint32_t seed, hipStream_t s) {
-  if (n == 0) return ET_OK;
-  hipLaunchKernelGGL(fill_random_bf16_kernel, dim3(4096), dim3(256), 0, s, p, n, seed);
   ET_LAUNCH_CHECK();
   return ET_OK;
 }

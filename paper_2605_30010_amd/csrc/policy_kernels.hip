@@ -6,14 +6,13 @@
 // Readings of points the paper leaves open are stated at plan_kernel.  The similarity kernel of
 // the simple path is reused; this file adds the sequential plan builder (one lane; the work is
 // O(T)), a weighted-range merge, the per-frame selection with two modes and a ragged gather.
-#include "et_common.h"
+#include "select_common.h"
 
 namespace et {
 
 namespace {
 
 constexpr int kRowsPerBlock = 4;
-constexpr int kSelThreads = 256;
 
 // ---------------------------------------------------------------------------------------
 // Plan builder.  info[0] = N output frames, info[1] = segments, info[2] = total kept tokens,
@@ -202,47 +201,20 @@ __global__ __launch_bounds__(kRowsPerBlock * kWave) void plan_merge_kernel(
   if (lane == 0) score[(size_t)n * L + l] = z;
 }
 
-__device__ __forceinline__ uint32_t score_key(float z) {
-  uint32_t u = __float_as_uint(z);
-  return (z != z) ? 0u : u + 1u;
-}
-
-__device__ __forceinline__ int block_prefix_flag(bool flag, int lane, int wave, int *wave_tot, int &total) {
-  unsigned long long m = __ballot(flag);
-  int before = __popcll(m & ((1ull << lane) - 1ull));
-  __syncthreads();
-  if (lane == 0) wave_tot[wave] = __popcll(m);
-  __syncthreads();
-  int base = 0;
-  total = 0;
-#pragma unroll
-  for (int w = 0; w < kSelThreads / kWave; ++w) {
-    int c = wave_tot[w];
-    if (w < wave) base += c;
-    total += c;
-  }
-  return base + before;
-}
-
 // ---------------------------------------------------------------------------------------
 // Per-frame selection with ragged output.  Dynamic frames (and every frame in uniform mode): the
-// radix select of the simple path with k = cu[n+1] - cu[n].  Static frames: one thread per local
+// radix select of the simple path (select_common.h) with k = cu[n+1] - cu[n].  Static frames: one thread per local
 // window of w consecutive positions, arg-max of the key, lowest position on ties.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kSelThreads) void select_policy_kernel(
     const float *__restrict__ score, const int32_t *__restrict__ info, const int32_t *__restrict__ frame_dyn,
     const int32_t *__restrict__ cu_tokens, int L, int all_topk, int32_t *__restrict__ kept) {
-  extern __shared__ uint32_t smem[];
-  uint32_t *keys = smem;
-  __shared__ int hist[256];
-  __shared__ int scan[256];
-  __shared__ int wave_tot[kSelThreads / kWave];
-  __shared__ uint32_t sel_bin;
-  __shared__ int sel_remaining;
+  extern __shared__ uint32_t keys[];     // [L]
+  __shared__ SelectShared sh;
 
   const int n = blockIdx.x;
   if (n >= info[0]) return;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x;
   const int out0 = cu_tokens[n], k = cu_tokens[n + 1] - out0;
   const float *row = score + (size_t)n * L;
   for (int i = tid; i < L; i += kSelThreads) keys[i] = score_key(row[i]);
@@ -264,54 +236,7 @@ __global__ __launch_bounds__(kSelThreads) void select_policy_kernel(
     return;
   }
 
-  uint32_t prefix = 0, mask = 0;
-  int remaining = k;
-  for (int pass = 0; pass < 4; ++pass) {
-    const int shift = 24 - 8 * pass;
-    hist[tid] = 0;
-    __syncthreads();
-    for (int i = tid; i < L; i += kSelThreads) {
-      uint32_t kk = keys[i];
-      if ((kk & mask) == prefix) atomicAdd(&hist[(kk >> shift) & 255u], 1);
-    }
-    __syncthreads();
-    const int mine = hist[255 - tid];
-    scan[tid] = mine;
-    __syncthreads();
-    for (int off = 1; off < 256; off <<= 1) {
-      int add = (tid >= off) ? scan[tid - off] : 0;
-      __syncthreads();
-      scan[tid] += add;
-      __syncthreads();
-    }
-    const int incl = scan[tid];
-    const int above = incl - mine;
-    if (above < remaining && remaining <= incl) {
-      sel_bin = 255u - (uint32_t)tid;
-      sel_remaining = remaining - above;
-    }
-    __syncthreads();
-    prefix |= sel_bin << shift;
-    mask |= 0xFFu << shift;
-    remaining = sel_remaining;
-    __syncthreads();
-  }
-  const uint32_t vstar = prefix;
-  const int need_eq = remaining;
-  int eq_base = 0, out_base = 0;
-  for (int i0 = 0; i0 < L; i0 += kSelThreads) {
-    const int i = i0 + tid;
-    const uint32_t kk = (i < L) ? keys[i] : 0u;
-    const bool gt = (i < L) && kk > vstar;
-    const bool eq = (i < L) && kk == vstar;
-    int tot_eq, tot_keep;
-    const int eq_rank = eq_base + block_prefix_flag(eq, lane, wave, wave_tot, tot_eq);
-    const bool keep = gt || (eq && eq_rank < need_eq);
-    const int pos = out_base + block_prefix_flag(keep, lane, wave, wave_tot, tot_keep);
-    if (keep) dst[pos] = i;
-    eq_base += tot_eq;
-    out_base += tot_keep;
-  }
+  radix_select_emit(keys, L, k, dst, sh);
 }
 
 // Gather with per-frame counts: out[cu[n] + j, :] = merged[n, kept[cu[n] + j], :].

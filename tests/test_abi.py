@@ -104,7 +104,8 @@ def test_encoder_entry_points_reject_bad_arguments():
     assert lib.et_workspace_bytes(None, 4) == 0
     lib.et_encoder_destroy(None)
     assert lib.et_profile_enable(None, 1) == -1
-    assert lib.et_encoder_set_frame_groups(None, 2) == -1
+    fake = C.c_void_p(4096)
+    assert lib.et_encoder_block_qkv(None, 0, fake, 4, fake, fake, None) == -1
 
 
 def test_single_step_entry_points_reject_bad_arguments():
