@@ -126,6 +126,21 @@ int et_merge_select(const uint16_t *x_dev, int32_t T, int32_t L, int32_t D, floa
                     void *hip_stream, et_output *out);
 size_t et_merge_workspace_bytes(int32_t T, int32_t L, int32_t D);
 
+/* et_merge_select for callers that cannot allocate or hand over a workspace (a stage under HIP graph
+ * capture set-up, a tight serving loop, a harness that forbids hipMalloc): same arguments minus the
+ * workspace, same kernels, same results bit for bit.  The scratch the kernels need (cosines, their
+ * partial sums, scores, the merged frames, counters) lives in a device array that is part of the
+ * library's code object, ET_STATIC_SCRATCH_BYTES large, one copy per GPU for the life of the process;
+ * its address is looked up once per device, on the first call there.  The call allocates nothing and
+ * frees nothing.  Shapes with et_merge_workspace_bytes(T, L, D) above ET_STATIC_SCRATCH_BYTES (e.g. more
+ * than 39 frames of 729 x 1152) are rejected with ET_ERR_WORKSPACE before any device work.  Every call
+ * on a GPU uses that GPU's one array: calls that overlap on one GPU (from several threads or streams)
+ * race; nothing in it has to start at zero, so a call is not affected by what the previous one left.
+ * Synchronises the stream once before returning, like et_merge_select. */
+#define ET_STATIC_SCRATCH_BYTES (64u << 20)
+int et_merge_select_static(const uint16_t *x_dev, int32_t T, int32_t L, int32_t D, float sim_threshold,
+                           float keep_ratio, void *hip_stream, et_output *out);
+
 /* k = clamp(floor(keep_ratio * L + 1e-4), 1, L); 0 on bad arguments.  (The paper floors
  * window sizes in Eq. 6 but does not state the rounding for top-K; this rule is this
  * library's reading.) */
@@ -201,7 +216,7 @@ int et_profile_enable(et_encoder *enc, int32_t on);
  * compression stage), phase 1 = launches on the kept tokens; clears them if `reset` != 0. */
 int et_profile_read(et_encoder *enc, double *ms, int64_t *launches, int32_t reset);
 const char *et_kernel_name(int32_t kind);
-/* The same for the stand-alone stage: with it on, et_merge_select brackets
+/* The same for the stand-alone stage: with it on, et_merge_select and et_merge_select_static bracket
  * every launch, and the whole launch sequence, with HIP events on `hip_stream`.  The read fills
  * ms[ET_K_COUNT] / launches[ET_K_COUNT] per kernel kind, *total_ms with the summed time between the
  * first launch's start and the last launch's end (launch gaps included, the final device-to-host copy

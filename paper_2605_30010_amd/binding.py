@@ -97,6 +97,7 @@ def load_library():
         "et_attention": (C.c_int, [vp, vp, i32, i32, i32, i32, vp, vp]),
         "et_attention_uniform": (C.c_int, [vp, i32, i32, i32, i32, vp, vp]),
         "et_encoder_block_qkv": (C.c_int, [vp, i32, vp, i32, vp, vp, vp]),
+        "et_merge_select_static": (C.c_int, [vp, i32, i32, i32, f32, f32, vp, C.POINTER(_Output)]),
         "et_encoder_create": (C.c_int, [C.POINTER(_Config), C.POINTER(_Weights), i32, C.POINTER(vp)]),
         "et_encoder_destroy": (None, [vp]),
         "et_workspace_bytes": (sz, [vp, i32]),
@@ -189,6 +190,18 @@ def et_merge_select(x, sim_threshold, keep_ratio, workspace=None, outputs=None, 
     o = _out_struct(bufs)
     _check(lib.et_merge_select(_ptr(x), T, L, D, float(sim_threshold), float(keep_ratio), _ptr(workspace),
                                workspace.numel(), _stream(stream), C.byref(o)))
+    return _trim(bufs, o, T)
+
+
+def et_merge_select_static(x, sim_threshold, keep_ratio, outputs=None, stream=None):
+    """et_merge_select on the library's static scratch buffer (no workspace argument)."""
+    lib = load_library()
+    _dev(x, torch.bfloat16, "x")
+    T, L, D = x.shape
+    bufs = outputs if outputs is not None else _alloc_outputs(T, L, D, x.device)
+    o = _out_struct(bufs)
+    _check(lib.et_merge_select_static(_ptr(x), T, L, D, float(sim_threshold), float(keep_ratio), _stream(stream),
+                                      C.byref(o)))
     return _trim(bufs, o, T)
 
 

@@ -4,7 +4,14 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "et_common.h"
+
+// Scratch of et_merge_select_static: one copy per GPU that loads the library, held until the process
+// ends.  In host code this name is only a handle for hipGetSymbolAddress (see static_scratch below);
+// it is never passed to a kernel or a copy.
+static __device__ __align__(256) unsigned char scratch[ET_STATIC_SCRATCH_BYTES];
 
 namespace et {
 
@@ -25,6 +32,31 @@ int hip_fail(hipError_t e, const char *what, const char *file, int line) {
 }
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Device address of `scratch` on the current device, looked up once per device.
+static int static_scratch(void **out) {
+  constexpr int kMaxDevices = 64;
+  static void *ptrs[kMaxDevices] = {};
+  static std::mutex mu;
+  int dev = 0;
+  ET_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) {
+    set_error("device index %d outside [0, %d)", dev, kMaxDevices);
+    return ET_ERR_UNSUPPORTED;
+  }
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptrs[dev]) {
+    void *p = nullptr;
+    ET_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) {
+      set_error("hipGetSymbolAddress returned a null address for the static scratch buffer");
+      return ET_ERR_HIP;
+    }
+    ptrs[dev] = p;
+  }
+  *out = ptrs[dev];
+  return ET_OK;
+}
 
 // Carves a workspace into 256-byte aligned pieces.
 struct Carver {
@@ -269,6 +301,21 @@ int et_merge_profile_read(double *ms, int64_t *launches, double *total_ms, int64
   *calls = g_stage.calls;
   if (reset) { g_stage.total_ms = 0.0; g_stage.calls = 0; }
   return ET_OK;
+}
+
+int et_merge_select_static(const uint16_t *x_dev, int32_t T, int32_t L, int32_t D, float sim_threshold,
+                           float keep_ratio, void *hip_stream, et_output *out) {
+  int rc;
+  if ((rc = check_merge_args(x_dev, T, L, D, sim_threshold, keep_ratio, out))) return rc;
+  const size_t need = et_merge_workspace_bytes(T, L, D);
+  if (need > (size_t)ET_STATIC_SCRATCH_BYTES) {
+    set_error("T * L * D = %d * %d * %d needs %zu bytes of scratch, the static buffer holds %zu: "
+              "use et_merge_select with a caller workspace", T, L, D, need, (size_t)ET_STATIC_SCRATCH_BYTES);
+    return ET_ERR_WORKSPACE;
+  }
+  void *ptr = nullptr;
+  if ((rc = static_scratch(&ptr))) return rc;
+  return merge_select_on(x_dev, T, L, D, sim_threshold, keep_ratio, ptr, static_cast<hipStream_t>(hip_stream), out);
 }
 
 int et_merge_select(const uint16_t *x_dev, int32_t T, int32_t L, int32_t D, float sim_threshold,

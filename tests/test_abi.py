@@ -82,6 +82,26 @@ def test_merge_select_rejects_bad_arguments_before_device_work():
     assert call(fake, 4, 8, 64, 0.9, 0.5, fake, 1 << 30, None) == -1
 
 
+def test_static_scratch_entry_point_rejects_bad_arguments_and_oversized_shapes():
+    """The entry point without a workspace argument validates like et_merge_select and refuses, before
+    any device work, shapes whose scratch would not fit its fixed buffer."""
+    lib = et.load_library()
+    out = B._Output()
+    fake = C.c_void_p(4096)
+    out.tokens_dev = out.kept_idx_dev = out.cu_tokens_dev = out.seg_start_dev = 4096
+    call = lambda x, T, L, D, tau, r, o: lib.et_merge_select_static(x, T, L, D, tau, r, None, o)
+    assert call(None, 4, 8, 64, 0.9, 0.5, C.byref(out)) == -1
+    assert call(fake, 4, 8, 60, 0.9, 0.5, C.byref(out)) == -1
+    assert call(fake, 4, 8, 64, math.nan, 0.5, C.byref(out)) == -1
+    assert call(fake, 4, 8, 64, 0.9, 0.0, C.byref(out)) == -1
+    assert call(fake, 4, 8, 64, 0.9, 0.5, None) == -1
+    limit = 64 << 20
+    assert et.et_merge_workspace_bytes(39, 729, 1152) <= limit < et.et_merge_workspace_bytes(40, 729, 1152)
+    assert call(fake, 40, 729, 1152, 0.9, 0.5, C.byref(out)) == -2
+    assert "static buffer" in et.et_last_error() and str(limit) in et.et_last_error()
+    assert call(fake, 64, 729, 1152, 0.9, 0.5, C.byref(out)) == -2
+
+
 def test_encoder_entry_points_reject_bad_arguments():
     lib = et.load_library()
     handle = C.c_void_p()
