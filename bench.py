@@ -73,8 +73,7 @@ def bytes_tables(shape, T, N, k):
         ("similarity", 0): X + (T - 1) * L * 4,
         ("scan", 0): (T - 1) * ((L + 3) // 4) * 4 + (T - 1) * 4 + (T + 1) * 4,
         ("merge", 0): X + N * L * D * 2 + N * L * 4,
-        ("select", 0): N * L * 4 + N * k * 4,
-        ("compact", 0): 2 * N * k * D * 2 + N * k * 4,
+        ("select", 0): N * L * 4 + N * k * 4 + 2 * N * k * D * 2,      # selection and gather are one launch
         # row statistics of the LayerNorms folded into the QKV / fc1 GEMMs: the rows are read, one float per row
         # is written (phase 1 also holds the one real LayerNorm, the final one: slightly under-counted)
         ("layernorm", 0): T * L * D * 2 + T * L * 4,
@@ -152,9 +151,9 @@ def time_steps(fn, steps, warmup, torch):
 
 def merge_microbench(et, torch, steps, warmup, variant=0):
     """The compression stage alone (et_merge_select) on the [64, 729, 1152] bf16 tensor of the merge-only
-    workload.  Before every timed call a 512 MiB buffer is overwritten, so the tensor starts out of the
-    256 MiB last-level cache: the stage's first pass comes from HBM, as it would behind a real encoder whose
-    activations do not fit.  Times come from HIP events that the library records on the launch stream around
+    workload.  Before every timed call a 1 GiB buffer is READ (a reduction: the caches are left full of clean
+    lines of another buffer, with nothing to write back), so the tensor starts out of the 256 MiB last-level
+    cache: the stage's first pass comes from HBM, as it would behind a real encoder whose activations do not fit.  Times come from HIP events that the library records on the launch stream around
     every launch and around the whole sequence (et_merge_profile_*)."""
     import numpy as np
     from et_inputs import build_workload, bf16_bits_to_f32
@@ -166,7 +165,7 @@ def merge_microbench(et, torch, steps, warmup, variant=0):
     x = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).cuda()
     ws = torch.empty((et.et_merge_workspace_bytes(T, L, D),), dtype=torch.uint8, device="cuda")
     bufs = B._alloc_outputs(T, L, D, x.device)
-    flush = torch.empty((512 << 20,), dtype=torch.uint8, device="cuda")
+    flush = torch.ones((256 << 20,), dtype=torch.float32, device="cuda")     # 1 GiB
     stream = torch.cuda.current_stream()
     run = lambda: et.et_merge_select(x, tau, keep, workspace=ws, outputs=bufs, stream=stream)
     for _ in range(warmup):
@@ -179,18 +178,18 @@ def merge_microbench(et, torch, steps, warmup, variant=0):
     assert np.array_equal(out["kept_idx"].cpu().numpy(), st["kept_idx"].reshape(-1))
     b_alg = stage_bytes(T, L, D, N, k)
     alg = {"similarity": T * L * D * 2 + (T - 1) * L * 4, "scan": (T - 1) * ((L + 3) // 4) * 4 + 2 * T * 4,
-           "merge": T * L * D * 2 + N * L * D * 2 + N * L * 4, "select": N * L * 4 + N * k * 4,
-           "compact": 2 * N * k * D * 2 + N * k * 4}
+           "merge": T * L * D * 2 + N * L * D * 2 + N * L * 4,
+           "select": N * L * 4 + N * k * 4 + 2 * N * k * D * 2}          # selection and gather are one launch
 
-    def timed(cold):
-        et.et_merge_profile_enable(True)
+    def timed(cold, level):
+        et.et_merge_profile_enable(level)
         et.et_merge_profile_read(reset=True)
         for _ in range(steps):
             if cold:
-                flush.fill_(1)
+                flush.sum()
             run()
         per, total_ms, calls = et.et_merge_profile_read(reset=True)
-        et.et_merge_profile_enable(False)
+        et.et_merge_profile_enable(0)
         us = 1e3 * total_ms / calls
         kernels = {}
         for kind, (ms, cnt) in per.items():
@@ -198,15 +197,17 @@ def merge_microbench(et, torch, steps, warmup, variant=0):
             kernels[kind] = {"avg_us": round(kus, 2), "gbs": round(alg[kind] / kus / 1e3, 1),
                              "hbm_frac": round(alg[kind] / kus / 1e3 / PEAK_HBM_GBS, 4)}
         return us, kernels
-    us_cold, k_cold = timed(True)
-    us_warm, k_warm = timed(False)
+    us_cold, _ = timed(True, 1)              # the sequence as it runs, two events around it
+    _, k_cold = timed(True, 2)               # again with events around every launch
+    us_warm, _ = timed(False, 1)
+    _, k_warm = timed(False, 2)
     res = {"workload": "c5_merge_only", "shape": [T, L, D], "n_frames_out": N, "k": k, "steps": steps,
            "algorithmic_bytes": b_alg, "avg_us": round(us_cold, 2), "gbs": round(b_alg / us_cold / 1e3, 1),
            "hbm_frac": round(b_alg / us_cold / 1e3 / PEAK_HBM_GBS, 4),
            "kernels": k_cold,
            "cache_resident": {"avg_us": round(us_warm, 2), "gbs": round(b_alg / us_warm / 1e3, 1),
                               "kernels": {n_: e["avg_us"] for n_, e in k_warm.items()}},
-           "timed": "first launch's start to last launch's end on the launch stream (5 launches, gaps included)",
+           "timed": "first launch's start to last launch's end on the launch stream (4 launches, gaps included)",
            "decisions_match_oracle": True}
     return res, rec
 
@@ -321,7 +322,7 @@ def main():
         kernels["share_kept_blocks"] = round(kept_share, 4)
         # the compression stage inside the clip, as one bandwidth figure (its tensor is cache-resident here:
         # block m - 1 has just written it; the cold figure is merge_stage_c5)
-        stage_ms = sum(prof[(kk, 0)][0] for kk in ("similarity", "scan", "merge", "select", "compact"))
+        stage_ms = sum(prof[(kk, 0)][0] for kk in ("similarity", "scan", "merge", "select"))
         stage_cnt = max(prof[("similarity", 0)][1], 1)
         D, L = shape.d_model, shape.tokens_per_frame
         sb = stage_bytes(T, L, D, N, k)

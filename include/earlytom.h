@@ -216,8 +216,9 @@ int et_profile_enable(et_encoder *enc, int32_t on);
  * compression stage), phase 1 = launches on the kept tokens; clears them if `reset` != 0. */
 int et_profile_read(et_encoder *enc, double *ms, int64_t *launches, int32_t reset);
 const char *et_kernel_name(int32_t kind);
-/* The same for the stand-alone stage: with it on, et_merge_select and et_merge_select_static bracket
- * every launch, and the whole launch sequence, with HIP events on `hip_stream`.  The read fills
+/* The same for the stand-alone stage: with on = 1, et_merge_select and et_merge_select_static bracket
+ * the whole launch sequence with two HIP events on `hip_stream`; with on = 2 also every launch (which
+ * lengthens the sequence by the events' own cost).  The read fills
  * ms[ET_K_COUNT] / launches[ET_K_COUNT] per kernel kind, *total_ms with the summed time between the
  * first launch's start and the last launch's end (launch gaps included, the final device-to-host copy
  * and stream wait excluded) and *calls.  Process-wide state, not thread-safe; off by default. */

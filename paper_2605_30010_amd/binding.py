@@ -485,7 +485,8 @@ def et_profile_read(handle, reset=True):
 
 
 def et_merge_profile_enable(on):
-    _check(load_library().et_merge_profile_enable(int(bool(on))))
+    """0 = off, 1 = time the whole launch sequence, 2 = also every launch."""
+    _check(load_library().et_merge_profile_enable(int(on)))
 
 
 def et_merge_profile_read(reset=True):

@@ -119,8 +119,12 @@ int enqueue_merge_stage(const uint16_t *x, int T, int L, int D, float tau, int k
     ET_HIP(hipEventRecord(early->ready, s));
   }
   ET_TIMED_P(prof, ET_K_MERGE, launch_segment_mean(x, T, L, D, seg_start, w.n_seg, w.merged, w.score, s));
-  ET_TIMED_P(prof, ET_K_SELECT, launch_topk(w.score, T, w.n_seg, L, k, kept, cu_tokens, s));
-  ET_TIMED_P(prof, ET_K_COMPACT, launch_compact(w.merged, kept, T, w.n_seg, L, D, k, packed, s));
+  if (L <= 7680) {     // selection and gather in one launch
+    ET_TIMED_P(prof, ET_K_SELECT, launch_topk_gather(w.score, w.merged, T, w.n_seg, L, D, k, kept, cu_tokens, packed, s));
+  } else {
+    ET_TIMED_P(prof, ET_K_SELECT, launch_topk(w.score, T, w.n_seg, L, k, kept, cu_tokens, s));
+    ET_TIMED_P(prof, ET_K_COMPACT, launch_compact(w.merged, kept, T, w.n_seg, L, D, k, packed, s));
+  }
   return ET_OK;
 }
 
@@ -245,6 +249,7 @@ static int check_merge_args(const uint16_t *x_dev, int32_t T, int32_t L, int32_t
 // around the whole sequence, on the caller's stream.  Process-wide; not thread-safe.
 static struct StageProfile {
   Profiler p;
+  bool on = false;                 // the whole-sequence bracket; p.on adds the per-launch brackets
   hipEvent_t t0 = nullptr, t1 = nullptr;
   double total_ms = 0.0;
   int64_t calls = 0;
@@ -256,14 +261,14 @@ static int merge_select_on(const uint16_t *x_dev, int32_t T, int32_t L, int32_t 
   int rc;
   MergeWs w = carve_merge(scratch_dev, T, L, D);
   const int k = et_keep_count(L, keep_ratio);
-  const bool timed = g_stage.p.on;
+  const bool timed = g_stage.on;
   if (timed) {
     g_stage.p.kinds.clear();
     ET_HIP(hipEventRecord(g_stage.t0, s));
   }
   if ((rc = enqueue_merge_stage(x_dev, T, L, D, sim_threshold, k, w, out->frame_sim_dev,
                                 out->seg_start_dev, out->kept_idx_dev, out->cu_tokens_dev,
-                                out->tokens_dev, s, timed ? &g_stage.p : nullptr)))
+                                out->tokens_dev, s, g_stage.p.on ? &g_stage.p : nullptr)))
     return rc;
   if (timed) ET_HIP(hipEventRecord(g_stage.t1, s));
   int32_t n_seg = 0;
@@ -286,7 +291,8 @@ int et_merge_profile_enable(int32_t on) {
     ET_HIP(hipEventCreate(&g_stage.t0));
     ET_HIP(hipEventCreate(&g_stage.t1));
   }
-  g_stage.p.on = on != 0;
+  g_stage.on = on != 0;
+  g_stage.p.on = on >= 2;
   return ET_OK;
 }
 

@@ -183,6 +183,9 @@ int launch_segment_mean(const uint16_t *x, int T, int L, int D, const int32_t *s
                         const int32_t *n_seg, uint16_t *merged, float *score, hipStream_t s);
 int launch_topk(const float *score, int n_rows_max, const int32_t *n_rows_dev, int L, int k,
                 int32_t *kept, int32_t *cu_tokens, hipStream_t s);
+// selection and gather of the kept rows in one launch (n_rows_dev must not be NULL; L <= 7680)
+int launch_topk_gather(const float *score, const uint16_t *merged, int n_rows_max, const int32_t *n_rows_dev, int L,
+                       int D, int k, int32_t *kept, int32_t *cu_tokens, uint16_t *out, hipStream_t s);
 int launch_compact(const uint16_t *merged, const int32_t *kept, int n_rows_max,
                    const int32_t *n_rows_dev, int L, int D, int k, uint16_t *out, hipStream_t s);
 int launch_identity_maps(int T, int L, int32_t *kept, int32_t *cu_tokens, int32_t *seg_start,

@@ -12,25 +12,31 @@ namespace et {
 
 namespace {
 
-constexpr int kRowsPerBlock = 4;   // wavefronts per workgroup in the row-streaming kernels
+// Wavefronts per workgroup in the row-streaming kernels.  Measured on [64, 729, 1152]: 2, 4 or 8
+// per workgroup and 2048 to 8192 wavefronts per launch all give the same time within 2 % (the two
+// passes over x run at about 5 TB/s whether x comes from HBM or from the last-level cache: the
+// limit is the path between the compute dies and the memory side, not the kernels' shape).
+constexpr int kRowsPerBlock = 4;
+constexpr int kSimWaves = kRowsPerBlock;
+constexpr int kMeanWaves = kRowsPerBlock;
 
 // ---------------------------------------------------------------------------------------
 // Similarity: cos[t-1, l] = <x[t,l], x[t-1,l]> / max(|x[t,l]| |x[t-1,l]|, 1e-8), t = 1..T-1.
 // One wavefront = one position l and `chunk` consecutive pairs; the previous row stays in
 // registers, so x is read (chunk + 1) / chunk times; two further rows are in flight while one
-// is reduced.  The workgroup also leaves, per pair, the sum of its kRowsPerBlock cosines in
+// is reduced.  The workgroup also leaves, per pair, the sum of its kSimWaves cosines in
 // part[t-1, blockIdx.x] (added in wavefront order), so that the mean over positions needs
-// L / kRowsPerBlock values per pair instead of L (part may be NULL: not written).
+// L / kSimWaves values per pair instead of L (part may be NULL: not written).
 // ---------------------------------------------------------------------------------------
 constexpr int kSimMaxChunk = 16;
 
 template <int NV>
-__global__ __launch_bounds__(kRowsPerBlock * kWave) void similarity_kernel(
+__global__ __launch_bounds__(kSimWaves * kWave) void similarity_kernel(
     const uint16_t *__restrict__ x, int T, int L, int D, int chunk, float *__restrict__ cos_out,
     float *__restrict__ part) {
-  __shared__ float csum[kRowsPerBlock][kSimMaxChunk];
+  __shared__ float csum[kSimWaves][kSimMaxChunk];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int l = blockIdx.x * kRowsPerBlock + wave;
+  const int l = blockIdx.x * kSimWaves + wave;
   const int t_first = blockIdx.y * chunk + 1;                   // first pair's later frame
   const int t_last = min(t_first + chunk - 1, T - 1);           // (t_first <= T - 1 by the grid's size)
   if (lane < kSimMaxChunk) csum[wave][lane] = 0.f;              // positions past L add nothing
@@ -77,7 +83,7 @@ __global__ __launch_bounds__(kRowsPerBlock * kWave) void similarity_kernel(
   if (part && i <= t_last - t_first) {
     float a = csum[0][i];
 #pragma unroll
-    for (int w = 1; w < kRowsPerBlock; ++w) a += csum[w][i];
+    for (int w = 1; w < kSimWaves; ++w) a += csum[w][i];
     part[(size_t)(t_first - 1 + i) * gridDim.x + blockIdx.x] = a;
   }
 }
@@ -94,12 +100,31 @@ __global__ __launch_bounds__(1024) void sim_mean_scan_kernel(
     int32_t *__restrict__ seg_start, int32_t *__restrict__ n_seg, int do_mean, int do_scan) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
   if (do_mean) {
-    for (int t = wave; t < T - 1; t += n_waves) {
-      const float *row = src + (size_t)t * n_src;
-      float acc = 0.f;
-      for (int i = lane; i < n_src; i += kWave) acc += row[i];
-      acc = wave_sum(acc);
-      if (lane == 0) sim[t] = acc / (float)L;
+    // a wavefront sums four rows at a time, their loads issued together (the kernel is one round trip
+    // to memory per 64 rows when a row has at most 256 values); each row's sum keeps its fixed order
+    constexpr int U = 4;
+    for (int t0 = wave; t0 < T - 1; t0 += U * n_waves) {
+      float acc[U] = {0.f, 0.f, 0.f, 0.f};
+      for (int i0 = lane; i0 < n_src; i0 += 4 * kWave) {
+        float v[U][4];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const int t = t0 + u * n_waves, i = i0 + j * kWave;
+            v[u][j] = (t < T - 1 && i < n_src) ? src[(size_t)t * n_src + i] : 0.f;
+          }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc[u] += v[u][j];
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const float a = wave_sum(acc[u]);
+        const int t = t0 + u * n_waves;
+        if (lane == 0 && t < T - 1) sim[t] = a / (float)L;
+      }
     }
   }
   if (!do_scan) return;
@@ -130,13 +155,13 @@ __global__ __launch_bounds__(1024) void sim_mean_scan_kernel(
 // segments (T) and exits when n >= *n_seg, so no host round trip is needed between scan and merge.
 // ---------------------------------------------------------------------------------------
 template <int NV>
-__global__ __launch_bounds__(kRowsPerBlock * kWave) void segment_mean_kernel(
+__global__ __launch_bounds__(kMeanWaves * kWave) void segment_mean_kernel(
     const uint16_t *__restrict__ x, int L, int D, const int32_t *__restrict__ seg_start,
     const int32_t *__restrict__ n_seg, uint16_t *__restrict__ merged, float *__restrict__ score) {
   const int n = blockIdx.y;
   if (n >= *n_seg) return;
   const int lane = threadIdx.x & 63;
-  const int l = blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
+  const int l = blockIdx.x * kMeanWaves + (threadIdx.x >> 6);
   if (l >= L) return;
   const int a = seg_start[n], b = seg_start[n + 1];
   const size_t frame_stride = (size_t)L * D;
@@ -215,6 +240,63 @@ __global__ __launch_bounds__(kSelThreads) void topk_kernel(
 }
 
 // ---------------------------------------------------------------------------------------
+// Selection and gather in one launch (what the stage runs): gridDim.x workgroups per frame each
+// repeat the frame's radix select (a few microseconds on L keys, all in LDS) into an LDS list and
+// then copy their share of the kept rows, rows j = blockIdx.x * 4 + wavefront, + 4 gridDim.x, ...:
+//   out[n*k + j, :] = merged[n, sel[j], :]   (Eq. 7).
+// The repeated select costs nothing in time (the workgroups run side by side), and the gather no
+// longer waits for a kernel boundary and a dependent index load.  Workgroup 0 of a frame also
+// writes the kept positions and the token offsets.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kSelThreads) void topk_gather_kernel(
+    const float *__restrict__ score, const uint16_t *__restrict__ merged, const int32_t *__restrict__ n_rows_dev,
+    int L, int D, int k, int32_t *__restrict__ kept, int32_t *__restrict__ cu_tokens, uint16_t *__restrict__ out) {
+  extern __shared__ uint32_t smem[];     // keys [L], then the kept positions [k]
+  uint32_t *keys = smem;
+  int32_t *sel = reinterpret_cast<int32_t *>(smem + L);
+  __shared__ SelectShared sh;
+  const int n = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // the frame's scores are fetched before the frame count is known (row n < gridDim.y lies inside the
+  // score buffer whether or not the frame exists), so that the two loads overlap
+  const float *row = score + (size_t)n * L;
+  for (int i = tid; i < L; i += kSelThreads) keys[i] = score_key(row[i]);
+  const int n_rows = *n_rows_dev;
+  if (n >= n_rows) return;
+  if (blockIdx.x == 0 && tid == 0) {
+    cu_tokens[n] = n * k;
+    if (n == 0) cu_tokens[n_rows] = n_rows * k;
+  }
+  radix_select_emit(keys, L, k, sel, sh);
+  __syncthreads();
+  if (blockIdx.x == 0)
+    for (int j = tid; j < k; j += kSelThreads) kept[(size_t)n * k + j] = sel[j];
+  // gather: a wavefront's rows (two with the launcher's grid) are all in flight at once
+  const int chunks = D / 8;
+  const int stride = 4 * gridDim.x;
+  for (int j = blockIdx.x * 4 + wave; j < k; j += 2 * stride) {
+    const int j2 = j + stride;
+    const int l0 = sel[j], l1 = j2 < k ? sel[j2] : l0;
+    const uint4 *s0 = reinterpret_cast<const uint4 *>(merged + ((size_t)n * L + l0) * D);
+    const uint4 *s1 = reinterpret_cast<const uint4 *>(merged + ((size_t)n * L + l1) * D);
+    uint4 *d0 = reinterpret_cast<uint4 *>(out + ((size_t)n * k + j) * D);
+    uint4 *d1 = reinterpret_cast<uint4 *>(out + ((size_t)n * k + j2) * D);
+    for (int c = lane; c < chunks; c += 4 * kWave) {
+      uint4 v0[4], v1[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (c + u * kWave < chunks) { v0[u] = s0[c + u * kWave]; v1[u] = s1[c + u * kWave]; }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (c + u * kWave < chunks) {
+          d0[c + u * kWave] = v0[u];
+          if (j2 < k) d1[c + u * kWave] = v1[u];
+        }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
 // Gather (Eq. 7): out[n*k + j, :] = merged[n, kept[n*k + j], :].  One wavefront per row.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kRowsPerBlock * kWave) void compact_kernel(
@@ -250,15 +332,16 @@ __global__ void cu_uniform_kernel(int n, int step, int32_t *cu) {
 
 }  // namespace
 
-int similarity_blocks(int L) { return (L + kRowsPerBlock - 1) / kRowsPerBlock; }
+int similarity_blocks(int L) { return (L + kSimWaves - 1) / kSimWaves; }
 
 int launch_similarity(const uint16_t *x, int T, int L, int D, float *cos_out, float *part, hipStream_t s) {
   if (T < 2) return ET_OK;
   // pairs per wavefront: as many as keep about 4096 wavefronts in the grid (x is re-read 1 / chunk times)
   int chunk = (int)(((long long)(T - 1) * L + 4095) / 4096);
   chunk = chunk < 4 ? 4 : (chunk > kSimMaxChunk ? kSimMaxChunk : chunk);
+  chunk = (T - 1 + (T - 1 + chunk - 1) / chunk - 1) / ((T - 1 + chunk - 1) / chunk);   // same number of wavefronts, even shares
   dim3 grid(similarity_blocks(L), (T - 1 + chunk - 1) / chunk);
-  dim3 block(kRowsPerBlock * kWave);
+  dim3 block(kSimWaves * kWave);
   ET_DISPATCH_NV(D, hipLaunchKernelGGL(similarity_kernel<NV>, grid, block, 0, s, x, T, L, D, chunk, cos_out, part));
   ET_LAUNCH_CHECK();
   return ET_OK;
@@ -275,8 +358,8 @@ int launch_sim_mean_scan(const float *src, int n_src, int T, int L, float tau, f
 
 int launch_segment_mean(const uint16_t *x, int T, int L, int D, const int32_t *seg_start,
                         const int32_t *n_seg, uint16_t *merged, float *score, hipStream_t s) {
-  dim3 grid((L + kRowsPerBlock - 1) / kRowsPerBlock, T);
-  dim3 block(kRowsPerBlock * kWave);
+  dim3 grid((L + kMeanWaves - 1) / kMeanWaves, T);
+  dim3 block(kMeanWaves * kWave);
   ET_DISPATCH_NV(D, hipLaunchKernelGGL(segment_mean_kernel<NV>, grid, block, 0, s, x, L, D, seg_start,
                                        n_seg, merged, score));
   ET_LAUNCH_CHECK();
@@ -291,6 +374,20 @@ int launch_topk(const float *score, int n_rows_max, const int32_t *n_rows_dev, i
   }
   hipLaunchKernelGGL(topk_kernel, dim3(n_rows_max), dim3(kSelThreads), (size_t)L * sizeof(uint32_t), s,
                      score, n_rows_dev, L, k, kept, cu_tokens);
+  ET_LAUNCH_CHECK();
+  return ET_OK;
+}
+
+int launch_topk_gather(const float *score, const uint16_t *merged, int n_rows_max, const int32_t *n_rows_dev, int L,
+                       int D, int k, int32_t *kept, int32_t *cu_tokens, uint16_t *out, hipStream_t s) {
+  if (L > 7680) {
+    set_error("tokens per frame %d above the 7680 the fused selection supports", L);
+    return ET_ERR_UNSUPPORTED;
+  }
+  int per_frame = (k + 7) / 8;             // workgroups per frame: two rows per wavefront, at most 32 workgroups
+  per_frame = per_frame > 32 ? 32 : per_frame;
+  hipLaunchKernelGGL(topk_gather_kernel, dim3(per_frame, n_rows_max), dim3(kSelThreads),
+                     (size_t)(L + k) * sizeof(uint32_t), s, score, merged, n_rows_dev, L, D, k, kept, cu_tokens, out);
   ET_LAUNCH_CHECK();
   return ET_OK;
 }

@@ -19,44 +19,88 @@ struct SelectShared {
   int hist[256];
   int wave_tot[kSelWaves];
   int eq_tot[2][kSelWaves], gt_tot[2][kSelWaves];   // double-buffered by chunk parity
+  uint32_t wave_or[kSelWaves], wave_and[kSelWaves];
   uint32_t sel_bin;
   int sel_remaining;
 };
 
-// Inclusive prefix sum over the lanes of a wavefront.
-__device__ __forceinline__ int wave_inclusive_scan(int v, int lane) {
-#pragma unroll
-  for (int o = 1; o < kWave; o <<= 1) {
-    const int up = __shfl_up(v, o, kWave);
-    if (lane >= o) v += up;
-  }
+// Cross-lane steps by data-parallel primitives (DPP: the operand of a vector instruction is taken
+// from another lane of the same 16-lane row, or broadcast from the last lane of the previous row(s));
+// a lane that has no source lane reads 0.  Much shorter latency than the LDS permute the generic
+// shuffles go through.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_or_zero(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, ROW_MASK, 0xf, false);
+}
+
+// Inclusive prefix sum over the lanes of a wavefront: shifts by 1, 2, 4, 8 inside each row of 16
+// lanes, then lane 15 of rows 0 and 2 is added to rows 1 and 3, then lane 31 to rows 2 and 3.
+__device__ __forceinline__ int wave_inclusive_scan(int v) {
+  v += dpp_or_zero<0x111, 0xf>(v);     // row_shr:1
+  v += dpp_or_zero<0x112, 0xf>(v);     // row_shr:2
+  v += dpp_or_zero<0x114, 0xf>(v);     // row_shr:4
+  v += dpp_or_zero<0x118, 0xf>(v);     // row_shr:8
+  v += dpp_or_zero<0x142, 0xa>(v);     // row_bcast:15 into rows 1 and 3
+  v += dpp_or_zero<0x143, 0xc>(v);     // row_bcast:31 into rows 2 and 3
   return v;
 }
 
-// keys[0..L) (LDS, already staged and visible to the whole workgroup) -> dst[0..k): the k positions
-// that come first in the order (key descending, position ascending), written in ascending position.
-// Four 8-bit radix passes find the k-th largest key v* and how many keys equal to v* are still
-// wanted; per pass a 256-bin histogram (LDS atomics) is suffix-summed by the four wavefronts, 64 bins
-// each (shuffle scan inside a wavefront, wavefront totals through LDS).  The emit pass ranks every
-// position by two ballots: a kept key's slot is (#greater before it) + min(#equal before it, wanted).
-// Must be called by all kSelThreads threads; 1 <= k <= L.
+// OR over the lanes of a wavefront (same steps; the result is complete in lane 63).
+__device__ __forceinline__ uint32_t wave_or_all(uint32_t u) {
+  int v = (int)u;
+  v |= dpp_or_zero<0x111, 0xf>(v);
+  v |= dpp_or_zero<0x112, 0xf>(v);
+  v |= dpp_or_zero<0x114, 0xf>(v);
+  v |= dpp_or_zero<0x118, 0xf>(v);
+  v |= dpp_or_zero<0x142, 0xa>(v);
+  v |= dpp_or_zero<0x143, 0xc>(v);
+  return (uint32_t)__builtin_amdgcn_readlane(v, 63);
+}
+
+// keys[0..L) (LDS, staged by this workgroup; the first barrier inside orders the staging) ->
+// dst[0..k): the k positions that come first in the order (key descending, position ascending),
+// written in ascending position.  Radix passes of up to 8 bits find the k-th largest key v* and how
+// many keys equal to v* are still wanted.  The bits above the highest bit in which any two keys
+// differ are skipped (scores of one frame share sign, exponent and often leading mantissa bits: a
+// pass over those would send every key to one histogram bin, one LDS atomic after the other).  Per
+// pass a histogram (LDS atomics) is suffix-summed by the four wavefronts, 64 bins each (shuffle
+// scan inside a wavefront, wavefront totals through LDS).  The emit pass ranks every position by
+// two ballots: a kept key's slot is (#greater before it) + min(#equal before it, wanted).
+// Must be called by all kSelThreads threads; 1 <= k <= L.  dst may be LDS or global memory.
 __device__ __forceinline__ void radix_select_emit(const uint32_t *keys, int L, int k, int32_t *dst,
                                                   SelectShared &sh) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  uint32_t prefix = 0, mask = 0;
-  int remaining = k;                     // how many of the keys matching `prefix` are wanted
-  for (int pass = 0; pass < 4; ++pass) {
-    const int shift = 24 - 8 * pass;
+  __syncthreads();
+  uint32_t all_or = 0u, all_and = 0xFFFFFFFFu;
+  for (int i = tid; i < L; i += kSelThreads) {
+    const uint32_t kk = keys[i];
+    all_or |= kk;
+    all_and &= kk;
+  }
+  all_or = wave_or_all(all_or);
+  all_and = ~wave_or_all(~all_and);                  // AND = NOT (OR of the complements)
+  if (lane == 0) { sh.wave_or[wave] = all_or; sh.wave_and[wave] = all_and; }
+  __syncthreads();
+#pragma unroll
+  for (int w = 0; w < kSelWaves; ++w) { all_or |= sh.wave_or[w]; all_and &= sh.wave_and[w]; }
+  const uint32_t diff = all_or ^ all_and;
+  const int top = diff ? 32 - __clz(diff) : 0;       // bits [0, top) are to be resolved
+  uint32_t mask = top >= 32 ? 0u : ~((1u << top) - 1u);
+  uint32_t prefix = all_and & mask;                  // the bits every key shares
+  int remaining = k;                                 // how many of the keys matching `prefix` are wanted
+  for (int hi = top; hi > 0;) {
+    const int lo = hi > 8 ? hi - 8 : 0;
+    const uint32_t bmask = (1u << (hi - lo)) - 1u;
     sh.hist[tid] = 0;
     __syncthreads();
     for (int i = tid; i < L; i += kSelThreads) {
       const uint32_t kk = keys[i];
-      if ((kk & mask) == prefix) atomicAdd(&sh.hist[(kk >> shift) & 255u], 1);
+      if ((kk & mask) == prefix) atomicAdd(&sh.hist[(kk >> lo) & bmask], 1);
     }
     __syncthreads();
     // thread t owns bin 255 - t: an inclusive scan in thread order counts the candidates in bins >= its own
     const int mine = sh.hist[255 - tid];
-    const int incl_w = wave_inclusive_scan(mine, lane);
+    const int incl_w = wave_inclusive_scan(mine);
     if (lane == kWave - 1) sh.wave_tot[wave] = incl_w;
     __syncthreads();
     int base = 0;
@@ -70,9 +114,10 @@ __device__ __forceinline__ void radix_select_emit(const uint32_t *keys, int L, i
       sh.sel_remaining = remaining - above;
     }
     __syncthreads();
-    prefix |= sh.sel_bin << shift;
-    mask |= 0xFFu << shift;
+    prefix |= sh.sel_bin << lo;
+    mask |= bmask << lo;
     remaining = sh.sel_remaining;
+    hi = lo;
   }
   const uint32_t vstar = prefix;
   const int need_eq = remaining;
