@@ -343,6 +343,26 @@ def main():
         paper = {"merge_layers": layers, "select_layer": sel, "policy": pol, "ms_per_step": round(1e3 * pt / args.steps, 3),
                  "frames_per_s": round(T * args.steps / pt, 2), "n_frames_out": po["n_frames_out"],
                  "n_tokens_out": po["n_tokens"], "retention": round(po["n_tokens"] / (T * shape.tokens_per_frame), 4)}
+        # "encoder + visual token processing" (Sec. 3.1: encoder -> projector -> language model): the same call
+        # followed by a two-layer projector of a 7B language model's width (1152 -> 3584 -> 3584, random weights)
+        rngp = np.random.default_rng(7)
+        d_llm = 3584
+        proj = et.Projector(rngp.standard_normal((d_llm, shape.d_model), dtype=np.float32) * 0.02, np.zeros(d_llm, np.float32),
+                            rngp.standard_normal((d_llm, d_llm), dtype=np.float32) * 0.02, np.zeros(d_llm, np.float32))
+        pbuf = torch.empty((T * shape.tokens_per_frame, d_llm), dtype=torch.bfloat16, device=dev)
+
+        def enc_and_project():
+            o = enc.encode_multi(frames, layers, sel, pol, stream=stream)
+            proj.project(o["tokens"], out=pbuf[:o["n_tokens"]], stream=stream)
+            return o
+        ppt, o_last = time_steps(enc_and_project, args.steps, max(args.warmup, 1), torch)
+        tok = o_last["tokens"].clone()
+        pj, _ = time_steps(lambda: proj.project(tok, out=pbuf[:tok.shape[0]], stream=stream), args.steps, 2, torch)
+        paper["encoder_plus_projector"] = {"projector": [shape.d_model, d_llm, d_llm],
+                                           "ms_per_step": round(1e3 * ppt / args.steps, 3),
+                                           "projector_alone_ms": round(1e3 * pj / args.steps, 3)}
+        proj.close()
+        del pbuf
         # the in-encoder decoupled policy (ragged frames after the selection) at the headline's merge layer
         pol2 = dict(pol, score_mode="l2")
         pt2, po2 = time_steps(lambda: enc.encode_policy(frames, m, pol2, stream=stream), args.steps,

@@ -312,6 +312,24 @@ size_t et_attention_scores_scratch_bytes(int32_t n_frames, int32_t L, int32_t n_
 int et_attention_scores(const uint16_t *qkv_dev, int32_t n_frames, int32_t L, int32_t n_heads,
                         int32_t head_dim, void *scratch_dev, float *score_dev, void *hip_stream);
 
+/* ---- the projector that follows the encoder (Sec. 3.1: vision encoder -> projector -> language
+ *      model) -------------------------------------------------------------------------------------
+ * A two-layer MLP on the kept tokens, out = W2 * gelu_tanh(W1 * x + b1) + b2, so that the time of
+ * "encoder + visual token processing" can be taken as one figure when the selection sits after the
+ * encoder (merge_layer = n_layers, where the paper places Stage II).  The paper does not describe the
+ * projector; the two-layer form and the GELU are this library's reading, the widths are arguments.
+ * Weights: HOST float32, out-features major (w1 [d_hidden, d_in], w2 [d_out, d_hidden]), converted once
+ * to bfloat16.  d_in a multiple of 64; d_hidden and d_out multiples of 8. */
+typedef struct et_projector et_projector;
+int et_projector_create(int32_t d_in, int32_t d_hidden, int32_t d_out, const float *w1, const float *b1,
+                        const float *w2, const float *b2, et_projector **out);
+void et_projector_destroy(et_projector *proj); /* NULL is allowed */
+size_t et_projector_workspace_bytes(const et_projector *proj, int32_t rows);
+/* tokens_dev bf16 [rows, d_in] -> out_dev bf16 [rows, d_out]; asynchronous on `hip_stream`.
+ * Errors: INVALID_ARG, WORKSPACE, HIP. */
+int et_project_tokens(et_projector *proj, const uint16_t *tokens_dev, int32_t rows, void *workspace_dev,
+                      size_t workspace_bytes, uint16_t *out_dev, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -126,6 +126,14 @@ def mlp(xn, lw):
     return h @ np.asarray(lw["w2"], dtype=dt).T + np.asarray(lw["b2"], dtype=dt)
 
 
+def project_tokens(x, w1, b1, w2, b2):
+    """The projector between encoder and language model (Sec. 3.1 names it, the paper gives no formula;
+    reading: a two-layer MLP with GELU-tanh): [n, D] -> [n, D_out] = gelu_tanh(x W1^T + b1) W2^T + b2."""
+    dt = x.dtype
+    h = gelu_tanh(x @ np.asarray(w1, dtype=dt).T + np.asarray(b1, dtype=dt))
+    return h @ np.asarray(w2, dtype=dt).T + np.asarray(b2, dtype=dt)
+
+
 def encoder_block(x, lw, n_heads, eps):
     """Pre-LN block: x += Attn(LN1(x)); x += MLP(LN2(x)).  x: [F, n, D]."""
     dt = x.dtype

@@ -12,5 +12,6 @@ from .binding import (  # noqa: F401
     et_layernorm, et_gemm_bf16, et_attention, et_attention_uniform, et_merge_select_static,
     et_encoder_block_qkv,
     et_encoder_create, et_encoder_destroy, et_workspace_bytes, et_encode_clip,
-    et_profile_enable, et_profile_read, et_kernel_name, et_merge_profile_enable, et_merge_profile_read, Encoder, KERNEL_KINDS,
+    et_profile_enable, et_profile_read, et_kernel_name, et_merge_profile_enable, et_merge_profile_read,
+    Encoder, Projector, KERNEL_KINDS,
 )

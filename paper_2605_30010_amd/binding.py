@@ -105,6 +105,10 @@ def load_library():
         "et_profile_enable": (C.c_int, [vp, i32]),
         "et_profile_read": (C.c_int, [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), i32]),
         "et_kernel_name": (C.c_char_p, [i32]),
+        "et_projector_create": (C.c_int, [i32, i32, i32, _FP, _FP, _FP, _FP, C.POINTER(vp)]),
+        "et_projector_destroy": (None, [vp]),
+        "et_projector_workspace_bytes": (sz, [vp, i32]),
+        "et_project_tokens": (C.c_int, [vp, vp, i32, vp, sz, vp, vp]),
         "et_merge_profile_enable": (C.c_int, [i32]),
         "et_merge_profile_read": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double),
                                            C.POINTER(C.c_int64), i32]),
@@ -501,6 +505,48 @@ def et_merge_profile_read(reset=True):
 
 def et_kernel_name(kind):
     return load_library().et_kernel_name(int(kind)).decode()
+
+
+class Projector:
+    """Owns an et_projector handle (two-layer MLP: w1 [d_hidden, d_in], b1, w2 [d_out, d_hidden], b2; host float32)."""
+
+    def __init__(self, w1, b1, w2, b2, device="cuda:0"):
+        self.device = torch.device(device)
+        w1, b1, w2, b2 = _f32(w1), _f32(b1), _f32(w2), _f32(b2)
+        self.d_hidden, self.d_in = w1.shape
+        self.d_out = w2.shape[0]
+        handle = C.c_void_p()
+        with torch.cuda.device(self.device):
+            _check(load_library().et_projector_create(self.d_in, self.d_hidden, self.d_out, w1.ctypes.data_as(_FP),
+                                                      b1.ctypes.data_as(_FP), w2.ctypes.data_as(_FP),
+                                                      b2.ctypes.data_as(_FP), C.byref(handle)))
+        self.handle = handle
+        self._ws = None
+
+    def project(self, tokens, out=None, stream=None):
+        """tokens bf16 CUDA [rows, d_in] -> bf16 [rows, d_out] (asynchronous on the stream)."""
+        lib = load_library()
+        _dev(tokens, torch.bfloat16, "tokens")
+        rows = tokens.shape[0]
+        need = int(lib.et_projector_workspace_bytes(self.handle, rows))
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = torch.empty((max(need, 1),), dtype=torch.uint8, device=self.device)
+        if out is None:
+            out = torch.empty((rows, self.d_out), dtype=torch.bfloat16, device=self.device)
+        _check(lib.et_project_tokens(self.handle, _ptr(tokens), rows, _ptr(self._ws), self._ws.numel(), _ptr(out),
+                                     _stream(stream)))
+        return out
+
+    def close(self):
+        if self.handle is not None:
+            load_library().et_projector_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 class Encoder:

@@ -248,3 +248,23 @@ def test_gemm_library_choice_at_encoder_row_count(N, epi):
     got = bf16_bits_to_f32(dev_to_bits(c))
     assert np.max(np.abs(got - ref) - 2 ** -8 * np.abs(ref)) < 5e-4
     assert rel_l2(got.astype(np.float64), ref.astype(np.float64)) < 4e-3
+
+
+@pytest.mark.parametrize("rows,d_in,d_hidden,d_out", [(4949, 1152, 3584, 3584), (300, 64, 104, 72), (1, 128, 8, 8)])
+def test_projector_matches_oracle(rows, d_in, d_hidden, d_out):
+    """The two-layer projector (Sec. 3.1) on as many tokens as the paper's layout keeps of a 32-frame clip,
+    at the widths of a 7B language model, and on small ragged widths; the hidden activation passes through
+    bfloat16 once, hence 1e-2."""
+    rng = np.random.default_rng(rows + d_out)
+    x_bits, x = _bf(rng, (rows, d_in))
+    w1_bits, w1 = _bf(rng, (d_hidden, d_in), scale=1.0 / math.sqrt(d_in))
+    w2_bits, w2 = _bf(rng, (d_out, d_hidden), scale=1.0 / math.sqrt(d_hidden))
+    b1 = (0.1 * rng.standard_normal(d_hidden)).astype(np.float32)
+    b2 = (0.1 * rng.standard_normal(d_out)).astype(np.float32)
+    proj = et.Projector(w1, b1, w2, b2)
+    got = dev_to_f64(proj.project(bits_to_dev(x_bits)))
+    proj.close()
+    ref = O.project_tokens(x, w1, b1.astype(np.float64), w2, b2.astype(np.float64))
+    assert got.shape == ref.shape
+    assert rel_l2(got, ref) < 1e-2
+    assert np.max(np.abs(got - ref)) < 0.05 * max(1.0, np.abs(ref).max())

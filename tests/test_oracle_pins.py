@@ -374,3 +374,22 @@ def test_blocks_after_compression_run_on_the_packed_tokens(tiny):
     f = O.encode_clip(TINY, w, frames, 2, 0.9, 0.5, force_seg_start=[0, 4, 8],
                       force_kept=st["kept_idx"])
     np.testing.assert_array_equal(f["tokens"], r["tokens"])
+
+
+def test_projector_equals_library_linear_gelu_linear():
+    """The projector (Sec. 3.1) is linear -> GELU-tanh -> linear: against torch's library routines, and a
+    dropped bias or a transposed weight shows."""
+    import torch
+    rng = np.random.default_rng(12)
+    n, D, Dh, Do = 7, 16, 24, 10
+    x, w1, b1 = rng.standard_normal((n, D)), rng.standard_normal((Dh, D)) * 0.3, rng.standard_normal(Dh)
+    w2, b2 = rng.standard_normal((Do, Dh)) * 0.3, rng.standard_normal(Do)
+    got = O.project_tokens(x, w1, b1, w2, b2)
+    t = lambda a: torch.from_numpy(a)
+    want = torch.nn.functional.linear(torch.nn.functional.gelu(torch.nn.functional.linear(t(x), t(w1), t(b1)),
+                                                               approximate="tanh"), t(w2), t(b2)).numpy()
+    assert got.shape == (n, Do)
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-12)
+    assert np.max(np.abs(O.project_tokens(x, w1, 0 * b1, w2, b2) - want)) > 1e-2
+    # zero input: only the biases act
+    np.testing.assert_allclose(O.project_tokens(np.zeros((1, D)), w1, b1, w2, b2)[0], O.gelu_tanh(b1) @ w2.T + b2, rtol=1e-13)
