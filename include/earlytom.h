@@ -277,8 +277,9 @@ int et_attention(const uint16_t *qkv_dev, const int32_t *cu_tokens_dev, int32_t 
                  void *hip_stream);
 
 /* The same attention for frames of equal length `len` (frame f = rows f*len .. f*len+len-1),
- * which is what the hot path runs: K tiles stream through LDS by direct global -> LDS loads and
- * the V^T fragments are taken with LDS transpose reads. */
+ * which is what the hot path runs; same kernel (K tiles stream through LDS by direct global -> LDS
+ * loads, V^T fragments by LDS transpose reads), and with enough frames a wavefront owns two blocks
+ * of 32 queries. */
 int et_attention_uniform(const uint16_t *qkv_dev, int32_t n_frames, int32_t len, int32_t n_heads,
                          int32_t head_dim, uint16_t *out_dev, void *hip_stream);
 

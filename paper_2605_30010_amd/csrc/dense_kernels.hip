@@ -564,13 +564,11 @@ int launch_gemm_stream_cfg(const GemmArgs &g, hipStream_t s) {
 // transposed: S^T = K Q^T puts the query on the accumulator's lane axis, so the running
 // maximum, the running sum and the rescale factor are per-lane scalars, and the exponentiated
 // accumulator registers are, without any data movement, MFMA operand "B" of
-// O^T = V^T P^T.  V is staged transposed in LDS with the keys of each 16-key chunk permuted
-// to match the accumulator's row order.
+// O^T = V^T P^T.
 // ---------------------------------------------------------------------------------------
 constexpr int kAttWaves = 4;
 constexpr int kAttBQ = kAttWaves * 32;
 constexpr int kAttBKV = 64;
-constexpr int kVtRow = kAttBKV + 8;
 
 // Workgroups go to the 8 XCDs round-robin by index.  A one-dimensional grid whose order puts
 // workgroups that share data next to each other is therefore remapped first: XCD x takes the x-th
@@ -580,159 +578,12 @@ __device__ __forceinline__ int xcd_contiguous_index() {
   return xcd * per + (xcd < rem ? xcd : rem) + slot;
 }
 
-template <int HD>
-__global__ __launch_bounds__(kAttWaves * 64) void attention_kernel(
-    const uint16_t *__restrict__ qkv, const int32_t *__restrict__ cu, int n_heads, int n_qblk, float scale_log2,
-    uint16_t *__restrict__ out) {
-  constexpr int NC = (HD + 15) / 16;        // 16-wide contraction chunks of Q K^T
-  constexpr int HDP = NC * 16;
-  constexpr int KROW = HDP + 8;             // LDS row stride of the K tile (elements)
-  constexpr int NDB = (HD + 31) / 32;       // 32-row blocks of O^T
-  constexpr int NCH = HD / 8;               // 16-byte chunks per head row in global memory
-  static_assert(HD % 8 == 0, "head_dim must be a multiple of 8");
-  __shared__ __align__(16) uint16_t Ks[kAttBKV * KROW];
-  __shared__ __align__(16) uint16_t Vt[NDB * 32 * kVtRow];
-
-  // grid over (frame, head, query block), query block fastest: the blocks of one (frame, head) read the same K and V
-  const int v = xcd_contiguous_index();
-  const int f = v / (n_qblk * n_heads), h = (v / n_qblk) % n_heads;
-  const int start = cu[f], len = cu[f + 1] - start;
-  const int q0 = (v % n_qblk) * kAttBQ;
-  if (q0 >= len) return;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int r32 = lane & 31, grp = lane >> 5;
-  const int D = n_heads * HD, ld = 3 * D;
-  const uint16_t *qbase = qkv + (size_t)start * ld + h * HD;
-  const uint16_t *kbase = qbase + D;
-  const uint16_t *vbase = qbase + 2 * D;
-
-  // rows of V^T past the head dimension stay zero for the whole kernel
-  for (int i = tid; i < NDB * 32 * kVtRow / 2; i += kAttWaves * 64) reinterpret_cast<uint32_t *>(Vt)[i] = 0u;
-
-  uint4 qf[NC];
-  {
-    const int q = q0 + wave * 32 + r32;
-#pragma unroll
-    for (int c = 0; c < NC; ++c) {
-      const int d = c * 16 + grp * 8;
-      qf[c] = (q < len && d < HD) ? *reinterpret_cast<const uint4 *>(qbase + (size_t)q * ld + d)
-                                  : make_uint4(0, 0, 0, 0);
-    }
-  }
-
-  f32x16 o_acc[NDB];
-#pragma unroll
-  for (int b = 0; b < NDB; ++b)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) o_acc[b][i] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;
-
-  for (int kv0 = 0; kv0 < len; kv0 += kAttBKV) {
-    __syncthreads();                                   // previous tile fully consumed (and Vt zeroed)
-    for (int i = tid; i < kAttBKV * (HDP / 8); i += kAttWaves * 64) {
-      const int key = i / (HDP / 8), ch = i % (HDP / 8);
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (kv0 + key < len && ch < NCH) v = *reinterpret_cast<const uint4 *>(kbase + (size_t)(kv0 + key) * ld + ch * 8);
-      *reinterpret_cast<uint4 *>(Ks + key * KROW + ch * 8) = v;
-    }
-    for (int i = tid; i < kAttBKV * NCH; i += kAttWaves * 64) {
-      const int key = i / NCH, ch = i % NCH;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (kv0 + key < len) v = *reinterpret_cast<const uint4 *>(vbase + (size_t)(kv0 + key) * ld + ch * 8);
-      // position of this key inside its 16-key chunk: group (key/4)%2, slot (key/8)*4 + key%4
-      const int k16 = key & 15;
-      const int pos = (key & ~15) + ((k16 >> 2) & 1) * 8 + (k16 >> 3) * 4 + (k16 & 3);
-      uint16_t *dst = Vt + (ch * 8) * kVtRow + pos;
-      dst[0 * kVtRow] = (uint16_t)(v.x & 0xFFFF); dst[1 * kVtRow] = (uint16_t)(v.x >> 16);
-      dst[2 * kVtRow] = (uint16_t)(v.y & 0xFFFF); dst[3 * kVtRow] = (uint16_t)(v.y >> 16);
-      dst[4 * kVtRow] = (uint16_t)(v.z & 0xFFFF); dst[5 * kVtRow] = (uint16_t)(v.z >> 16);
-      dst[6 * kVtRow] = (uint16_t)(v.w & 0xFFFF); dst[7 * kVtRow] = (uint16_t)(v.w >> 16);
-    }
-    __syncthreads();
-
-    // S^T for two 32-key blocks: rows = keys, columns = this wavefront's 32 queries
-    f32x16 s_acc[2];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) s_acc[kb][i] = 0.f;
-#pragma unroll
-      for (int c = 0; c < NC; ++c) {
-        const uint4 kf = *reinterpret_cast<const uint4 *>(Ks + (kb * 32 + r32) * KROW + c * 16 + grp * 8);
-        s_acc[kb] = mfma32(kf, qf[c], s_acc[kb]);
-      }
-    }
-    float m_tile = -INFINITY;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int key = kv0 + kb * 32 + (i >> 2) * 8 + grp * 4 + (i & 3);
-        const float v = (key < len) ? s_acc[kb][i] * scale_log2 : -INFINITY;
-        s_acc[kb][i] = v;
-        m_tile = fmaxf(m_tile, v);
-      }
-    m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32, 64));
-    const float m_new = fmaxf(m_run, m_tile);            // finite: every tile has a valid key
-    const float alpha = exp2f(m_run - m_new);
-    m_run = m_new;
-    float l_tile = 0.f;
-    uint4 pf[4];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      float p[16];
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        p[i] = exp2f(s_acc[kb][i] - m_new);
-        l_tile += p[i];
-      }
-#pragma unroll
-      for (int hh = 0; hh < 2; ++hh) {
-        uint4 v;
-        v.x = cvt_pk_bf16(p[hh * 8 + 0], p[hh * 8 + 1]); v.y = cvt_pk_bf16(p[hh * 8 + 2], p[hh * 8 + 3]);
-        v.z = cvt_pk_bf16(p[hh * 8 + 4], p[hh * 8 + 5]); v.w = cvt_pk_bf16(p[hh * 8 + 6], p[hh * 8 + 7]);
-        pf[kb * 2 + hh] = v;
-      }
-    }
-    l_run = l_run * alpha + l_tile;
-#pragma unroll
-    for (int b = 0; b < NDB; ++b) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) o_acc[b][i] *= alpha;
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const uint4 vf = *reinterpret_cast<const uint4 *>(Vt + (b * 32 + r32) * kVtRow + c * 16 + grp * 8);
-        o_acc[b] = mfma32(vf, pf[c], o_acc[b]);
-      }
-    }
-  }
-
-  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-  const float inv = 1.0f / l_tot;
-  const int q = q0 + wave * 32 + r32;
-  if (q < len) {
-    uint16_t *orow = out + (size_t)(start + q) * D + h * HD;
-#pragma unroll
-    for (int b = 0; b < NDB; ++b)
-#pragma unroll
-      for (int qd = 0; qd < 4; ++qd) {
-        const int d = b * 32 + qd * 8 + grp * 4;
-        if (d < HD) {
-          uint2 o;
-          o.x = cvt_pk_bf16(o_acc[b][qd * 4 + 0] * inv, o_acc[b][qd * 4 + 1] * inv);
-          o.y = cvt_pk_bf16(o_acc[b][qd * 4 + 2] * inv, o_acc[b][qd * 4 + 3] * inv);
-          *reinterpret_cast<uint2 *>(orow + d) = o;
-        }
-      }
-  }
-}
-
 // ---------------------------------------------------------------------------------------
-// Fast attention path for frames of equal length (always the case on the hot path).
-//
-// attention_dma_kernel: same transposed online-softmax scheme as attention_kernel, but the K tile
-// is brought in by direct global -> LDS loads and the V tile through registers, one tile ahead,
-// two LDS stages, one barrier per 64-key tile.
+// attention_dma_kernel: the K tile is brought in by direct global -> LDS loads and the V tile
+// through registers, one tile ahead, two LDS stages, one barrier per 64-key tile.  Frames have
+// equal length n (frame f = rows f n ..) or, with `cu` given, the row ranges cu[f] .. cu[f+1]
+// (decoupled selection: the grid is sized for the longest frame and workgroups past a frame's
+// end leave at once).
 // Both tiles sit in LDS as they are in memory, rows back to back (row stride = head_dim * 2
 // bytes; 144 bytes for head_dim 72 spreads 16-byte reads of consecutive rows over all banks).
 // MFMA wants the contraction index (the key) contiguous per lane for the P V product, i.e. V^T:
@@ -759,7 +610,8 @@ __device__ __forceinline__ uint2 lds_read_tr16(const uint16_t *p) {
 
 template <int HD, int QB, int MINB>
 __global__ __launch_bounds__(kAttWaves * 64, MINB) void attention_dma_kernel(
-    const uint16_t *__restrict__ qkv, int n, int n_heads, int n_qblk, float scale_log2, uint16_t *__restrict__ out) {
+    const uint16_t *__restrict__ qkv, const int32_t *__restrict__ cu, int n, int n_heads, int n_qblk, float scale_log2,
+    uint16_t *__restrict__ out) {
   constexpr int NC = (HD + 15) / 16;
   constexpr int NDB = (HD + 31) / 32;
   constexpr int STAGES = 2;
@@ -784,11 +636,17 @@ __global__ __launch_bounds__(kAttWaves * 64, MINB) void attention_dma_kernel(
   // of one (frame, head) - which read the same K and V - run on one XCD and share its L2.
   const int v = xcd_contiguous_index();
   const int q0 = (v % n_qblk) * (kAttBQ * QB), h = (v / n_qblk) % n_heads, f = v / (n_qblk * n_heads);
+  int start = f * n;
+  if (cu) {                                            // ragged frames (workgroup-uniform)
+    start = cu[f];
+    n = cu[f + 1] - start;
+    if (q0 >= n) return;
+  }
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps load dispatch scalar
   const int r32 = lane & 31, grp = lane >> 5;
   const int D = n_heads * HD, ld = 3 * D;
-  const uint16_t *qbase = qkv + (size_t)f * n * ld + h * HD;
+  const uint16_t *qbase = qkv + (size_t)start * ld + h * HD;
   const uint16_t *kbase = qbase + D;                    // (V: + D again)
   const int n_tiles = (n + kAttBKV - 1) / kAttBKV;
 
@@ -1018,7 +876,7 @@ __global__ __launch_bounds__(kAttWaves * 64, MINB) void attention_dma_kernel(
     const float inv = 1.0f / l_tot;
     const int q = q0 + (wave * QB + j) * 32 + r32;
     if (q < n) {
-      uint16_t *orow = out + ((size_t)f * n + q) * D + h * HD;
+      uint16_t *orow = out + ((size_t)start + q) * D + h * HD;
 #pragma unroll
       for (int b = 0; b < NDB; ++b)
 #pragma unroll
@@ -1181,8 +1039,11 @@ int launch_attention(const uint16_t *qkv, const int32_t *cu, int n_frames, int m
   const int n_qblk = (max_len + kAttBQ - 1) / kAttBQ;
   const dim3 grid((unsigned)n_qblk * n_heads * n_frames), block(kAttWaves * 64);
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)head_dim);
-#define ET_ATT(HD) \
-  case HD: hipLaunchKernelGGL(attention_kernel<HD>, grid, block, 0, s, qkv, cu, n_heads, n_qblk, scale_log2, out); break;
+#define ET_ATT(HD)                                                                                           \
+  case HD:                                                                                                   \
+    hipLaunchKernelGGL((attention_dma_kernel<HD, 1, (HD <= 96 ? 2 : 1)>), grid, block, 0, s, qkv, cu, 0, n_heads, \
+                       n_qblk, scale_log2, out);                                                             \
+    break;
   switch (head_dim) {
     ET_ATT(16) ET_ATT(32) ET_ATT(64) ET_ATT(72) ET_ATT(80) ET_ATT(96) ET_ATT(128)
     default: set_error("head_dim %d is not instantiated", head_dim); return ET_ERR_UNSUPPORTED;
@@ -1212,11 +1073,12 @@ int launch_attention_uniform(const uint16_t *qkv, int n_frames, int len, int n_h
   case HD:                                                                                                \
     if (HD <= 80 && wide)                                                                                 \
       hipLaunchKernelGGL((attention_dma_kernel<HD, (HD <= 80 ? 2 : 1), (HD <= 96 ? 2 : 1)>),            \
-                         dim3(agrid2.x * agrid2.y * agrid2.z), dim3(kAttWaves * 64), 0, s, qkv, len, n_heads,   \
-                         (int)agrid2.x, scale_log2, out);                                                 \
+                         dim3(agrid2.x * agrid2.y * agrid2.z), dim3(kAttWaves * 64), 0, s, qkv,                 \
+                         (const int32_t *)nullptr, len, n_heads, (int)agrid2.x, scale_log2, out);                                                 \
     else                                                                                                  \
       hipLaunchKernelGGL((attention_dma_kernel<HD, 1, (HD <= 96 ? 2 : 1)>), dim3(agrid.x * agrid.y * agrid.z),   \
-                         dim3(kAttWaves * 64), 0, s, qkv, len, n_heads, (int)agrid.x, scale_log2, out);   \
+                         dim3(kAttWaves * 64), 0, s, qkv, (const int32_t *)nullptr, len, n_heads, (int)agrid.x,   \
+                         scale_log2, out);                                                                \
     break;
   switch (head_dim) {
     ET_ATT(16) ET_ATT(32) ET_ATT(64) ET_ATT(72) ET_ATT(80) ET_ATT(96) ET_ATT(128)

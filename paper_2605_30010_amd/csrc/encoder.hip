@@ -161,7 +161,7 @@ static int run_block(et_encoder *e, const LayerDev &lw, const EncWs &w, int rows
   ET_TIMED(ET_K_GEMM_QKV, launch_gemm(g, s));
   if (with_scores)
     ET_TIMED(ET_K_SCORE, launch_attention_scores(w.qkv, n_frames, max_len, c.n_heads, e->hd, w.score_ws, w.att_score, s));
-  if (ragged) {   // frames of different lengths (decoupled selection): the general kernel
+  if (ragged) {   // frames of different lengths (decoupled selection): row ranges from cu
     ET_TIMED(ET_K_ATTENTION, launch_attention(w.qkv, cu, n_frames, max_len, c.n_heads, e->hd, w.att, s));
   } else {        // every frame has max_len tokens
     ET_TIMED(ET_K_ATTENTION, launch_attention_uniform(w.qkv, n_frames, max_len, c.n_heads, e->hd, w.att, s));

@@ -155,7 +155,7 @@ def test_attention_uniform_matches_oracle(n_heads, hd, n_frames, length):
     assert np.all(np.isfinite(got))
     assert rel_l2(got, ref) < 6e-3
     assert np.max(np.abs(got - ref)) < 0.05
-    # the general (ragged) kernel agrees on the same input
+    # the ragged entry point (row ranges from cu_tokens) agrees on the same input
     gen = et.et_attention(bits_to_dev(bits), torch.from_numpy(cu).cuda(), length, n_heads, hd)
     assert rel_l2(dev_to_f64(gen), got) < 6e-3
 
