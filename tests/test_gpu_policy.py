@@ -108,6 +108,52 @@ def test_merge_select_policy_matches_oracle(pi, T, L, D, mean_len):
         assert simple["cu_tokens"].tolist() == r["cu_tokens"].tolist()
 
 
+def _alg1_golden_cases():
+    import os
+    out = []
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "alg1_cases.txt")):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        p = [q.strip() for q in line.split("|")]
+        if len(p) > 4 and p[4] == "exact":
+            continue                      # sits on an equality: only meaningful for exactly given similarities
+        alpha, tau_seg, tau_merge = [float(v) for v in p[0].split()]
+        frames = [(int(t.split(":")[0]), int(t.split(":")[1].split("(")[0])) for t in p[3].split()]
+        out.append((alpha, tau_seg, tau_merge, [float(v) for v in p[1].split()], [int(v) for v in p[2].split()], frames))
+    return out
+
+
+@pytest.mark.parametrize("case", _alg1_golden_cases())
+def test_device_plan_on_the_hand_worked_alg1_cases(case):
+    """The hand-worked cases of Eq. 1 / Alg. 1 (tests/golden/alg1_cases.txt) against the DEVICE plan, not via the
+    oracle: hidden states are built so that every position's cosine between frames t and t-1 is the case's s_t
+    (x_t = s_t x_{t-1} + sqrt(1 - s_t^2) w_t with w_t a fresh unit vector orthogonal to x_{t-1}); the bfloat16
+    rounding moves a similarity by < 1e-3, the cases keep every comparison at least 5e-3 apart."""
+    alpha, tau_seg, tau_merge, s, seg, frames = case
+    T, L, D = len(s) + 1, 8, 256
+    rng = np.random.default_rng(T * 7 + len(frames))
+    x = np.empty((T, L, D))
+    x[0] = rng.standard_normal((L, D))
+    x[0] /= np.linalg.norm(x[0], axis=-1, keepdims=True)
+    for t in range(1, T):
+        w = rng.standard_normal((L, D))
+        w -= (w * x[t - 1]).sum(-1, keepdims=True) * x[t - 1]
+        w /= np.linalg.norm(w, axis=-1, keepdims=True)
+        x[t] = s[t - 1] * x[t - 1] + math.sqrt(1.0 - s[t - 1] ** 2) * w
+    bits = f64_to_bits(x * 3.0)
+    pol = _f32_policy(dict(merge_mode="alg1", select_mode="uniform", alpha=alpha, tau_seg=tau_seg, tau_merge=tau_merge,
+                           ratio=1.0))
+    r = et.et_merge_select_policy(bits_to_dev(bits), pol)
+    np.testing.assert_allclose(r["frame_sim"].cpu().numpy(), s, atol=1.5e-3)
+    assert r["seg_start"].tolist() == seg
+    assert list(zip(r["frame_first"].tolist(), r["frame_count"].tolist())) == frames
+    dyn = r["frame_dynamic"].tolist()
+    for n in range(len(seg) - 1):                    # head and tail of every segment are the dynamic frames
+        idx = [i for i, (f, c) in enumerate(frames) if seg[n] <= f < seg[n + 1]]
+        assert [dyn[i] for i in idx] == [1 if i in (idx[0], idx[-1]) else 0 for i in idx]
+
+
 def test_policy_degenerate_cases():
     rng = np.random.default_rng(5)
     from et_inputs import f32_to_bf16_bits

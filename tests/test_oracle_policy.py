@@ -22,7 +22,7 @@ def _alg1_cases():
         line = line.strip()
         if not line or line.startswith("#"):
             continue
-        p = [q.strip() for q in line.split("|")]
+        p = [q.strip() for q in line.split("|")]        # (a fifth field, "exact", is for the device test)
         alpha, tau_seg, tau_merge = [float(v) for v in p[0].split()]
         s = [float(v) for v in p[1].split()]
         seg = [int(v) for v in p[2].split()]
@@ -36,6 +36,44 @@ def _alg1_cases():
                 frames.append((int(first), int(rest), None))
         out.append((alpha, tau_seg, tau_merge, s, seg, frames))
     return out
+
+
+def _plan_by_runs(s, seg_start, tau_merge):
+    """Alg. 1's result characterised without walking the frames: inside a segment with frames F_0 .. F_k,
+    index i (1 <= i <= k - 2) is 'eligible' iff s_i > tau_merge and s_i > s_{i+1}; in every maximal run
+    a .. b of consecutive eligible indices the fused pairs start at a, a + 2, a + 4, ... <= b.  Everything
+    not covered by a pair is a frame of its own.  Returns [(first, count)]."""
+    out = []
+    for n in range(len(seg_start) - 1):
+        a0, k = int(seg_start[n]), int(seg_start[n + 1]) - int(seg_start[n]) - 1
+        elig = [1 <= i <= k - 2 and s[a0 + i] > tau_merge and s[a0 + i] > s[a0 + i + 1] for i in range(k + 1)]
+        starts, i = set(), 0
+        while i <= k:
+            if elig[i]:
+                j = i
+                while j + 1 <= k and elig[j + 1]:
+                    j += 1
+                starts.update(range(i, j + 1, 2))
+                i = j + 1
+            else:
+                i += 1
+        covered = {p + 1 for p in starts}
+        out += [(a0 + i, 2 if i in starts else 1) for i in range(k + 1) if i not in covered]
+    return out
+
+
+def test_alg1_walk_equals_the_run_characterisation():
+    """The oracle walks the middle frames left to right as Alg. 1 does; the same plan follows from the
+    maximal runs of eligible indices.  Random similarities on a coarse grid, so that ties s_i = s_{i+1} and
+    s_i = tau_merge occur often."""
+    rng = np.random.default_rng(4)
+    for _ in range(300):
+        T = int(rng.integers(1, 25))
+        s = rng.integers(0, 8, T - 1) / 8.0 + 0.125          # {0.125, 0.25, .. 1.0}
+        seg = O.segment_starts(s, 0.375, T)
+        for tau_merge in (0.5, 0.625, 0.0):
+            plan = O.merge_plan(s, seg, tau_merge, "alg1")
+            assert [(p["first"], p["count"]) for p in plan] == _plan_by_runs(s, seg, tau_merge)
 
 
 @pytest.mark.parametrize("case", _alg1_cases())
