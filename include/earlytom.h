@@ -225,8 +225,10 @@ const char *et_kernel_name(int32_t kind);
 int et_merge_profile_enable(int32_t on);
 int et_merge_profile_read(double *ms, int64_t *launches, double *total_ms, int64_t *calls, int32_t reset);
 
-/* ---- single steps (the same kernels the hot path launches; for parity tests and
- *      micro-benchmarks).  All asynchronous on `hip_stream` unless stated. ------------- */
+/* ---- single steps (the device code of the hot path, one step per call; for parity tests and
+ *      micro-benchmarks).  All asynchronous on `hip_stream` unless stated.  The hot path itself runs
+ *      selection and gather (et_topk_select + et_compact_tokens) as ONE launch on the same select
+ *      routine; the two calls below launch them separately. ------------- */
 
 /* Sec. 3.2: cos_dev [T-1, L] float32 per-position cosine similarities of frames t and t-1,
  * sim_dev [T-1] their mean over positions.  x_dev bf16 [T, L, D]. */
@@ -316,7 +318,7 @@ int et_attention_scores(const uint16_t *qkv_dev, int32_t n_frames, int32_t L, in
 /* ---- the projector that follows the encoder (Sec. 3.1: vision encoder -> projector -> language
  *      model) -------------------------------------------------------------------------------------
  * A two-layer MLP on the kept tokens, out = W2 * gelu_tanh(W1 * x + b1) + b2, so that the time of
- * "encoder + visual token processing" can be taken as one figure when the selection sits after the
+ * encoder plus everything done to the visual tokens can be taken as one figure when the selection sits after the
  * encoder (merge_layer = n_layers, where the paper places Stage II).  The paper does not describe the
  * projector; the two-layer form and the GELU are this library's reading, the widths are arguments.
  * Weights: HOST float32, out-features major (w1 [d_hidden, d_in], w2 [d_out, d_hidden]), converted once

@@ -203,7 +203,7 @@ def keep_count(L, keep_ratio):
 
 def topk_positions(z, k):
     """Eq. 4 with a total order: rank by (score descending, position ascending), keep the
-    first k, return those positions in ascending order (Eq. 7's "initial order").
+    first k, return those positions in ascending order (the order Eq. 7 restores).
 
     The ranking is decided on float32 scores (the precision the kernel ranks in);
     NaN ranks below everything.

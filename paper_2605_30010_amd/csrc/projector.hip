@@ -1,6 +1,6 @@
 // The vision-language projector that follows the encoder in the pipeline of Sec. 3.1 (vision encoder ->
 // projector -> language model): a two-layer MLP on the kept tokens, out = W2 gelu(W1 x + b1) + b2.  It
-// exists here so that "encoder + visual token processing" can be timed as one figure when the selection
+// exists here so that the encoder plus everything done to the visual tokens can be timed as one figure when the selection
 // sits after the encoder (Stage II's position in the paper); it runs on the same GEMM kernel as the
 // encoder's MLP.
 #include <math.h>
