@@ -15,13 +15,16 @@ Beside the headline (frames/s of the 32-frame clip, merge layer 8, keep 0.5) the
                 8-frame and the 64-frame clip (same encoder weights: only shapes matter for timing)
   merge_stage_c5  the compression stage alone on a [64, 729, 1152] tensor that starts cold in HBM
   paper_policy  the paper's own layout (Stage I at layers 6 / 14 / 20, Stage II after the encoder)
+  power         board power, shader clock and junction temperature while the headline step runs back to back
   cpu_baseline  the oracle on the same clip on the host cores
 With --workload c5_merge_only the compression stage alone is the step and its GB/s the value.
 """
 import argparse
+import glob
 import json
 import os
 import sys
+import threading
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
@@ -138,6 +141,80 @@ def cpu_baseline_stage(x_bits, tau, keep):
             "kind": "oracle", "sample": "the whole [%d, %d, %d] tensor, float64 numpy oracle, %.1f s" % (T, L, D, dt)}
 
 
+class PowerSampler(threading.Thread):
+    """Board power, shader clock and junction temperature read from the amdgpu driver's sysfs files every 20 ms
+    (power1_input in microwatts, the starred line of pp_dpm_sclk, temp2_input in millidegrees)."""
+
+    def __init__(self, period=0.02):
+        super().__init__(daemon=True)
+        self.period, self.stop_flag, self.rows = period, False, []
+        self.dev = self.hwmon = None
+        for d in sorted(glob.glob("/sys/class/drm/card*/device")):
+            h = glob.glob(os.path.join(d, "hwmon/hwmon*/power1_input"))
+            if h:
+                self.dev, self.hwmon = d, os.path.dirname(h[0])
+                break
+
+    @staticmethod
+    def _read(path):
+        try:
+            with open(path) as f:
+                return f.read()
+        except OSError:
+            return ""
+
+    def available(self):
+        return self.hwmon is not None and self._read(os.path.join(self.hwmon, "power1_input")).strip() != ""
+
+    def cap_w(self):
+        v = self._read(os.path.join(self.hwmon, "power1_cap")).strip()
+        return float(v) / 1e6 if v else None
+
+    def sample(self):
+        p = self._read(os.path.join(self.hwmon, "power1_input")).strip()
+        t = self._read(os.path.join(self.hwmon, "temp2_input")).strip()
+        clk = None
+        for ln in self._read(os.path.join(self.dev, "pp_dpm_sclk")).splitlines():
+            if "*" in ln:
+                clk = float(ln.split(":")[1].lower().replace("mhz", "").replace("*", "").strip())
+        return (time.perf_counter(), float(p) / 1e6 if p else None, clk, float(t) / 1e3 if t else None)
+
+    def run(self):
+        while not self.stop_flag:
+            self.rows.append(self.sample())
+            time.sleep(self.period)
+
+
+def power_under_load(fn, torch, seconds, settle=0.7):
+    """Runs fn back to back for `seconds` and returns the mean board power / shader clock over the samples taken
+    after the first `settle` seconds (the driver's power reading is itself an average over a short window)."""
+    s = PowerSampler()
+    if not s.available():
+        return None
+    fn()
+    torch.cuda.synchronize()
+    s.start()
+    t0 = time.perf_counter()
+    n = 0
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(10):
+            fn()
+        n += 10
+        torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    s.stop_flag = True
+    s.join()
+    rows = [r for r in s.rows if r[0] - t0 >= settle and r[1] is not None]
+    if not rows:
+        return None
+    mean = lambda v: sum(v) / len(v)
+    clk = [r[2] for r in rows if r[2] is not None]
+    tj = [r[3] for r in rows if r[3] is not None]
+    return {"avg_w": round(mean([r[1] for r in rows]), 1), "max_w": round(max(r[1] for r in rows), 1),
+            "sclk_mhz": round(mean(clk), 0) if clk else None, "junction_c": round(mean(tj), 1) if tj else None,
+            "samples": len(rows), "us_per_call": round(1e6 * dt / n, 1)}
+
+
 def time_steps(fn, steps, warmup, torch):
     for _ in range(warmup):
         out = fn()
@@ -228,6 +305,9 @@ def main():
                     help="skip the extra timing of the paper's own configuration (reported beside the headline)")
     ap.add_argument("--no-sweep", action="store_true", help="skip the other merge layers / keep ratios / clip lengths")
     ap.add_argument("--no-merge-microbench", action="store_true", help="skip the compression stage on its own")
+    ap.add_argument("--no-power", action="store_true", help="skip the board power / clock reading under load")
+    ap.add_argument("--power-kernels", action="store_true",
+                    help="also read power / clock under the MLP GEMM pair and under attention run alone")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 256 MiB device copy first (reference for scaling "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -240,6 +320,8 @@ def main():
     import paper_2605_30010_amd as et
     from et_inputs import build_workload
 
+    idle_sampler = PowerSampler()
+    idle_w = idle_sampler.sample()[1] if idle_sampler.available() else None      # before anything runs on the device
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
 
@@ -330,6 +412,38 @@ def main():
                                   "gbs": round(sb / (stage_ms / stage_cnt * 1e-3) / 1e9, 1)}
         kernels["merge_stage"]["hbm_frac"] = round(kernels["merge_stage"]["gbs"] / PEAK_HBM_GBS, 4)
 
+    # Board power and shader clock while the headline step runs back to back (sysfs; the published peaks assume
+    # 2.4 GHz, the clock the chip actually holds under this load is what the roofline fractions run against).
+    power = None
+    if not args.no_power:
+        ps = PowerSampler()
+        if ps.available():
+            power = {"cap_w": ps.cap_w(), "idle_w": idle_w, "peak_clock_mhz": 2400,
+                     "whole_clip": power_under_load(lambda: enc.encode(frames, m, tau, keep, stream=stream), torch, 2.5)}
+            if args.power_kernels:
+                rngw = np.random.default_rng(11)
+                mlp = et.Projector(rngw.standard_normal((shape.d_mlp, shape.d_model), dtype=np.float32) * 0.02,
+                                   np.zeros(shape.d_mlp, np.float32),
+                                   rngw.standard_normal((shape.d_model, shape.d_mlp), dtype=np.float32) * 0.02,
+                                   np.zeros(shape.d_model, np.float32))
+                rows_all = T * shape.tokens_per_frame
+                for name, rows in (("mlp_gemm_pair@all", rows_all), ("mlp_gemm_pair@kept", max(n_tokens, 1))):
+                    xin = torch.randn((rows, shape.d_model), device=dev).to(torch.bfloat16)
+                    xout = torch.empty_like(xin)
+                    e = power_under_load(lambda: mlp.project(xin, out=xout, stream=stream), torch, 2.0)
+                    if e:
+                        e["tflops"] = round(4.0 * rows * shape.d_mlp * shape.d_model / e["us_per_call"] / 1e6, 1)
+                    power[name] = e
+                mlp.close()
+                L_ = shape.tokens_per_frame
+                qkv = torch.randn((rows_all, 3 * shape.d_model), device=dev).to(torch.bfloat16)
+                hd = shape.d_model // shape.n_heads
+                e = power_under_load(lambda: et.et_attention_uniform(qkv, T, L_, shape.n_heads, hd, stream=stream), torch, 2.0)
+                if e:
+                    e["tflops"] = round(4.0 * T * shape.n_heads * L_ * L_ * hd / e["us_per_call"] / 1e6, 1)
+                power["attention@all"] = e
+                del qkv
+
     # Extra, not the headline: the paper's own layout (Table 8 / Alg. 1-2) on the same clip - Stage I after
     # blocks 6, 14, 20 with EMA segmentation and the weighted middle-pair merge, Stage II once on the encoder
     # output (decoupled top-k / local windows, overall retention 20 %, attention-received scores).
@@ -412,6 +526,7 @@ def main():
         "effective_tflops": round(total_flops / (ms_per_step * 1e-3) / 1e12, 1),
         "roofline": roofline,
         "kernels": kernels,
+        "power": power,
         "paper_policy": paper,
         "sweep": sweep,
     }
