@@ -191,7 +191,10 @@ def _assert_stage_equal(r, ref, exact_tokens=False):
 
 
 @pytest.mark.parametrize("T,L,D,keep,mean_len", [(12, 100, 256, 0.3, 3), (16, 729, 1152, 0.5, 4),
-                                                 (33, 64, 64, 0.25, 5), (70, 40, 128, 0.6, 6)])
+                                                 (33, 64, 64, 0.25, 5), (70, 40, 128, 0.6, 6),
+                                                 # long clips (many pairs per workgroup of the mean / scan launch)
+                                                 (1025, 16, 64, 0.5, 6), (1100, 12, 64, 0.5, 6),
+                                                 (300, 400, 64, 0.25, 8)])
 def test_merge_select_matches_oracle(T, L, D, keep, mean_len):
     tau = 0.9
     for variant in range(20):                     # re-seed until the decision margins hold
