@@ -122,7 +122,7 @@ def _check_topk(z32, k):
 
 def test_topk_matches_oracle_bit_exactly():
     rng = np.random.default_rng(1)
-    for n_rows, L in [(7, 729), (3, 1000), (2, 64), (1, 1), (5, 4097), (4, 255), (4, 257)]:
+    for n_rows, L in [(7, 729), (3, 1000), (2, 64), (1, 1), (5, 4097), (4, 255), (4, 257), (2, 15360)]:
         z = (rng.random((n_rows, L)) * 1000).astype(np.float32)
         for k in sorted({1, max(1, L // 4), max(1, L // 2), L}):
             _check_topk(z, k)
@@ -139,6 +139,13 @@ def test_topk_matches_oracle_bit_exactly():
     z[1, 100:300] = np.float32(1.0) + np.arange(200, dtype=np.float32) * np.float32(2 ** -20)
     for k in (1, 2, 100, 243, 244, 364, 728, 729):
         _check_topk(z, k)
+
+
+def test_topk_rejects_frames_longer_than_its_limit():
+    z = torch.zeros((1, 15361), dtype=torch.float32, device="cuda")
+    with pytest.raises(et.EtError) as e:
+        et.et_topk_select(z, 4)
+    assert e.value.code == -5 and "15360" in str(e.value)
 
 
 def test_topk_hand_cases():
@@ -194,7 +201,10 @@ def _assert_stage_equal(r, ref, exact_tokens=False):
                                                  (33, 64, 64, 0.25, 5), (70, 40, 128, 0.6, 6),
                                                  # long clips (many pairs per workgroup of the mean / scan launch)
                                                  (1025, 16, 64, 0.5, 6), (1100, 12, 64, 0.5, 6),
-                                                 (300, 400, 64, 0.25, 8)])
+                                                 (300, 400, 64, 0.25, 8),
+                                                 # frames longer than the fused selection + gather launch holds:
+                                                 # selection and gather as launches of their own
+                                                 (3, 8000, 64, 0.1, 2)])
 def test_merge_select_matches_oracle(T, L, D, keep, mean_len):
     tau = 0.9
     for variant in range(20):                     # re-seed until the decision margins hold
