@@ -1013,18 +1013,30 @@ int launch_gemm(const GemmArgs &g, hipStream_t s, int force_cfg) {
   return rc;
 }
 
-// Pulls a buffer through the cache hierarchy (weight warm-up of the short blocks): every lane reads
-// 16-byte pieces; the XOR of everything is kept alive by a store that never happens.
-__global__ __launch_bounds__(256) void touch_kernel(const uint4 *__restrict__ p, size_t n16, uint32_t *sink) {
+// Pulls up to four buffers through the cache hierarchy in one launch (weight warm-up of the short
+// blocks): every lane reads 16-byte pieces; the XOR of everything is kept alive by a store that never
+// happens.
+struct TouchList {
+  const uint4 *p[4];
+  size_t n16[4];
+};
+__global__ __launch_bounds__(256) void touch_kernel(TouchList t, uint32_t *sink) {
   uint32_t x = 0;
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x) {
-    const uint4 v = p[i];
-    x ^= v.x ^ v.y ^ v.z ^ v.w;
-  }
+#pragma unroll
+  for (int b = 0; b < 4; ++b)
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < t.n16[b]; i += (size_t)gridDim.x * blockDim.x) {
+      const uint4 v = t.p[b][i];
+      x ^= v.x ^ v.y ^ v.z ^ v.w;
+    }
   if (x == 0x9E3779B9u && sink) *sink = x;
 }
-int launch_touch(const void *p, size_t bytes, hipStream_t s) {
-  hipLaunchKernelGGL(touch_kernel, dim3(512), dim3(256), 0, s, static_cast<const uint4 *>(p), bytes / 16, (uint32_t *)nullptr);
+int launch_touch(const void *const *p, const size_t *bytes, int n, hipStream_t s) {
+  TouchList t{};
+  for (int b = 0; b < 4; ++b) {
+    t.p[b] = b < n ? static_cast<const uint4 *>(p[b]) : nullptr;
+    t.n16[b] = b < n ? bytes[b] / 16 : 0;
+  }
+  hipLaunchKernelGGL(touch_kernel, dim3(512), dim3(256), 0, s, t, (uint32_t *)nullptr);
   ET_LAUNCH_CHECK();
   return ET_OK;
 }

@@ -191,11 +191,11 @@ static int warm_weights(et_encoder *e, int li, hipStream_t s) {
   const size_t D = e->D, Dn = round_up(e->D, 256);
   ET_HIP(hipEventRecord(e->warm_go, s));
   ET_HIP(hipStreamWaitEvent(e->warm_stream, e->warm_go, 0));
+  const void *const mats[4] = {lw.wqkv, lw.wo, lw.w1, lw.w2};
+  const size_t bytes[4] = {(size_t)round_up(3 * e->D, 256) * D * 2, Dn * D * 2, (size_t)round_up(e->Mhp, 256) * D * 2,
+                           Dn * e->Mhp * 2};
   int rc;
-  if ((rc = launch_touch(lw.wqkv, (size_t)round_up(3 * e->D, 256) * D * 2, e->warm_stream))) return rc;
-  if ((rc = launch_touch(lw.wo, Dn * D * 2, e->warm_stream))) return rc;
-  if ((rc = launch_touch(lw.w1, (size_t)round_up(e->Mhp, 256) * D * 2, e->warm_stream))) return rc;
-  if ((rc = launch_touch(lw.w2, Dn * e->Mhp * 2, e->warm_stream))) return rc;
+  if ((rc = launch_touch(mats, bytes, 4, e->warm_stream))) return rc;
   return ET_OK;
 }
 

@@ -231,7 +231,7 @@ int gemm_config_count();
 int launch_attention(const uint16_t *qkv, const int32_t *cu, int n_frames, int max_len, int n_heads,
                      int head_dim, uint16_t *out, hipStream_t s);
 bool head_dim_supported(int hd);
-int launch_touch(const void *p, size_t bytes, hipStream_t s);
+int launch_touch(const void *const *p, const size_t *bytes, int n, hipStream_t s);   // n <= 4 buffers, one launch
 // Equal-length frames (frame f = rows f * len .. f * len + len - 1).
 int launch_attention_uniform(const uint16_t *qkv, int n_frames, int len, int n_heads, int head_dim,
                              uint16_t *out, hipStream_t s);
