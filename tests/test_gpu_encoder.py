@@ -162,6 +162,46 @@ def test_ragged_clip_lengths_and_merge_at_the_ends(tiny):
     enc.close()
 
 
+def test_two_encoders_on_two_streams_from_two_host_threads(tiny):
+    """Encoders share no state: two of them driven at the same time, each from a host thread and a
+    stream of its own, give what each gives alone (bit for bit)."""
+    import threading
+    w, frames = tiny
+    clips = [frames, make_clip(TINY, [3, 1, 4], 5, base="uniform", sigma=0.02)]
+    settings = [(2, 0.9, 0.5), (1, 0.9, 0.3)]
+    alone = []
+    for clip, (m, tau, keep) in zip(clips, settings):
+        enc = et.Encoder(TINY, w, 8)
+        alone.append(_encode(enc, clip, m, tau, keep))
+        enc.close()
+    results, errors = [None, None], []
+
+    def worker(i):
+        try:
+            enc = et.Encoder(TINY, w, 8)
+            stream = torch.cuda.Stream()
+            x = torch.from_numpy(clips[i]).cuda()
+            torch.cuda.synchronize()
+            m, tau, keep = settings[i]
+            for _ in range(25):
+                r = enc.encode(x, m, tau, keep, stream=stream)
+                stream.synchronize()
+                for key in ("tokens", "kept_idx", "seg_start", "cu_tokens"):
+                    assert torch.equal(r[key], alone[i][key]), key
+            results[i] = True
+            enc.close()
+        except Exception as e:      # noqa: BLE001 - reported by the parent thread
+            errors.append(repr(e))
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(120)
+    assert not errors, errors
+    assert results == [True, True]
+
+
 @pytest.fixture(scope="module")
 def siglip8():
     rec = build_workload("c2_siglip_t8")
