@@ -111,7 +111,7 @@ def test_ema_reduces_to_plain_threshold_and_smooths():
     seg, s_hat = O.ema_segment_starts(np.array([0.95, 0.97, 0.5, 0.6]), 0.9, 0.8, 5)
     np.testing.assert_allclose(s_hat, [0.95, 0.968, 0.5468, 0.6], atol=1e-12)
     assert seg.tolist() == [0, 3, 4, 5]          # the recursion restarts after the break at frame 3
-    # smoothing can keep a segment together across one dip (alg1_cases line 6) and NaN breaks
+    # smoothing can keep a segment together across one dip (the alpha = 0.5 case of the golden file) and NaN breaks
     assert O.ema_segment_starts(np.array([0.99, np.nan, 0.99]), 0.9, 0.5, 4)[0].tolist() == [0, 2, 4]
 
 
