@@ -151,6 +151,47 @@ __global__ __launch_bounds__(256) void im2col_kernel(const float *__restrict__ f
   *reinterpret_cast<uint4 *>(out + row * Kpad + ch * 8) = o;
 }
 
+// The same through LDS, one workgroup per (frame, row of patches): the C * P image rows of the stripe
+// are read as whole rows (float4, coalesced), kept in LDS as bf16, and the stripe's GX output rows are
+// written as whole 16-byte chunks - both sides of the copy are contiguous, where the kernel above reads
+// P-pixel runs.  Needs W % 4 == 0, 16-byte aligned frames and C * P * W * 2 bytes of LDS.
+__global__ __launch_bounds__(256) void im2col_stripe_kernel(const float *__restrict__ frames, int C, int H, int W, int P,
+                                                            int GX, int GY, int Kreal, int Kpad,
+                                                            uint16_t *__restrict__ out) {
+  extern __shared__ __align__(16) uint16_t stripe[];           // [C * P][W] bf16
+  const int t = blockIdx.x / GY, gy = blockIdx.x % GY;
+  const int w4 = W / 4, n4 = C * P * w4;
+  for (int i = threadIdx.x; i < n4; i += 256) {
+    const int r = i / w4, x4 = i % w4, c = r / P, py = r % P;
+    const float4 v = *reinterpret_cast<const float4 *>(frames + (((size_t)t * C + c) * H + (gy * P + py)) * W + x4 * 4);
+    uint2 o;
+    o.x = cvt_pk_bf16(v.x, v.y);
+    o.y = cvt_pk_bf16(v.z, v.w);
+    *reinterpret_cast<uint2 *>(stripe + r * W + x4 * 4) = o;
+  }
+  __syncthreads();
+  const int chunks = Kpad / 8;
+  uint16_t *orow = out + ((size_t)t * GY + gy) * GX * Kpad;
+  for (int i = threadIdx.x; i < GX * chunks; i += 256) {
+    const int gx = i / chunks, ch = i % chunks;
+    uint16_t v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int kk = ch * 8 + e;
+      uint16_t val = 0;
+      if (kk < Kreal) {
+        const int r = kk / P, px = kk % P;                       // r = c * P + py
+        val = stripe[r * W + gx * P + px];
+      }
+      v[e] = val;
+    }
+    uint4 o;
+    o.x = v[0] | ((uint32_t)v[1] << 16); o.y = v[2] | ((uint32_t)v[3] << 16);
+    o.z = v[4] | ((uint32_t)v[5] << 16); o.w = v[6] | ((uint32_t)v[7] << 16);
+    *reinterpret_cast<uint4 *>(orow + (size_t)gx * Kpad + ch * 8) = o;
+  }
+}
+
 // ---------------------------------------------------------------------------------------
 // GEMM  C[m, n] = sum_k A[m, k] W[n, k] + bias[n]  (+ epilogue), bf16 operands, fp32 accumulate.
 // Both operands are k-contiguous, so both feed MFMA as 16-byte vectors straight from LDS.
@@ -915,6 +956,13 @@ int launch_rowstats(const uint16_t *x, float eps, int rows, int D, float *rstd, 
 int launch_im2col(const float *frames, int T, int C, int H, int W, int P, int Kpad, uint16_t *out,
                   hipStream_t s) {
   const int GX = W / P, GY = H / P, L = GX * GY;
+  const size_t stripe_bytes = (size_t)C * P * W * sizeof(uint16_t);
+  if (W % 4 == 0 && reinterpret_cast<uintptr_t>(frames) % 16 == 0 && stripe_bytes <= 64 * 1024) {
+    hipLaunchKernelGGL(im2col_stripe_kernel, dim3((unsigned)(T * GY)), dim3(256), stripe_bytes, s, frames, C, H, W, P,
+                       GX, GY, C * P * P, Kpad, out);
+    ET_LAUNCH_CHECK();
+    return ET_OK;
+  }
   const size_t n = (size_t)T * L * (Kpad / 8);
   hipLaunchKernelGGL(im2col_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, frames, T, C, H, W, P,
                      GX, L, C * P * P, Kpad, out);

@@ -162,6 +162,23 @@ def test_ragged_clip_lengths_and_merge_at_the_ends(tiny):
     enc.close()
 
 
+def test_both_patch_extraction_kernels_agree_bit_for_bit(tiny):
+    """Frames that are not 16-byte aligned take the element-wise patch extraction, aligned ones the one that goes
+    through LDS a row of patches at a time: same patches, so the whole encoder output is identical."""
+    w, frames = tiny
+    enc = et.Encoder(TINY, w, 8)
+    x = torch.from_numpy(frames).cuda()
+    assert x.data_ptr() % 16 == 0
+    shifted = torch.empty(x.numel() + 1, dtype=torch.float32, device="cuda")[1:].view_as(x)
+    shifted.copy_(x)
+    assert shifted.data_ptr() % 16 == 4
+    a = {k: (v.clone() if isinstance(v, torch.Tensor) else v) for k, v in enc.encode(x, 2, 0.9, 0.5).items()}
+    b = enc.encode(shifted, 2, 0.9, 0.5)
+    for key in ("tokens", "kept_idx", "seg_start", "cu_tokens", "frame_sim"):
+        assert torch.equal(a[key], b[key]), key
+    enc.close()
+
+
 def test_two_encoders_on_two_streams_from_two_host_threads(tiny):
     """Encoders share no state: two of them driven at the same time, each from a host thread and a
     stream of its own, give what each gives alone (bit for bit)."""
