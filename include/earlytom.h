@@ -18,7 +18,8 @@
  *     message of the last failure on the calling thread is available from et_last_error().
  *     Arguments are validated before any device work is issued.
  *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  All
- *     work is enqueued on it.  One encoder must be used by one stream at a time.
+ *     work is enqueued on it.  One encoder must be used by one stream at a time; different
+ *     encoders share no state and may be driven at once from different host threads and streams.
  *   - No exceptions cross this boundary.
  */
 #ifndef EARLYTOM_H
